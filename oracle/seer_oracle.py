@@ -1,0 +1,169 @@
+"""CPU oracle for the Seer SpMV hot path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+module; the product library never does, and this module never imports the
+product.  It is deliberately plain and slow.
+
+What it defines
+  * spmv        -- y = A x by the inner-product definition (Sec. IV, Table II:
+                   every schedule computes the same SpMV), fp64, via the C row
+                   loop in spmv_oracle.c; spmv_python is the same loop in Python
+                   for tiny inputs.
+  * features    -- the statistics gathered from the CSR offsets (Sec. IV and
+                   IV-A: max / min / variance / mean of the row density, where a
+                   row's density is its nonzero count over the number of columns;
+                   Table III's rows, nnz, Most, Least, Avg, Var), plus the
+                   row-length forms of the same statistics and the fraction of
+                   empty rows.
+  * select      -- decision-tree inference (Sec. III-B: nested if/else over the
+                   feature vector, returning an integer class index).
+
+Readings where the paper is silent (all listed again in the design document):
+  * variance is the population variance (divide by rows);
+  * integer statistics are exact; every derived float is computed in fp64 from
+    exact integers with one division, then rounded once to fp32:
+        mean_len   = fl32( fl64(nnz) / fl64(rows) )
+        var_len    = fl32( fl64(rows*sum_sq - nnz^2) / fl64(rows^2) )
+        empty_frac = fl32( fl64(empty) / fl64(rows) )
+        densities  = the same fp64 quotient divided once more by fl64(cols)
+                     (variance: by fl64(cols)*fl64(cols)), then rounded to fp32
+    with fl64(int) the correctly rounded int->double conversion;
+  * min is the plain minimum (0 if any row is empty);
+  * rows == 0: every statistic and derived value is 0; cols == 0: densities 0;
+  * tree split convention is scikit-learn's: go left iff x[feature] <= threshold,
+    features fp32, thresholds fp64, comparison in fp64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+NUM_FEATURES = 12
+FEATURE_NAMES = (
+    "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
+    "mean_density", "max_density", "min_density", "var_density",
+)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile spmv_oracle.c with gcc (-O2, no OpenMP, no fast-math)."""
+    src = os.path.join(_HERE, "spmv_oracle.c")
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
+        subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-o", _SO, src, "-lm"])
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_SO)
+        p = ctypes.c_void_p
+        lib.oracle_spmv_f64.argtypes = [ctypes.c_int64, p, p, p, p, p, p]
+        lib.oracle_spmv_f64.restype = None
+        lib.oracle_spmv_f64_nobound.argtypes = [ctypes.c_int64, p, p, p, p, p]
+        lib.oracle_spmv_f64_nobound.restype = None
+        _lib = lib
+    return _lib
+
+
+def _check_csr(rows, row_ptr, col_idx, values, x):
+    assert row_ptr.dtype == np.int32 and row_ptr.flags.c_contiguous and row_ptr.shape == (rows + 1,)
+    nnz = int(row_ptr[rows]) if rows >= 0 else 0
+    assert col_idx.dtype == np.int32 and col_idx.flags.c_contiguous and col_idx.size >= nnz
+    assert values.dtype == np.float32 and values.flags.c_contiguous and values.size >= nnz
+    assert x.dtype == np.float32 and x.flags.c_contiguous
+    if nnz:
+        assert int(col_idx[:nnz].min()) >= 0 and int(col_idx[:nnz].max()) < x.size
+
+
+def spmv(rows, row_ptr, col_idx, values, x, want_bound: bool = True):
+    """O1.  Returns (y_ref fp64 [rows], bound fp64 [rows] or None)."""
+    _check_csr(rows, row_ptr, col_idx, values, x)
+    y = np.empty(rows, dtype=np.float64)
+    lib = _load()
+    ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    if want_bound:
+        b = np.empty(rows, dtype=np.float64)
+        lib.oracle_spmv_f64(rows, ptr(row_ptr), ptr(col_idx), ptr(values), ptr(x), ptr(y), ptr(b))
+        return y, b
+    lib.oracle_spmv_f64_nobound(rows, ptr(row_ptr), ptr(col_idx), ptr(values), ptr(x), ptr(y))
+    return y, None
+
+
+def spmv_python(rows, row_ptr, col_idx, values, x):
+    """O1 again as a pure-Python loop (Python floats are fp64); tiny inputs only."""
+    y = [0.0] * rows
+    bound = [0.0] * rows
+    for i in range(rows):
+        s = 0.0
+        b = 0.0
+        for k in range(int(row_ptr[i]), int(row_ptr[i + 1])):
+            p = float(values[k]) * float(x[int(col_idx[k])])
+            s += p
+            b += abs(p)
+        y[i] = s
+        bound[i] = b
+    return np.array(y, dtype=np.float64), np.array(bound, dtype=np.float64)
+
+
+def _f32(v: float) -> np.float32:
+    return np.float32(np.float64(v))
+
+
+def features(rows: int, cols: int, row_ptr) -> dict:
+    """O2.  One pass over the CSR offsets; exact integers, then the derived vector."""
+    out = dict(rows=int(rows), cols=int(cols), nnz=0, max_len=0, min_len=0,
+               empty_rows=0, sum_sq_len=0)
+    f = np.zeros(NUM_FEATURES, dtype=np.float32)
+    if rows > 0:
+        rp = np.asarray(row_ptr[: rows + 1], dtype=np.int64)
+        lens = rp[1:] - rp[:-1]
+        nnz = int(rp[rows] - rp[0])
+        max_len = int(lens.max())
+        min_len = int(lens.min())
+        empty = int(np.count_nonzero(lens == 0))
+        # len < 2^31 and sum(len) < 2^31, so sum(len^2) <= max*nnz < 2^62: exact in uint64
+        sum_sq = int(np.sum(lens.astype(np.uint64) ** 2, dtype=np.uint64))
+        out.update(nnz=nnz, max_len=max_len, min_len=min_len, empty_rows=empty, sum_sq_len=sum_sq)
+
+        R = float(rows)                       # exact for rows < 2^53
+        mean64 = float(nnz) / R
+        var_num = rows * sum_sq - nnz * nnz   # Python int: exact, >= 0 (Cauchy-Schwarz)
+        var64 = float(var_num) / float(rows * rows)
+        f[0] = _f32(float(rows)); f[1] = _f32(float(cols)); f[2] = _f32(float(nnz))
+        f[3] = _f32(mean64)
+        f[4] = _f32(float(max_len))
+        f[5] = _f32(float(min_len))
+        f[6] = _f32(var64)
+        f[7] = _f32(float(empty) / R)
+        if cols > 0:
+            C = float(cols)
+            f[8] = _f32(mean64 / C)
+            f[9] = _f32(float(max_len) / C)
+            f[10] = _f32(float(min_len) / C)
+            f[11] = _f32(var64 / (C * C))
+    else:
+        f[1] = _f32(float(cols))
+    out["f"] = f
+    return out
+
+
+def select(f, feature, threshold, left, right, klass) -> int:
+    """O3.  Walk a binary decision tree stored as parallel arrays; node 0 is the
+    root; a node with feature < 0 is a leaf and returns klass[node]."""
+    n = 0
+    steps = 0
+    while int(feature[n]) >= 0:
+        n = int(left[n]) if float(np.float32(f[int(feature[n])])) <= float(threshold[n]) else int(right[n])
+        steps += 1
+        if steps > len(feature):
+            raise ValueError("tree has a cycle")
+    return int(klass[n])
