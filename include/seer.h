@@ -1,0 +1,159 @@
+/*
+ * seer.h -- C ABI of the MI355X (gfx950) SpMV schedule family, the CSR feature
+ * reduction and the decision-tree kernel selector of the Seer case study.
+ *
+ * Runtime flow (Sec. III-B, "Runtime Inference"): gather the dynamically computed
+ * features of the matrix, walk a decision tree over them to obtain a kernel index,
+ * run that SpMV kernel.  The three calls below are those three steps.
+ *
+ * General rules
+ *   - Plain C types only.  Every pointer is marked DEVICE (memory the current HIP
+ *     device can access, owned and freed by the caller) or HOST.
+ *   - The library never allocates or frees device memory.  Scratch is a caller
+ *     buffer handed in as (workspace, workspace_bytes); its contents on entry do
+ *     not matter and are undefined on return.  Required sizes come from the
+ *     *_workspace_bytes calls.  A workspace must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     device work is enqueued on it.  seer_spmv returns without waiting;
+ *     seer_features waits for its own result because it returns host values.
+ *   - Every call returns SEER_OK (0) or a negative seer_status; on error no output
+ *     is written.  Nothing throws or aborts.  Matrix contents (monotone row_ptr,
+ *     column range) are NOT validated: they are the caller's contract.
+ *   - The first call on a device allocates one 64-byte pinned host buffer per
+ *     process (result mailbox of seer_features); no other state is kept.
+ *   - Calls that use the same workspace, or seer_features calls on the same device,
+ *     must not overlap in time.
+ */
+#ifndef SEER_H
+#define SEER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SEER_OK = 0,
+    SEER_EINVAL = -1,     /* null pointer, negative size, misaligned buffer           */
+    SEER_EKERNEL = -2,    /* kernel id outside [0, seer_num_kernels())                */
+    SEER_ETREE = -3,      /* malformed tree: index out of range, cycle, bad feature   */
+    SEER_EWORKSPACE = -4, /* workspace missing, misaligned or too small               */
+    SEER_EHIP = -5        /* a HIP runtime call failed; see seer_last_hip_error()     */
+} seer_status;
+
+/* Kernel ids: the CSR rows of Table II ("load balancing schedules"), in its order. */
+enum {
+    SEER_CSR_TM = 0, /* thread mapped: one row per lane                               */
+    SEER_CSR_WM = 1, /* wavefront mapped: one row per group of 2..64 lanes of a wave  */
+    SEER_CSR_BM = 2, /* block mapped: a block of consecutive rows per workgroup,
+                        nonzeros staged through LDS                                   */
+    SEER_CSR_MP = 3, /* work oriented / merge path: equal shares of rows + nonzeros   */
+    SEER_NUM_KERNELS = 4
+};
+
+/* CSR matrix, fp32 values, int32 indices.  All pointers DEVICE, caller-owned.
+ * row_ptr[0] must be 0, row_ptr non-decreasing, row_ptr[rows] == nnz < 2^31;
+ * columns may be in any order inside a row and may repeat (repeats are summed). */
+typedef struct {
+    int32_t rows, cols, nnz;
+    const int32_t *row_ptr; /* DEVICE [rows + 1] */
+    const int32_t *col_idx; /* DEVICE [nnz]      */
+    const float *values;    /* DEVICE [nnz]      */
+} seer_csr;
+
+/* Feature vector indices.  0-2 are the "known" features of Sec. IV (rows, columns,
+ * nonzeros); 8-11 are the gathered row-density statistics named there (density of
+ * a row = its nonzero count / cols, Sec. IV-A); 3-7 are the same statistics on
+ * row lengths (Table III: Most, Least, Avg, Var) plus the fraction of empty rows. */
+enum {
+    SEER_F_ROWS = 0, SEER_F_COLS, SEER_F_NNZ,
+    SEER_F_MEAN_LEN, SEER_F_MAX_LEN, SEER_F_MIN_LEN, SEER_F_VAR_LEN, SEER_F_EMPTY_FRAC,
+    SEER_F_MEAN_DENSITY, SEER_F_MAX_DENSITY, SEER_F_MIN_DENSITY, SEER_F_VAR_DENSITY,
+    SEER_NUM_FEATURES = 12
+};
+
+/* HOST struct filled by seer_features.  Integer fields are exact.  f[] is derived
+ * from them on the host: each entry is computed in fp64 from exact integers
+ * (int -> double correctly rounded, one division; densities one further division
+ * by cols, the variance by cols*cols) and rounded once to fp32.  Variance is the
+ * population variance: (rows * sum_sq_len - nnz^2) / rows^2.  rows == 0 gives all
+ * zeros except f[SEER_F_COLS]; cols == 0 gives zero densities. */
+typedef struct {
+    int64_t rows, cols, nnz;  /* nnz = row_ptr[rows] - row_ptr[0], read on the device */
+    int64_t max_len, min_len; /* longest / shortest row (0 when rows == 0)            */
+    int64_t empty_rows;
+    uint64_t sum_sq_len;      /* sum over rows of len^2                               */
+    float f[SEER_NUM_FEATURES];
+} seer_features_t;
+
+/* Decision tree as a flat node array, HOST memory.  Node 0 is the root.  A node with
+ * feature < 0 is a leaf and yields klass.  Otherwise go to `left` iff
+ * (double)f[feature] <= threshold, else to `right` (the CART convention of the
+ * library the paper trains with, Sec. III-A). */
+typedef struct {
+    int32_t feature;
+    int32_t left, right;
+    int32_t klass;
+    double threshold;
+} seer_node;
+
+typedef struct {
+    int32_t n_nodes;
+    int32_t n_features; /* entries of f[] the tree may index; <= SEER_NUM_FEATURES     */
+    int32_t n_classes;  /* klass of every leaf must be in [0, n_classes)               */
+    const seer_node *nodes; /* HOST [n_nodes] */
+} seer_tree;
+
+/* Feature collection (Sec. IV-A: parallel kernels that loop over the CSR offsets).
+ * Reads A->row_ptr only (col_idx / values may be NULL).  Enqueues one reduction
+ * kernel on `stream`, waits for it, and fills *out.  workspace: DEVICE, at least
+ * seer_features_workspace_bytes(A->rows) bytes. */
+int seer_features(const seer_csr *A, seer_features_t *out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+size_t seer_features_workspace_bytes(int32_t rows);
+
+/* Recomputes io->f[] from the integer fields of *io by the rule stated at
+ * seer_features_t (what seer_features does after its reduction; also the way to
+ * finish integer partials that were combined elsewhere).  Rejects negative fields
+ * and min_len > max_len.  HOST only. */
+int seer_derive_features(seer_features_t *io);
+
+/* Fills out->f[] (and the three known integers) from rows, cols, nnz alone, with
+ * the gathered entries set to 0: the input of a "known features" model (Sec. III-A),
+ * which costs nothing at run time.  HOST only, no GPU work. */
+int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t *out);
+
+/* Tree inference (Sec. III-B: nested if/else over the input vector, yielding an
+ * integer index).  HOST only.  Validates the tree (SEER_ETREE) before walking. */
+int seer_select(const seer_features_t *f, const seer_tree *tree, int *kernel_id);
+
+/* y = A x with the schedule `kernel_id` (Table II).  x: DEVICE [cols], y: DEVICE
+ * [rows], overwritten (no alpha/beta); x and y must not alias.  Every kernel id is
+ * valid for every matrix and gives the same y up to fp32 summation order.
+ * rows == 0: nothing is written.  Asynchronous on `stream`.
+ * workspace: at least seer_spmv_workspace_bytes(kernel_id, rows, nnz) bytes (0 for
+ * ids 0-2, then workspace may be NULL). */
+int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y,
+              void *workspace, size_t workspace_bytes, void *stream);
+size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
+
+/* Launch-shape overrides for experiments; the defaults (value < 0) derive every
+ * launch shape from rows and nnz alone (the trivially known sizes of Sec. III-A).
+ *   "wm_lanes"  lanes per row of CSR,WM: 2, 4, 8, 16, 32 or 64
+ *   "bm_rows"   rows per workgroup of CSR,BM: 1..1024
+ *   "mp_ipt"    merge items per lane of CSR,MP: 7 or 15
+ *   "xcd_remap" 1: consecutive tiles stay on one XCD (default), 0: round-robin
+ * Unknown name: SEER_EINVAL.  A value outside the listed set selects the default. */
+int seer_set_tuning(const char *name, int value);
+
+int seer_num_kernels(void);
+const char *seer_kernel_name(int kernel_id); /* "CSR,TM" ...; NULL if out of range  */
+const char *seer_strerror(int status);
+int seer_last_hip_error(void);               /* raw hipError_t of the last SEER_EHIP */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEER_H */

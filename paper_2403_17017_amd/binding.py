@@ -1,0 +1,242 @@
+"""ctypes binding of libseer.so: argument marshalling only.
+
+Every step of the path -- feature reduction, tree walk, SpMV -- runs inside the
+library; there is no Python or PyTorch fallback.  PyTorch supplies device memory
+(``tensor.data_ptr()``) and the stream.  If the library has not been built the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libseer.so")
+
+NUM_FEATURES = 12
+NUM_KERNELS = 4
+CSR_TM, CSR_WM, CSR_BM, CSR_MP = range(4)
+FEATURE_NAMES = (
+    "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
+    "mean_density", "max_density", "min_density", "var_density",
+)
+
+
+class SeerError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {status} ({strerror(status)})")
+        self.status = status
+
+
+class seer_csr(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("cols", C.c_int32), ("nnz", C.c_int32),
+                ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("values", C.c_void_p)]
+
+
+class seer_features_t(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("nnz", C.c_int64),
+                ("max_len", C.c_int64), ("min_len", C.c_int64), ("empty_rows", C.c_int64),
+                ("sum_sq_len", C.c_uint64), ("f", C.c_float * NUM_FEATURES)]
+
+    def vector(self) -> np.ndarray:
+        return np.array(list(self.f), dtype=np.float32)
+
+    def as_dict(self) -> dict:
+        d = {k: int(getattr(self, k)) for k in
+             ("rows", "cols", "nnz", "max_len", "min_len", "empty_rows", "sum_sq_len")}
+        d["f"] = self.vector()
+        return d
+
+
+class seer_node(C.Structure):
+    _fields_ = [("feature", C.c_int32), ("left", C.c_int32), ("right", C.c_int32),
+                ("klass", C.c_int32), ("threshold", C.c_double)]
+
+
+class seer_tree(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("n_features", C.c_int32), ("n_classes", C.c_int32),
+                ("nodes", C.POINTER(seer_node))]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2403_17017_amd.build` "
+                "(there is no non-HIP code path)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32
+        L.seer_features.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_features_t), vp, sz, vp]
+        L.seer_features.restype = C.c_int
+        L.seer_features_workspace_bytes.argtypes = [i32]
+        L.seer_features_workspace_bytes.restype = sz
+        L.seer_derive_features.argtypes = [C.POINTER(seer_features_t)]
+        L.seer_derive_features.restype = C.c_int
+        L.seer_known_features.argtypes = [i32, i32, i32, C.POINTER(seer_features_t)]
+        L.seer_known_features.restype = C.c_int
+        L.seer_select.argtypes = [C.POINTER(seer_features_t), C.POINTER(seer_tree), C.POINTER(C.c_int)]
+        L.seer_select.restype = C.c_int
+        L.seer_spmv.argtypes = [C.c_int, C.POINTER(seer_csr), vp, vp, vp, sz, vp]
+        L.seer_spmv.restype = C.c_int
+        L.seer_spmv_workspace_bytes.argtypes = [C.c_int, i32, i32]
+        L.seer_spmv_workspace_bytes.restype = sz
+        L.seer_set_tuning.argtypes = [C.c_char_p, C.c_int]
+        L.seer_set_tuning.restype = C.c_int
+        L.seer_num_kernels.restype = C.c_int
+        L.seer_kernel_name.argtypes = [C.c_int]
+        L.seer_kernel_name.restype = C.c_char_p
+        L.seer_strerror.argtypes = [C.c_int]
+        L.seer_strerror.restype = C.c_char_p
+        L.seer_last_hip_error.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().seer_strerror(status).decode()
+
+
+def kernel_name(kernel_id: int) -> str:
+    s = lib().seer_kernel_name(kernel_id)
+    return s.decode() if s else "?"
+
+
+def set_tuning(name: str, value: int) -> None:
+    rc = lib().seer_set_tuning(name.encode(), int(value))
+    if rc:
+        raise SeerError(rc, f"seer_set_tuning({name})")
+
+
+@dataclass
+class DeviceCSR:
+    """CSR matrix whose three arrays are torch tensors on the GPU."""
+    rows: int
+    cols: int
+    row_ptr: "torch.Tensor"   # int32 [rows + 1]
+    col_idx: "torch.Tensor"   # int32 [nnz]
+    values: "torch.Tensor"    # float32 [nnz]
+    nnz: int = -1
+
+    def __post_init__(self):
+        import torch
+        assert self.row_ptr.dtype == torch.int32 and self.col_idx.dtype == torch.int32
+        assert self.values.dtype == torch.float32
+        assert self.row_ptr.is_contiguous() and self.col_idx.is_contiguous() and self.values.is_contiguous()
+        assert self.row_ptr.numel() == self.rows + 1
+        if self.nnz < 0:
+            self.nnz = int(self.col_idx.numel())
+        assert self.col_idx.numel() >= self.nnz and self.values.numel() >= self.nnz
+
+    @classmethod
+    def from_host(cls, A, device="cuda:0") -> "DeviceCSR":
+        import torch
+        return cls(A.rows, A.cols,
+                   torch.from_numpy(A.row_ptr).to(device),
+                   torch.from_numpy(A.col_idx).to(device),
+                   torch.from_numpy(A.values).to(device), A.nnz)
+
+    def c_struct(self) -> seer_csr:
+        return seer_csr(self.rows, self.cols, self.nnz, self.row_ptr.data_ptr(),
+                        self.col_idx.data_ptr() if self.nnz else None,
+                        self.values.data_ptr() if self.nnz else None)
+
+
+class Tree:
+    """Flat decision tree in host memory (node 0 = root, feature < 0 = leaf)."""
+
+    def __init__(self, feature, threshold, left, right, klass, n_classes=NUM_KERNELS,
+                 n_features=NUM_FEATURES):
+        n = len(feature)
+        self._nodes = (seer_node * n)()
+        for i in range(n):
+            self._nodes[i] = seer_node(int(feature[i]), int(left[i]), int(right[i]), int(klass[i]),
+                                       float(threshold[i]))
+        self.c = seer_tree(n, n_features, n_classes, C.cast(self._nodes, C.POINTER(seer_node)))
+        self.arrays = (np.asarray(feature, np.int32), np.asarray(threshold, np.float64),
+                       np.asarray(left, np.int32), np.asarray(right, np.int32), np.asarray(klass, np.int32))
+
+    @classmethod
+    def constant(cls, klass: int) -> "Tree":
+        return cls([-1], [0.0], [-1], [-1], [klass])
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(int(stream.cuda_stream)) if hasattr(stream, "cuda_stream") else C.c_void_p(int(stream))
+
+
+def features_workspace_bytes(rows: int) -> int:
+    return int(lib().seer_features_workspace_bytes(rows))
+
+
+def spmv_workspace_bytes(kernel_id: int, rows: int, nnz: int) -> int:
+    return int(lib().seer_spmv_workspace_bytes(kernel_id, rows, nnz))
+
+
+def alloc_workspace(nbytes: int, device="cuda:0"):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def seer_features(A: DeviceCSR, workspace=None, stream=None) -> seer_features_t:
+    """Gathered features of A (runs the reduction kernel and waits for it)."""
+    if workspace is None:
+        workspace = alloc_workspace(features_workspace_bytes(A.rows), A.row_ptr.device)
+    out = seer_features_t()
+    cs = A.c_struct()
+    rc = lib().seer_features(C.byref(cs), C.byref(out), workspace.data_ptr(), workspace.numel(),
+                             _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_features")
+    return out
+
+
+def seer_derive_features(rows, cols, nnz, max_len, min_len, empty_rows, sum_sq_len) -> seer_features_t:
+    io = seer_features_t(rows, cols, nnz, max_len, min_len, empty_rows, sum_sq_len)
+    rc = lib().seer_derive_features(C.byref(io))
+    if rc:
+        raise SeerError(rc, "seer_derive_features")
+    return io
+
+
+def seer_known_features(rows: int, cols: int, nnz: int) -> seer_features_t:
+    out = seer_features_t()
+    rc = lib().seer_known_features(rows, cols, nnz, C.byref(out))
+    if rc:
+        raise SeerError(rc, "seer_known_features")
+    return out
+
+
+def seer_select(f: seer_features_t, tree: Tree) -> int:
+    k = C.c_int(-1)
+    rc = lib().seer_select(C.byref(f), C.byref(tree.c), C.byref(k))
+    if rc:
+        raise SeerError(rc, "seer_select")
+    return int(k.value)
+
+
+def seer_spmv(kernel_id: int, A: DeviceCSR, x, y, workspace=None, stream=None) -> None:
+    """y = A x with schedule kernel_id; asynchronous on the stream."""
+    import torch
+    assert x.dtype == torch.float32 and y.dtype == torch.float32
+    assert x.is_contiguous() and y.is_contiguous()
+    assert x.numel() >= A.cols and y.numel() >= A.rows
+    need = spmv_workspace_bytes(kernel_id, A.rows, A.nnz) if 0 <= kernel_id < NUM_KERNELS else 0
+    if need and workspace is None:
+        workspace = alloc_workspace(need, A.row_ptr.device)
+    cs = A.c_struct()
+    rc = lib().seer_spmv(int(kernel_id), C.byref(cs), x.data_ptr(), y.data_ptr(),
+                         workspace.data_ptr() if workspace is not None else None,
+                         workspace.numel() if workspace is not None else 0, _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, f"seer_spmv(kernel {kernel_id})")

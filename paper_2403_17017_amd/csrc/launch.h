@@ -1,0 +1,43 @@
+// Host-side declarations shared by the kernel files and the C ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace seer {
+
+constexpr int kBmMaxRows = 1024;  // most rows one CSR,BM workgroup owns (LDS row_ptr segment)
+constexpr int kBmChunk = 2048;    // products staged in LDS per CSR,BM pass
+constexpr int kMpIptSmall = 7;    // merge items per thread, small problems (tile = 1792 items)
+constexpr int kMpIptLarge = 15;   // merge items per thread, large problems (tile = 3840 items)
+
+struct SpmvArgs {
+    int rows, cols, nnz;
+    const int *rp, *ci;
+    const float *va, *x;
+    float *y;
+    int remap;  // 1: tiles laid out contiguously per XCD
+};
+
+void launch_tm(const SpmvArgs &a, hipStream_t st);
+void launch_wm(const SpmvArgs &a, int lanes_per_row, hipStream_t st);
+void launch_bm(const SpmvArgs &a, int rows_per_block, bool vec, hipStream_t st);
+
+// merge path: ipt is kMpIptSmall or kMpIptLarge
+uint32_t mp_num_tiles(int rows, int nnz, int ipt);
+size_t mp_workspace_bytes(int rows, int nnz, int ipt);
+void launch_mp(const SpmvArgs &a, int ipt, bool vec, void *workspace, hipStream_t st);
+
+// feature reduction
+struct FeatureRaw {           // written by the device into pinned host memory
+    int32_t max_len, min_len;
+    int32_t first, last;      // row_ptr[0], row_ptr[rows]
+    uint64_t sum_sq, empty;
+    uint64_t seq;             // call counter echoed back (host checks it moved)
+};
+uint32_t features_num_blocks(int rows);
+size_t features_workspace_bytes(int rows);
+void launch_features(int rows, const int *rp, void *workspace, FeatureRaw *mailbox_dev,
+                     uint64_t seq, hipStream_t st);
+
+} // namespace seer

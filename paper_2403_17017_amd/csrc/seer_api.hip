@@ -1,0 +1,297 @@
+// C ABI of the library: argument checks, launch heuristics that need only the
+// trivially known sizes (rows, nnz), the host-side feature derivation and the
+// decision-tree walk.  No device memory is allocated here.
+#include "../../include/seer.h"
+#include "launch.h"
+
+#include <atomic>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+using namespace seer;
+
+namespace {
+
+std::atomic<int> g_last_hip_error{0};
+
+// Tuning hooks (negative = choose automatically).
+std::atomic<int> g_tune_wm_lanes{-1};
+std::atomic<int> g_tune_bm_rows{-1};
+std::atomic<int> g_tune_mp_ipt{-1};
+std::atomic<int> g_tune_remap{-1};
+
+std::mutex g_mailbox_mutex;
+FeatureRaw *g_mailbox_host = nullptr;   // pinned, mapped
+FeatureRaw *g_mailbox_dev = nullptr;
+uint64_t g_feature_seq = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error.store((int)e);
+    return SEER_EHIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_csr(const seer_csr *A, bool need_entries)
+{
+    if (!A) return SEER_EINVAL;
+    if (A->rows < 0 || A->cols < 0 || A->nnz < 0) return SEER_EINVAL;
+    if (!A->row_ptr) return SEER_EINVAL;
+    if (need_entries && A->nnz > 0 && (!A->col_idx || !A->values)) return SEER_EINVAL;
+    return SEER_OK;
+}
+
+int pow2_at_least(double v, int lo, int hi)
+{
+    int g = lo;
+    while (g < hi && (double)g < v) g <<= 1;
+    return g;
+}
+
+// Lanes per row for CSR,WM: the power of two nearest above the mean row length.
+int wm_lanes(int rows, int nnz)
+{
+    const int t = g_tune_wm_lanes.load();
+    if (t == 2 || t == 4 || t == 8 || t == 16 || t == 32 || t == 64) return t;
+    const double mean = rows > 0 ? (double)nnz / (double)rows : 0.0;
+    return pow2_at_least(mean, 2, 64);
+}
+
+// Rows per workgroup for CSR,BM: about one LDS chunk of nonzeros per block.
+int bm_rows(int rows, int nnz)
+{
+    const int t = g_tune_bm_rows.load();
+    if (t >= 1 && t <= kBmMaxRows) return t;
+    const double mean = rows > 0 ? (double)nnz / (double)rows : 0.0;
+    int r = kBmMaxRows;
+    while (r > 64 && (double)r * mean > (double)kBmChunk) r >>= 1;
+    return r;
+}
+
+int mp_ipt(int rows, int nnz)
+{
+    const int t = g_tune_mp_ipt.load();
+    if (t == kMpIptSmall || t == kMpIptLarge) return t;
+    // enough tiles to give each of the 256 CUs several workgroups
+    const uint64_t total = (uint64_t)rows + (uint64_t)nnz;
+    return total < (uint64_t)256 * kMpIptLarge * 256 * 16 ? kMpIptSmall : kMpIptLarge;
+}
+
+int use_remap()
+{
+    const int t = g_tune_remap.load();
+    return t < 0 ? 1 : (t != 0);
+}
+
+int ensure_mailbox()
+{
+    if (g_mailbox_host) return SEER_OK;
+    void *h = nullptr;
+    hipError_t e = hipHostMalloc(&h, 64, hipHostMallocPortable | hipHostMallocMapped);
+    if (e != hipSuccess) return hip_fail(e);
+    void *d = nullptr;
+    e = hipHostGetDevicePointer(&d, h, 0);
+    if (e != hipSuccess) {
+        (void)hipHostFree(h);
+        return hip_fail(e);
+    }
+    std::memset(h, 0, 64);
+    g_mailbox_host = static_cast<FeatureRaw *>(h);
+    g_mailbox_dev = static_cast<FeatureRaw *>(d);
+    return SEER_OK;
+}
+
+// f[] from the exact integers; every entry is one fp64 quotient rounded once to fp32.
+void derive(seer_features_t *o)
+{
+    for (int i = 0; i < SEER_NUM_FEATURES; ++i) o->f[i] = 0.0f;
+    o->f[SEER_F_COLS] = (float)(double)o->cols;
+    if (o->rows <= 0) return;
+    const double R = (double)o->rows;
+    const double mean = (double)o->nnz / R;
+    const unsigned __int128 num = (unsigned __int128)(uint64_t)o->rows * (unsigned __int128)o->sum_sq_len -
+                                  (unsigned __int128)(uint64_t)o->nnz * (unsigned __int128)(uint64_t)o->nnz;
+    const double var = (double)num / (double)((uint64_t)o->rows * (uint64_t)o->rows);
+    o->f[SEER_F_ROWS] = (float)R;
+    o->f[SEER_F_NNZ] = (float)(double)o->nnz;
+    o->f[SEER_F_MEAN_LEN] = (float)mean;
+    o->f[SEER_F_MAX_LEN] = (float)(double)o->max_len;
+    o->f[SEER_F_MIN_LEN] = (float)(double)o->min_len;
+    o->f[SEER_F_VAR_LEN] = (float)var;
+    o->f[SEER_F_EMPTY_FRAC] = (float)((double)o->empty_rows / R);
+    if (o->cols > 0) {
+        const double C = (double)o->cols;
+        o->f[SEER_F_MEAN_DENSITY] = (float)(mean / C);
+        o->f[SEER_F_MAX_DENSITY] = (float)((double)o->max_len / C);
+        o->f[SEER_F_MIN_DENSITY] = (float)((double)o->min_len / C);
+        o->f[SEER_F_VAR_DENSITY] = (float)(var / (C * C));
+    }
+}
+
+const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP"};
+
+} // namespace
+
+extern "C" {
+
+int seer_num_kernels(void) { return SEER_NUM_KERNELS; }
+
+const char *seer_kernel_name(int k) { return (k >= 0 && k < SEER_NUM_KERNELS) ? kKernelNames[k] : nullptr; }
+
+const char *seer_strerror(int s)
+{
+    switch (s) {
+    case SEER_OK: return "ok";
+    case SEER_EINVAL: return "invalid argument";
+    case SEER_EKERNEL: return "kernel id out of range";
+    case SEER_ETREE: return "malformed decision tree";
+    case SEER_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SEER_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int seer_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int seer_set_tuning(const char *name, int value)
+{
+    if (!name) return SEER_EINVAL;
+    if (!std::strcmp(name, "wm_lanes")) g_tune_wm_lanes.store(value);
+    else if (!std::strcmp(name, "bm_rows")) g_tune_bm_rows.store(value);
+    else if (!std::strcmp(name, "mp_ipt")) g_tune_mp_ipt.store(value);
+    else if (!std::strcmp(name, "xcd_remap")) g_tune_remap.store(value);
+    else return SEER_EINVAL;
+    return SEER_OK;
+}
+
+size_t seer_features_workspace_bytes(int32_t rows) { return rows < 0 ? 0 : features_workspace_bytes(rows); }
+
+size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz)
+{
+    if (kernel_id != SEER_CSR_MP || rows <= 0 || nnz < 0) return 0;
+    // the small tile gives the larger count; cover either choice
+    return mp_workspace_bytes(rows, nnz, kMpIptSmall);
+}
+
+int seer_derive_features(seer_features_t *io)
+{
+    if (!io) return SEER_EINVAL;
+    if (io->rows < 0 || io->cols < 0 || io->nnz < 0 || io->max_len < 0 || io->min_len < 0 ||
+        io->empty_rows < 0 || io->min_len > io->max_len || io->empty_rows > io->rows)
+        return SEER_EINVAL;
+    // rows * sum_sq >= nnz^2 holds for every real matrix (Cauchy-Schwarz); refuse anything else
+    if ((unsigned __int128)(uint64_t)io->rows * io->sum_sq_len <
+        (unsigned __int128)(uint64_t)io->nnz * (uint64_t)io->nnz)
+        return SEER_EINVAL;
+    derive(io);
+    return SEER_OK;
+}
+
+int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t *out)
+{
+    if (!out || rows < 0 || cols < 0 || nnz < 0) return SEER_EINVAL;
+    seer_features_t o;
+    std::memset(&o, 0, sizeof o);
+    o.rows = rows; o.cols = cols; o.nnz = nnz;
+    o.f[SEER_F_ROWS] = (float)(double)rows;
+    o.f[SEER_F_COLS] = (float)(double)cols;
+    o.f[SEER_F_NNZ] = (float)(double)nnz;
+    *out = o;
+    return SEER_OK;
+}
+
+int seer_features(const seer_csr *A, seer_features_t *out, void *workspace, size_t workspace_bytes,
+                  void *stream)
+{
+    const int rc = check_csr(A, false);
+    if (rc != SEER_OK) return rc;
+    if (!out) return SEER_EINVAL;
+    seer_features_t o;
+    std::memset(&o, 0, sizeof o);
+    o.rows = A->rows;
+    o.cols = A->cols;
+    if (A->rows > 0) {
+        if (!workspace || !aligned16(workspace) || workspace_bytes < features_workspace_bytes(A->rows))
+            return SEER_EWORKSPACE;
+        std::lock_guard<std::mutex> lock(g_mailbox_mutex);
+        const int mrc = ensure_mailbox();
+        if (mrc != SEER_OK) return mrc;
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const uint64_t seq = ++g_feature_seq;
+        launch_features(A->rows, A->row_ptr, workspace, g_mailbox_dev, seq, st);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+        e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return hip_fail(e);
+        FeatureRaw raw;
+        std::memcpy(&raw, g_mailbox_host, sizeof raw);   // written by the device; the sync ordered it
+        if (raw.seq != seq) return hip_fail(hipErrorUnknown);
+        o.nnz = (int64_t)raw.last - (int64_t)raw.first;
+        o.max_len = raw.max_len;
+        o.min_len = raw.min_len;
+        o.empty_rows = (int64_t)raw.empty;
+        o.sum_sq_len = raw.sum_sq;
+    }
+    derive(&o);
+    *out = o;
+    return SEER_OK;
+}
+
+int seer_select(const seer_features_t *f, const seer_tree *t, int *kernel_id)
+{
+    if (!f || !t || !kernel_id) return SEER_EINVAL;
+    if (!t->nodes || t->n_nodes < 1 || t->n_classes < 1 || t->n_features < 0 ||
+        t->n_features > SEER_NUM_FEATURES)
+        return SEER_ETREE;
+    for (int32_t n = 0; n < t->n_nodes; ++n) {
+        const seer_node &nd = t->nodes[n];
+        if (nd.feature < 0) {
+            if (nd.klass < 0 || nd.klass >= t->n_classes) return SEER_ETREE;
+        } else {
+            if (nd.feature >= t->n_features) return SEER_ETREE;
+            if (nd.left < 0 || nd.left >= t->n_nodes || nd.right < 0 || nd.right >= t->n_nodes) return SEER_ETREE;
+            if (nd.threshold != nd.threshold) return SEER_ETREE;   // NaN
+        }
+    }
+    int32_t n = 0;
+    for (int32_t steps = 0; steps <= t->n_nodes; ++steps) {
+        const seer_node &nd = t->nodes[n];
+        if (nd.feature < 0) {
+            *kernel_id = nd.klass;
+            return SEER_OK;
+        }
+        n = ((double)f->f[nd.feature] <= nd.threshold) ? nd.left : nd.right;
+    }
+    return SEER_ETREE;   // walked more nodes than exist: a cycle
+}
+
+int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *workspace,
+              size_t workspace_bytes, void *stream)
+{
+    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS) return SEER_EKERNEL;
+    const int rc = check_csr(A, true);
+    if (rc != SEER_OK) return rc;
+    if (A->rows == 0) return SEER_OK;
+    if (!y || (!x && A->nnz > 0)) return SEER_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap()};
+    const bool vec = aligned16(A->col_idx) && aligned16(A->values);
+    switch (kernel_id) {
+    case SEER_CSR_TM: launch_tm(a, st); break;
+    case SEER_CSR_WM: launch_wm(a, wm_lanes(A->rows, A->nnz), st); break;
+    case SEER_CSR_BM: launch_bm(a, bm_rows(A->rows, A->nnz), vec, st); break;
+    default: {
+        const int ipt = mp_ipt(A->rows, A->nnz);
+        if (!workspace || !aligned16(workspace) || workspace_bytes < mp_workspace_bytes(A->rows, A->nnz, ipt))
+            return SEER_EWORKSPACE;
+        launch_mp(a, ipt, vec, workspace, st);
+        break;
+    }
+    }
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+} // extern "C"

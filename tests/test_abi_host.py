@@ -1,0 +1,191 @@
+"""CPU-only tests of the C ABI: every declared symbol is exported, host-only calls
+(feature derivation, tree walk) agree bit for bit with the oracle, and argument
+errors are reported as status codes.  No GPU work is issued here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import paper_2403_17017_amd as S
+from paper_2403_17017_amd import binding as B
+from oracle import seer_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "seer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(seer_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_functions()
+    assert {"seer_features", "seer_select", "seer_spmv"} <= set(names)
+    L = S.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/seer.h but not exported"
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(B.seer_csr) == 40
+    assert C.sizeof(B.seer_features_t) == 7 * 8 + 12 * 4
+    assert C.sizeof(B.seer_node) == 24 and B.seer_node.threshold.offset == 16
+    assert C.sizeof(B.seer_tree) == 24
+
+
+def test_names_and_errors():
+    assert S.lib().seer_num_kernels() == 4
+    assert [S.kernel_name(k) for k in range(4)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP"]
+    assert S.lib().seer_kernel_name(4) is None
+    assert S.strerror(0) == "ok" and "tree" in S.strerror(-3)
+    with pytest.raises(S.SeerError):
+        S.set_tuning("no_such_knob", 1)
+
+
+def test_feature_names_agree():
+    assert tuple(S.FEATURE_NAMES) == tuple(O.FEATURE_NAMES) and S.NUM_FEATURES == O.NUM_FEATURES
+
+
+@settings(max_examples=300, deadline=None)
+@given(st.lists(st.integers(0, 2**20), min_size=1, max_size=200), st.integers(0, 2**31 - 1))
+def test_derivation_bit_exact_vs_oracle(lens, cols):
+    rows = len(lens)
+    rp = np.zeros(rows + 1, np.int64)
+    rp[1:] = np.cumsum(lens)
+    if rp[-1] >= 2**31:
+        return
+    want = O.features(rows, cols, rp.astype(np.int32))
+    got = S.seer_derive_features(rows, cols, want["nnz"], want["max_len"], want["min_len"],
+                                 want["empty_rows"], want["sum_sq_len"])
+    assert got.vector().tobytes() == want["f"].tobytes()
+
+
+def test_derivation_extremes():
+    # widest numerator: two rows of ~2^30
+    lens = [2**30 - 1, 2**30 - 3, 0, 1]
+    rp = np.zeros(5, np.int64)
+    rp[1:] = np.cumsum(lens)
+    want = O.features(4, 2**31 - 1, rp.astype(np.int32))
+    got = S.seer_derive_features(4, 2**31 - 1, want["nnz"], want["max_len"], want["min_len"],
+                                 want["empty_rows"], want["sum_sq_len"])
+    assert got.vector().tobytes() == want["f"].tobytes()
+    # rows == 0 and cols == 0
+    z = S.seer_derive_features(0, 9, 0, 0, 0, 0, 0)
+    assert z.vector().tobytes() == O.features(0, 9, np.zeros(1, np.int32))["f"].tobytes()
+    z = S.seer_derive_features(3, 0, 0, 0, 0, 3, 0)
+    assert z.vector().tobytes() == O.features(3, 0, np.zeros(4, np.int32))["f"].tobytes()
+    with pytest.raises(S.SeerError):
+        S.seer_derive_features(2, 2, 10, 1, 0, 0, 1)   # rows*sum_sq < nnz^2: impossible
+    with pytest.raises(S.SeerError):
+        S.seer_derive_features(-1, 2, 0, 0, 0, 0, 0)
+
+
+def test_known_features():
+    f = S.seer_known_features(1000, 2000, 30000)
+    v = f.vector()
+    assert v[0] == 1000 and v[1] == 2000 and v[2] == 30000 and np.all(v[3:] == 0)
+
+
+def random_tree(rng, n_internal, n_classes=4):
+    """Random binary tree in preorder, as parallel arrays."""
+    feat, thr, left, right, kl = [], [], [], [], []
+
+    def grow(budget):
+        me = len(feat)
+        feat.append(-1); thr.append(0.0); left.append(-1); right.append(-1); kl.append(int(rng.integers(n_classes)))
+        if budget > 0:
+            feat[me] = int(rng.integers(O.NUM_FEATURES))
+            thr[me] = float(np.float32(np.exp(rng.normal(2, 3)))) if rng.random() < 0.5 else float(np.exp(rng.normal(2, 3)))
+            kl[me] = -1
+            lb = int(rng.integers(0, budget))
+            left[me] = grow(lb)
+            right[me] = grow(budget - 1 - lb)
+        return me
+
+    grow(n_internal)
+    return feat, thr, left, right, kl
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_bit_exact_vs_oracle(seed):
+    rng = np.random.default_rng(seed)
+    arrs = random_tree(rng, n_internal=int(rng.integers(0, 40)))
+    tree = S.Tree(*arrs)
+    thr = [t for f, t in zip(arrs[0], arrs[1]) if f >= 0]
+    for _ in range(300):
+        f = B.seer_features_t()
+        vec = np.exp(rng.normal(2, 3, O.NUM_FEATURES)).astype(np.float32)
+        if thr and rng.random() < 0.5:      # sit exactly on a threshold
+            vec[int(rng.integers(O.NUM_FEATURES))] = np.float32(thr[int(rng.integers(len(thr)))])
+        for i in range(O.NUM_FEATURES):
+            f.f[i] = float(vec[i])
+        assert S.seer_select(f, tree) == O.select(vec, *arrs)
+
+
+def test_select_against_sklearn_tree():
+    from sklearn.tree import DecisionTreeClassifier
+    rng = np.random.default_rng(5)
+    X = np.exp(rng.normal(3, 3, (500, O.NUM_FEATURES))).astype(np.float32)
+    lab = (X[:, 3] > 20).astype(int) + 2 * (X[:, 6] > X[:, 3])
+    clf = DecisionTreeClassifier(criterion="gini", max_depth=6, random_state=0).fit(X, lab)
+    t = clf.tree_
+    feat = np.where(t.children_left < 0, -1, t.feature)
+    kl = clf.classes_[np.argmax(t.value[:, 0, :], axis=1)]
+    tree = S.Tree(feat, t.threshold, t.children_left, t.children_right, kl)
+    want = clf.predict(X)
+    for r, w in zip(X, want):
+        f = B.seer_features_t()
+        for i in range(O.NUM_FEATURES):
+            f.f[i] = float(r[i])
+        assert S.seer_select(f, tree) == w
+
+
+def test_malformed_trees_are_rejected():
+    f = B.seer_features_t()
+    bad = [
+        S.Tree([0, -1, -1], [1.0, 0, 0], [1, -1, -1], [7, -1, -1], [-1, 0, 1]),     # child out of range
+        S.Tree([0, 0], [1e30, 1e30], [1, 0], [1, 0], [0, 0]),                       # cycle
+        S.Tree([12, -1, -1], [1.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),    # feature index too large
+        S.Tree([-1], [0.0], [-1], [-1], [4]),                                       # class out of range
+        S.Tree([0, -1, -1], [float("nan"), 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),
+    ]
+    for t in bad:
+        with pytest.raises(S.SeerError) as ei:
+            S.seer_select(f, t)
+        assert ei.value.status == -3
+    k = C.c_int(-7)
+    assert S.lib().seer_select(None, C.byref(bad[0].c), C.byref(k)) == -1 and k.value == -7
+
+
+def test_spmv_argument_errors_without_gpu():
+    L = S.lib()
+    A = B.seer_csr(0, 0, 0, None, None, None)
+    assert L.seer_spmv(9, C.byref(A), None, None, None, 0, None) == -2
+    assert L.seer_spmv(-1, C.byref(A), None, None, None, 0, None) == -2
+    assert L.seer_spmv(0, None, None, None, None, 0, None) == -1
+    assert L.seer_spmv(0, C.byref(A), None, None, None, 0, None) == -1          # row_ptr null
+    dummy = (C.c_int32 * 4)()
+    A = B.seer_csr(-1, 0, 0, C.cast(dummy, C.c_void_p), None, None)
+    assert L.seer_spmv(0, C.byref(A), None, None, None, 0, None) == -1
+    A = B.seer_csr(0, 5, 0, C.cast(dummy, C.c_void_p), None, None)
+    assert L.seer_spmv(3, C.byref(A), None, None, None, 0, None) == 0           # rows == 0: nothing to do
+    A = B.seer_csr(3, 5, 2, C.cast(dummy, C.c_void_p), None, None)
+    assert L.seer_spmv(1, C.byref(A), None, None, None, 0, None) == -1          # nnz > 0 but no entries
+    out = B.seer_features_t()
+    assert L.seer_features(None, C.byref(out), None, 0, None) == -1
+    A = B.seer_csr(3, 5, 2, C.cast(dummy, C.c_void_p), None, None)
+    assert L.seer_features(C.byref(A), C.byref(out), None, 0, None) == -4       # no workspace
+    A0 = B.seer_csr(0, 5, 0, C.cast(dummy, C.c_void_p), None, None)
+    assert L.seer_features(C.byref(A0), C.byref(out), None, 0, None) == 0 and out.f[1] == 5.0
+
+
+def test_workspace_sizes():
+    assert S.spmv_workspace_bytes(0, 10**6, 10**7) == 0
+    assert S.spmv_workspace_bytes(2, 10**6, 10**7) == 0
+    n_tiles = -(-(10**6 + 10**7) // (256 * 7))
+    assert S.spmv_workspace_bytes(3, 10**6, 10**7) >= 8 * n_tiles
+    assert S.features_workspace_bytes(10**6) >= 32 * 1024
