@@ -1,0 +1,315 @@
+#!/usr/bin/env python3
+"""Benchmark of the Seer SpMV hot path on one MI355X.
+
+One step = one pass of the whole path over one matrix that is already resident in
+HBM: seer_features (reduction kernel + wait), seer_select (tree walk on the host),
+seer_spmv with the selected schedule.  The matrix is BASELINE config 2 (5-point
+Laplacian on a 1024 x 1024 grid).  Because that matrix (54 MB) fits the 256 MB
+last-level cache, the step rotates through enough independent copies of (A, x, y)
+to exceed 1 GiB, so every launch streams its operands from HBM.
+
+Prints ONE JSON line.  value = model bytes per step / wall time per step, with
+model bytes = 8 nnz + 4 (rows + 1) + 4 cols + 4 rows.  The `roofline` object
+prices the SpMV kernel alone (HIP events around each launch in the timed region)
+against the 8 TB/s HBM peak; `cpu_baseline` is the CPU oracle on the same matrix.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "SpMV achieved HBM GB/s (% of peak) + selected-vs-best-single-kernel speedup"
+COLD_BYTES = 1 << 30
+CAL_WORDS = 1 << 26   # the calibration copy moves 256 MiB in and 256 MiB out
+TREE_PATH = os.path.join(ROOT, "paper_2403_17017_amd", "selector_tree.json")
+
+
+def make_workload(name: str):
+    from workloads import csr_gen as G
+    if name == "fixed16_4096":
+        return G.fixed_degree()
+    if name == "laplace5_1024":
+        return G.laplacian_5pt(1024)
+    if name == "zipf1.85_2M":
+        return G.zipf_rows(s=1.85)
+    if name == "zipf1.6_2M":
+        return G.zipf_rows(s=1.6)
+    if name == "empty30_poisson4_8M":
+        return G.empty_poisson()
+    if name == "laplace5_4096":
+        return G.laplacian_5pt(4096)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def load_tree():
+    import paper_2403_17017_amd as S
+    if os.path.exists(TREE_PATH):
+        with open(TREE_PATH) as fh:
+            t = json.load(fh)
+        return S.Tree(t["feature"], t["threshold"], t["left"], t["right"], t["klass"]), t.get("note", "trained")
+    # fallback tree used only until a trained one is shipped:
+    # var_len <= 50 ? CSR,BM : CSR,MP
+    return S.Tree([6, -1, -1], [50.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 2, 3]), "hand-written default"
+
+
+def load_traffic_summary(workload, kernel):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc
+    (FETCH_SIZE and WRITE_SIZE, calibrated against the plain copy kernel).  Counters
+    cannot be collected from inside a timed run, so the figure comes from the committed
+    summary of that separate run; None if there is none for this workload and kernel."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as fh:
+        for ln in fh:
+            if ":" in ln and not ln.startswith("#"):
+                k, v = ln.split(":", 1)
+                vals[k.strip()] = v.strip()
+    if vals.get("kernel") != kernel:
+        return None
+    try:
+        return int(float(vals["hbm_bytes_per_launch"]))
+    except (KeyError, ValueError):
+        return None
+
+
+class Rotation:
+    """n independent device copies of (A, x, y, workspaces)."""
+
+    def __init__(self, A, x, n):
+        import torch
+
+        import paper_2403_17017_amd as S
+        self.sets = []
+        base = S.DeviceCSR.from_host(A)
+        xb = torch.from_numpy(x).cuda()
+        ws_bytes = max(S.spmv_workspace_bytes(3, A.rows, A.nnz), S.features_workspace_bytes(A.rows))
+        for i in range(n):
+            d = base if i == 0 else S.DeviceCSR(A.rows, A.cols, base.row_ptr.clone(), base.col_idx.clone(),
+                                                base.values.clone(), A.nnz)
+            self.sets.append((d, xb if i == 0 else xb.clone(), torch.empty(max(A.rows, 1), device="cuda:0"),
+                              S.alloc_workspace(ws_bytes)))
+        self.n = n
+
+    def __getitem__(self, i):
+        return self.sets[i % self.n]
+
+
+def time_spmv_back_to_back(kid, rot, reps, warmup):
+    """Average time per launch, launches issued back to back (events around the batch)."""
+    import torch
+
+    import paper_2403_17017_amd as S
+    for i in range(warmup):
+        d, x, y, ws = rot[i]
+        S.seer_spmv(kid, d, x, y, workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        d, x, y, ws = rot[warmup + i]
+        S.seer_spmv(kid, d, x, y, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps   # microseconds
+
+
+def time_spmv_graph(kid, rot, reps, replays=3):
+    """Average kernel time per launch with the launches replayed from one HIP graph,
+    which takes the host's launch cost out of the measurement."""
+    import torch
+
+    import paper_2403_17017_amd as S
+    for i in range(min(reps, rot.n)):
+        d, x, y, ws = rot[i]
+        S.seer_spmv(kid, d, x, y, workspace=ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(reps):
+            d, x, y, ws = rot[i]
+            S.seer_spmv(kid, d, x, y, workspace=ws)
+    g.replay()
+    torch.cuda.synchronize()
+    total = 0.0
+    for _ in range(replays):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        total += e0.elapsed_time(e1) * 1e3 / reps
+    del g
+    return total / replays
+
+
+def stream_copy_ceiling(nbytes=1 << 31, reps=10):
+    import torch
+
+    import paper_2403_17017_amd as S
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+    b = torch.empty_like(a)
+    for _ in range(2):
+        S.seer_stream_copy(b, a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        S.seer_stream_copy(b, a)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def cpu_baseline(A, x, tree, budget_s=10.0):
+    """The oracle's whole step (features, tree walk, SpMV) on the host, single thread."""
+    from oracle import seer_oracle as O
+    from workloads.csr_gen import model_bytes
+    reps, t_feat, t_spmv = 0, 0.0, 0.0
+    t_start = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        f = O.features(A.rows, A.cols, A.row_ptr)
+        O.select(f["f"], *tree.arrays)
+        t1 = time.perf_counter()
+        O.spmv(A.rows, A.row_ptr, A.col_idx, A.values, x, want_bound=False)
+        t2 = time.perf_counter()
+        t_feat += t1 - t0
+        t_spmv += t2 - t1
+        reps += 1
+        if time.perf_counter() - t_start > budget_s or reps >= 1000:
+            break
+    mb = model_bytes(A.rows, A.cols, A.nnz)
+    return {
+        "value": round(mb * reps / (t_feat + t_spmv) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"{reps} whole steps (oracle features + tree walk + fp64 C row loop) on the full "
+                  f"{A.name} matrix, {t_feat + t_spmv:.1f} s of CPU time",
+        "spmv_only_gbps": round(mb * reps / t_spmv / 1e9, 4),
+        "spmv_ms": round(t_spmv / reps * 1e3, 3), "features_select_ms": round(t_feat / reps * 1e3, 3),
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="laplace5_1024")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel table and copy ceiling")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
+                         "described in DESIGN.md but not built")
+
+    import torch
+
+    import paper_2403_17017_amd as S
+    from workloads.csr_gen import dense_vector, model_bytes
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    S.lib()   # fail now if the HIP library is missing
+    A = make_workload(args.workload)
+    x = dense_vector(A.cols, 12345)
+    mb = model_bytes(A.rows, A.cols, A.nnz)
+    n_sets = max(1, math.ceil(COLD_BYTES / mb)) + 1
+    rot = Rotation(A, x, n_sets)
+    tree, tree_note = load_tree()
+
+    def step(i, ev=None):
+        d, xd, y, ws = rot[i]
+        f = S.seer_features(d, workspace=ws)
+        kid = S.seer_select(f, tree)
+        if ev is not None:
+            ev[0].record()
+        S.seer_spmv(kid, d, xd, y, workspace=ws)
+        if ev is not None:
+            ev[1].record()
+        return kid
+
+    # one plain copy of known size first: the calibration dispatch for byte counters
+    cal_src = torch.empty(CAL_WORDS, dtype=torch.float32, device="cuda:0").normal_()
+    cal_dst = torch.empty_like(cal_src)
+    S.seer_stream_copy(cal_dst, cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
+    for i in range(args.warmup):
+        kid = step(i)
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        kid = step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    spmv_us_in_step = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in events)
+    value = mb / (ms_per_step * 1e-3) / 1e9
+
+    # Duration of the dominant kernel (the selected SpMV schedule): the same K launches
+    # on the same rotating copies, replayed from one HIP graph between two HIP events,
+    # so that the figure is kernel time and not the host's launch latency (which the
+    # per-step events above include, because the stream is idle when each step starts).
+    spmv_avg_us = time_spmv_graph(kid, rot, args.steps)
+    achieved = mb / (spmv_avg_us * 1e-6) / 1e9
+    traffic = load_traffic_summary(args.workload, S.kernel_name(kid))
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{A.name}: {A.rows}x{A.cols} CSR, nnz={A.nnz}, fp32 values, int32 indices"
+                               + (" (BASELINE config 2)" if args.workload == "laplace5_1024" else ""),
+                   "step": "seer_features + seer_select + seer_spmv(selected)",
+                   "model_bytes_per_step": mb, "cache_protocol": f"cold: rotates {n_sets} copies of (A,x,y), "
+                   f"{n_sets * mb / 2**30:.2f} GiB", "selected_kernel": S.kernel_name(kid), "tree": tree_note},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel": S.kernel_name(kid), "avg_launch_us": round(spmv_avg_us, 3),
+                     "how": f"{args.steps} launches of the selected kernel on the rotating cold copies, "
+                            "one HIP graph replay bracketed by HIP events",
+                     "algorithmic_bytes_per_launch": mb,
+                     "in_step_event_us_median": round(spmv_us_in_step[len(spmv_us_in_step) // 2], 3)},
+    }
+
+    if not args.no_extras:
+        extras = {"per_kernel_cold_us": {}, "per_kernel_warm_us": {}}
+        warm = Rotation(A, x, 1)
+        for k in range(S.NUM_KERNELS):
+            c = time_spmv_graph(k, rot, max(n_sets, 20))
+            w = time_spmv_graph(k, warm, max(n_sets, 20))
+            extras["per_kernel_cold_us"][S.kernel_name(k)] = round(c, 2)
+            extras["per_kernel_warm_us"][S.kernel_name(k)] = round(w, 2)
+        best = min(extras["per_kernel_cold_us"].values())
+        extras["best_fixed_kernel_cold_gbps"] = round(mb / (best * 1e-6) / 1e9, 1)
+        # features alone
+        t0 = time.perf_counter()
+        for i in range(50):
+            d, xd, y, ws = rot[i]
+            S.seer_features(d, workspace=ws)
+        extras["features_call_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 2)
+        del warm
+        extras["stream_copy_ceiling_gbps"] = round(stream_copy_ceiling(), 1)
+        out["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(A, x, tree)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

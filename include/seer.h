@@ -108,7 +108,9 @@ typedef struct {
 
 /* Feature collection (Sec. IV-A: parallel kernels that loop over the CSR offsets).
  * Reads A->row_ptr only (col_idx / values may be NULL).  Enqueues one reduction
- * kernel on `stream`, waits for it, and fills *out.  workspace: DEVICE, at least
+ * kernel on `stream`, waits for its result (the kernel's last act is to write it to
+ * pinned host memory; on return the stream may still be retiring that kernel), and
+ * fills *out.  workspace: DEVICE, at least
  * seer_features_workspace_bytes(A->rows) bytes. */
 int seer_features(const seer_csr *A, seer_features_t *out,
                   void *workspace, size_t workspace_bytes, void *stream);
@@ -142,11 +144,27 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
 /* Launch-shape overrides for experiments; the defaults (value < 0) derive every
  * launch shape from rows and nnz alone (the trivially known sizes of Sec. III-A).
  *   "wm_lanes"  lanes per row of CSR,WM: 2, 4, 8, 16, 32 or 64
- *   "bm_rows"   rows per workgroup of CSR,BM: 1..1024
+ *   "bm_rows"   rows per workgroup of CSR,BM: 1..2048
+ *   "bm_chunk"  products staged in LDS per pass of CSR,BM: 2048 or 4096
  *   "mp_ipt"    merge items per lane of CSR,MP: 7 or 15
  *   "xcd_remap" 1: consecutive tiles stay on one XCD (default), 0: round-robin
+ *   "nt"        1: CSR,BM / CSR,MP load the matrix streams with the non-temporal
+ *               hint (default), 0: plain loads
+ *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise
+ *               (default) it first watches its pinned result word for up to 2 ms
  * Unknown name: SEER_EINVAL.  A value outside the listed set selects the default. */
 int seer_set_tuning(const char *name, int value);
+
+/* Measurement aid, not part of the method: dst[i] = src[i] for n 4-byte words with
+ * 16-byte accesses (dst, src DEVICE, 16-byte aligned, non-overlapping).  A kernel of
+ * exactly known traffic (4n bytes read, 4n written) against which hardware byte
+ * counters are calibrated and the attainable streaming bandwidth is measured. */
+int seer_stream_copy(void *dst, const void *src, size_t n_words, void *stream);
+
+/* Measurement aid: reads n 4-byte words of src (DEVICE, 16-byte aligned) and adds a
+ * checksum into out64 (DEVICE, 64 uint32 words, caller-zeroed or not): a read-only
+ * stream of exactly 4n bytes, the access pattern an SpMV mostly is. */
+int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream);
 
 int seer_num_kernels(void);
 const char *seer_kernel_name(int kernel_id); /* "CSR,TM" ...; NULL if out of range  */

@@ -90,6 +90,10 @@ def lib():
         L.seer_spmv_workspace_bytes.restype = sz
         L.seer_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.seer_set_tuning.restype = C.c_int
+        L.seer_stream_copy.argtypes = [vp, vp, sz, vp]
+        L.seer_stream_copy.restype = C.c_int
+        L.seer_stream_sum.argtypes = [vp, sz, vp, vp]
+        L.seer_stream_sum.restype = C.c_int
         L.seer_num_kernels.restype = C.c_int
         L.seer_kernel_name.argtypes = [C.c_int]
         L.seer_kernel_name.restype = C.c_char_p
@@ -240,3 +244,20 @@ def seer_spmv(kernel_id: int, A: DeviceCSR, x, y, workspace=None, stream=None) -
                          workspace.numel() if workspace is not None else 0, _stream_ptr(stream))
     if rc:
         raise SeerError(rc, f"seer_spmv(kernel {kernel_id})")
+
+
+def seer_stream_copy(dst, src, stream=None) -> None:
+    """dst[:] = src with the library's plain copy kernel (measurement aid)."""
+    assert dst.is_contiguous() and src.is_contiguous() and dst.element_size() == 4 == src.element_size()
+    assert dst.numel() == src.numel()
+    rc = lib().seer_stream_copy(dst.data_ptr(), src.data_ptr(), src.numel(), _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_stream_copy")
+
+
+def seer_stream_sum(src, out64, stream=None) -> None:
+    """Read-only pass over src with the library's checksum kernel (measurement aid)."""
+    assert src.is_contiguous() and src.element_size() == 4 and out64.numel() * out64.element_size() >= 256
+    rc = lib().seer_stream_sum(src.data_ptr(), src.numel(), out64.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_stream_sum")

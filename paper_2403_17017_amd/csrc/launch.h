@@ -6,8 +6,8 @@
 
 namespace seer {
 
-constexpr int kBmMaxRows = 1024;  // most rows one CSR,BM workgroup owns (LDS row_ptr segment)
-constexpr int kBmChunk = 2048;    // products staged in LDS per CSR,BM pass
+constexpr int kBmMaxRows = 2048;  // most rows one CSR,BM workgroup owns (8 per lane, bounds in registers)
+constexpr int kBmChunk = 2048;    // products staged in LDS per CSR,BM pass (4096 is the other choice)
 constexpr int kMpIptSmall = 7;    // merge items per thread, small problems (tile = 1792 items)
 constexpr int kMpIptLarge = 15;   // merge items per thread, large problems (tile = 3840 items)
 
@@ -17,11 +17,12 @@ struct SpmvArgs {
     const float *va, *x;
     float *y;
     int remap;  // 1: tiles laid out contiguously per XCD
+    int nt;     // 1: matrix streams are loaded with the non-temporal hint (keeps x in L2)
 };
 
 void launch_tm(const SpmvArgs &a, hipStream_t st);
 void launch_wm(const SpmvArgs &a, int lanes_per_row, hipStream_t st);
-void launch_bm(const SpmvArgs &a, int rows_per_block, bool vec, hipStream_t st);
+void launch_bm(const SpmvArgs &a, int rows_per_block, int chunk, bool vec, hipStream_t st);
 
 // merge path: ipt is kMpIptSmall or kMpIptLarge
 uint32_t mp_num_tiles(int rows, int nnz, int ipt);
@@ -39,5 +40,8 @@ uint32_t features_num_blocks(int rows);
 size_t features_workspace_bytes(int rows);
 void launch_features(int rows, const int *rp, void *workspace, FeatureRaw *mailbox_dev,
                      uint64_t seq, hipStream_t st);
+
+void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);
+void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st);
 
 } // namespace seer

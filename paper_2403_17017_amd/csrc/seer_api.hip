@@ -5,6 +5,7 @@
 #include "launch.h"
 
 #include <atomic>
+#include <chrono>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -18,8 +19,11 @@ std::atomic<int> g_last_hip_error{0};
 // Tuning hooks (negative = choose automatically).
 std::atomic<int> g_tune_wm_lanes{-1};
 std::atomic<int> g_tune_bm_rows{-1};
+std::atomic<int> g_tune_bm_chunk{-1};
 std::atomic<int> g_tune_mp_ipt{-1};
 std::atomic<int> g_tune_remap{-1};
+std::atomic<int> g_tune_nt{-1};
+std::atomic<int> g_tune_poll{-1};
 
 std::mutex g_mailbox_mutex;
 FeatureRaw *g_mailbox_host = nullptr;   // pinned, mapped
@@ -59,15 +63,25 @@ int wm_lanes(int rows, int nnz)
     return pow2_at_least(mean, 2, 64);
 }
 
-// Rows per workgroup for CSR,BM: about one LDS chunk of nonzeros per block.
+// Rows per workgroup for CSR,BM.  A block should stream about 5 K nonzeros (two to
+// three LDS chunks: fewer, fatter blocks stream better), but a small matrix is cut
+// finer so that the 256 CUs still get 8 blocks each.
 int bm_rows(int rows, int nnz)
 {
     const int t = g_tune_bm_rows.load();
     if (t >= 1 && t <= kBmMaxRows) return t;
     const double mean = rows > 0 ? (double)nnz / (double)rows : 0.0;
     int r = kBmMaxRows;
-    while (r > 64 && (double)r * mean > (double)kBmChunk) r >>= 1;
+    while (r > 8 && (double)r * mean > 5120.0) r >>= 1;
+    if (r > 1024) r = 1024;
+    while (r > 256 && rows / r < 2048) r >>= 1;
     return r;
+}
+
+int bm_chunk()
+{
+    const int t = g_tune_bm_chunk.load();
+    return t == 4096 ? 4096 : kBmChunk;
 }
 
 int mp_ipt(int rows, int nnz)
@@ -82,6 +96,12 @@ int mp_ipt(int rows, int nnz)
 int use_remap()
 {
     const int t = g_tune_remap.load();
+    return t < 0 ? 1 : (t != 0);
+}
+
+int use_nt()
+{
+    const int t = g_tune_nt.load();
     return t < 0 ? 1 : (t != 0);
 }
 
@@ -160,8 +180,11 @@ int seer_set_tuning(const char *name, int value)
     if (!name) return SEER_EINVAL;
     if (!std::strcmp(name, "wm_lanes")) g_tune_wm_lanes.store(value);
     else if (!std::strcmp(name, "bm_rows")) g_tune_bm_rows.store(value);
+    else if (!std::strcmp(name, "bm_chunk")) g_tune_bm_chunk.store(value);
     else if (!std::strcmp(name, "mp_ipt")) g_tune_mp_ipt.store(value);
     else if (!std::strcmp(name, "xcd_remap")) g_tune_remap.store(value);
+    else if (!std::strcmp(name, "nt")) g_tune_nt.store(value);
+    else if (!std::strcmp(name, "poll")) g_tune_poll.store(value);
     else return SEER_EINVAL;
     return SEER_OK;
 }
@@ -223,11 +246,29 @@ int seer_features(const seer_csr *A, seer_features_t *out, void *workspace, size
         launch_features(A->rows, A->row_ptr, workspace, g_mailbox_dev, seq, st);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e);
-        e = hipStreamSynchronize(st);
-        if (e != hipSuccess) return hip_fail(e);
+        // The kernel writes the statistics, then the sequence number, into pinned host
+        // memory.  Watching that word is quicker than waiting for the stream; if it does
+        // not show up soon, wait for the stream and look again.
+        volatile uint64_t *seq_word = &g_mailbox_host->seq;
+        bool seen = false;
+        if (g_tune_poll.load() != 0) {
+            const auto t0 = std::chrono::steady_clock::now();
+            for (uint32_t spin = 0;; ++spin) {
+                if (*seq_word == seq) { seen = true; break; }
+                if ((spin & 1023u) == 1023u &&
+                    std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(2))
+                    break;
+                __builtin_ia32_pause();
+            }
+        }
+        if (!seen) {
+            e = hipStreamSynchronize(st);
+            if (e != hipSuccess) return hip_fail(e);
+            if (*seq_word != seq) return hip_fail(hipErrorUnknown);
+        }
+        std::atomic_thread_fence(std::memory_order_acquire);
         FeatureRaw raw;
-        std::memcpy(&raw, g_mailbox_host, sizeof raw);   // written by the device; the sync ordered it
-        if (raw.seq != seq) return hip_fail(hipErrorUnknown);
+        std::memcpy(&raw, const_cast<const FeatureRaw *>(g_mailbox_host), sizeof raw);
         o.nnz = (int64_t)raw.last - (int64_t)raw.first;
         o.max_len = raw.max_len;
         o.min_len = raw.min_len;
@@ -267,6 +308,24 @@ int seer_select(const seer_features_t *f, const seer_tree *t, int *kernel_id)
     return SEER_ETREE;   // walked more nodes than exist: a cycle
 }
 
+int seer_stream_copy(void *dst, const void *src, size_t n_words, void *stream)
+{
+    if (n_words == 0) return SEER_OK;
+    if (!dst || !src || !aligned16(dst) || !aligned16(src)) return SEER_EINVAL;
+    launch_stream_copy(dst, src, n_words, static_cast<hipStream_t>(stream));
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream)
+{
+    if (n_words == 0) return SEER_OK;
+    if (!src || !out64 || !aligned16(src)) return SEER_EINVAL;
+    launch_stream_sum(src, n_words, out64, static_cast<hipStream_t>(stream));
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
 int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *workspace,
               size_t workspace_bytes, void *stream)
 {
@@ -276,12 +335,12 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *
     if (A->rows == 0) return SEER_OK;
     if (!y || (!x && A->nnz > 0)) return SEER_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap()};
+    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt()};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values);
     switch (kernel_id) {
     case SEER_CSR_TM: launch_tm(a, st); break;
     case SEER_CSR_WM: launch_wm(a, wm_lanes(A->rows, A->nnz), st); break;
-    case SEER_CSR_BM: launch_bm(a, bm_rows(A->rows, A->nnz), vec, st); break;
+    case SEER_CSR_BM: launch_bm(a, bm_rows(A->rows, A->nnz), bm_chunk(), vec, st); break;
     default: {
         const int ipt = mp_ipt(A->rows, A->nnz);
         if (!workspace || !aligned16(workspace) || workspace_bytes < mp_workspace_bytes(A->rows, A->nnz, ipt))

@@ -57,7 +57,7 @@ __device__ __forceinline__ SegPair seg_join(SegPair left, SegPair right)
     return r;
 }
 
-template <int IPT, bool VEC>
+template <int IPT, bool VEC, bool NT>
 __global__ __launch_bounds__(kWG) void spmv_mp_kernel(
     int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
@@ -88,19 +88,19 @@ __global__ __launch_bounds__(kWG) void spmv_mp_kernel(
     const uint32_t nr = i1 - i0, nn = j1 - j0, n_items = d1 - d0;
 
     // ---- stage row ends and products
-    for (uint32_t a = tid; a < nr; a += kWG) s_item[a] = (int)((uint32_t)rp[i0 + 1 + a] - j0);
+    for (uint32_t a = tid; a < nr; a += kWG) s_item[a] = (int)((uint32_t)load_1<NT>(rp + i0 + 1 + a) - j0);
     {
         const uint32_t base = j0 & ~3u;
-        int4 c[NV];
-        float4 v[NV];
+        v4i c[NV];
+        v4f v[NV];
         bool full[NV];
 #pragma unroll
         for (int m = 0; m < NV; ++m) {
             const uint32_t k = base + 4u * (tid + kWG * m);
             full[m] = VEC && k >= j0 && k + 4 <= j1;
             if (full[m]) {
-                c[m] = *reinterpret_cast<const int4 *>(ci + k);
-                v[m] = *reinterpret_cast<const float4 *>(va + k);
+                c[m] = load_v4i<NT>(ci + k);
+                v[m] = load_v4f<NT>(va + k);
             }
         }
 #pragma unroll
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kWG) void spmv_mp_kernel(
                 for (uint32_t q = 0; q < 4; ++q) {
                     const uint32_t j = k + q;
                     if (j >= j0 && j < j1)
-                        reinterpret_cast<float *>(s_item)[nr + (j - j0)] = va[j] * x[ci[j]];
+                        reinterpret_cast<float *>(s_item)[nr + (j - j0)] = load_1<NT>(va + j) * x[load_1<NT>(ci + j)];
                 }
             }
         }
@@ -246,12 +246,15 @@ static void launch_mp_ipt(const SpmvArgs &a, bool vec, void *workspace, hipStrea
     int *carry_row = static_cast<int *>(workspace);
     float *carry_val = reinterpret_cast<float *>(static_cast<char *>(workspace) + one);
     const dim3 grid(a.remap ? tiles_per_xcd(n_tiles) * kXCD : n_tiles);
-    if (vec)
-        hipLaunchKernelGGL((spmv_mp_kernel<IPT, true>), grid, dim3(kWG), 0, st, a.rows, a.nnz, a.rp, a.ci,
-                           a.va, a.x, a.y, carry_row, carry_val, n_tiles, a.remap);
-    else
-        hipLaunchKernelGGL((spmv_mp_kernel<IPT, false>), grid, dim3(kWG), 0, st, a.rows, a.nnz, a.rp, a.ci,
-                           a.va, a.x, a.y, carry_row, carry_val, n_tiles, a.remap);
+#define SEER_MP_LAUNCH(V, N)                                                                            \
+    hipLaunchKernelGGL((spmv_mp_kernel<IPT, V, N>), grid, dim3(kWG), 0, st, a.rows, a.nnz, a.rp, a.ci, a.va, \
+                       a.x, a.y, carry_row, carry_val, n_tiles, a.remap)
+    if (vec) {
+        if (a.nt) SEER_MP_LAUNCH(true, true); else SEER_MP_LAUNCH(true, false);
+    } else {
+        if (a.nt) SEER_MP_LAUNCH(false, true); else SEER_MP_LAUNCH(false, false);
+    }
+#undef SEER_MP_LAUNCH
     hipLaunchKernelGGL(spmv_mp_fixup_kernel, dim3((n_tiles + kWG - 1) / kWG), dim3(kWG), 0, st,
                        a.rows, n_tiles, carry_row, carry_val, a.y);
 }

@@ -72,99 +72,119 @@ __global__ __launch_bounds__(kWG) void spmv_wm_kernel(
 }
 
 // ------------------------------------------------------------------ CSR,BM
-// LDS: row_ptr segment (kBmMaxRows + 1 ints), one running sum per row, CH staged
-// products, and a short list of the rows that are long inside the current chunk.
-constexpr int kBmLong = 32;   // a row's overlap with a chunk above this is reduced by a wave
+// A workgroup owns rows_per_block consecutive rows, i.e. one contiguous range of
+// nonzeros [s, e).  The range is streamed in chunks of CH entries with 16-byte loads
+// (entry k of the chunk is loaded by lane (k / 4) mod 256, whatever row it belongs
+// to), the products val * x[col] are parked in LDS, and after one barrier each lane
+// adds up the slice of the chunk that belongs to each of its rows.  A row whose
+// slice is longer than kBmLong is instead reduced by the whole wave that owns it.
+// Row bounds live in registers (lane t owns rows t, t + 256, ... of the block), so
+// the only LDS traffic is the products.
+constexpr int kBmLong = 32;
 
-template <int CH, bool VEC>
+// Stage val * x[col] for entries [lo, ce) of the chunk starting at cs (cs % 4 == 0)
+// into s_prod[k - cs].  All loads are issued before the first gather.
+template <int CH, bool VEC, bool NT>
+__device__ __forceinline__ void stage_products(
+    const int *__restrict__ ci, const float *__restrict__ va, const float *__restrict__ x,
+    float *__restrict__ s_prod, uint32_t cs, uint32_t lo, uint32_t ce, int tid)
+{
+    constexpr int NV = CH / (4 * kWG);
+    v4i c[NV];
+    v4f v[NV];
+    bool full[NV];
+#pragma unroll
+    for (int m = 0; m < NV; ++m) {
+        const uint32_t k = cs + 4u * (uint32_t)(tid + kWG * m);
+        full[m] = VEC && k >= lo && k + 4 <= ce;
+        if (full[m]) {
+            c[m] = load_v4i<NT>(ci + k);
+            v[m] = load_v4f<NT>(va + k);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < NV; ++m) {
+        const uint32_t k = cs + 4u * (uint32_t)(tid + kWG * m);
+        if (full[m]) {
+            v4f p;
+            p.x = v[m].x * x[c[m].x];
+            p.y = v[m].y * x[c[m].y];
+            p.z = v[m].z * x[c[m].z];
+            p.w = v[m].w * x[c[m].w];
+            *reinterpret_cast<v4f *>(s_prod + (k - cs)) = p;
+        } else {
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t j = k + q;
+                if (j >= lo && j < ce) s_prod[j - cs] = load_1<NT>(va + j) * x[load_1<NT>(ci + j)];
+            }
+        }
+    }
+}
+
+template <int CH, bool VEC, bool NT>
 __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     int rows, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
     int rows_per_block, uint32_t n_tiles, int remap)
 {
-    static_assert(CH % (4 * kWG) == 0, "chunk must be whole float4 rounds");
-    constexpr int NV = CH / (4 * kWG);
-    __shared__ int s_rp[kBmMaxRows + 1];
-    __shared__ float s_y[kBmMaxRows];
+    static_assert(CH % (4 * kWG) == 0, "chunk must be whole 16-byte rounds");
+    constexpr int RPT = kBmMaxRows / kWG;   // most rows one lane owns
     __shared__ __attribute__((aligned(16))) float s_prod[CH];
-    __shared__ int s_long[CH / kBmLong];
-    __shared__ int s_nlong;
 
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
-    const int tid = (int)threadIdx.x;
+    const int tid = (int)threadIdx.x, lane = tid % kWave;
     const uint32_t r0 = tile * (uint32_t)rows_per_block;
     const int nr = (int)min((uint32_t)rows_per_block, (uint32_t)rows - r0);
 
-    for (int i = tid; i <= nr; i += kWG) s_rp[i] = rp[r0 + i];
-    for (int i = tid; i < nr; i += kWG) s_y[i] = 0.f;
-    if (tid == 0) s_nlong = 0;
-    __syncthreads();
+    const uint32_t s = (uint32_t)rp[r0], e = (uint32_t)rp[r0 + nr];   // block-uniform
+    uint32_t ra[RPT], rb[RPT];
+    float acc[RPT];
+#pragma unroll
+    for (int m = 0; m < RPT; ++m) {
+        const int r = tid + kWG * m;
+        const bool own = r < nr;
+        ra[m] = own ? (uint32_t)load_1<NT>(rp + r0 + r) : 0u;
+        rb[m] = own ? (uint32_t)load_1<NT>(rp + r0 + r + 1) : 0u;
+        acc[m] = 0.f;
+    }
 
-    const uint32_t s = (uint32_t)s_rp[0], e = (uint32_t)s_rp[nr];
     for (uint32_t cs = s & ~3u; cs < e; cs += CH) {
         const uint32_t ce = min(cs + (uint32_t)CH, e);
         const uint32_t lo = max(cs, s);
-        // ---- stage val * x[col] for [lo, ce) at s_prod[k - cs]
-        int4 c[NV];
-        float4 v[NV];
-        bool full[NV];
+        stage_products<CH, VEC, NT>(ci, va, x, s_prod, cs, lo, ce, tid);
+        __syncthreads();
 #pragma unroll
-        for (int m = 0; m < NV; ++m) {
-            const uint32_t k = cs + 4u * (uint32_t)(tid + kWG * m);
-            full[m] = VEC && k >= lo && k + 4 <= ce;
-            if (full[m]) {
-                c[m] = *reinterpret_cast<const int4 *>(ci + k);
-                v[m] = *reinterpret_cast<const float4 *>(va + k);
+        for (int m = 0; m < RPT; ++m) {
+            if (kWG * m >= nr) break;                       // block-uniform
+            const uint32_t a = max(ra[m], lo), b = min(rb[m], ce);
+            const bool has = b > a;
+            const bool is_long = has && b - a > (uint32_t)kBmLong;
+            if (has && !is_long) {
+                float t = 0.f;
+                for (uint32_t k = a; k < b; ++k) t += s_prod[k - cs];
+                acc[m] += t;
+            }
+            // rows that are long inside this chunk: the owning wave reduces them together
+            uint64_t todo = __ballot(is_long);
+            while (todo) {                                   // wave-uniform
+                const int src = __ffsll((unsigned long long)todo) - 1;
+                todo &= todo - 1;
+                const uint32_t la = (uint32_t)__shfl((int)a, src), lb = (uint32_t)__shfl((int)b, src);
+                float t = 0.f;
+                for (uint32_t k = la + (uint32_t)lane; k < lb; k += kWave) t += s_prod[k - cs];
+                t = group_sum<64>(t);
+                if (lane == src) acc[m] += t;
             }
         }
-#pragma unroll
-        for (int m = 0; m < NV; ++m) {
-            const uint32_t k = cs + 4u * (uint32_t)(tid + kWG * m);
-            if (full[m]) {
-                float4 p;
-                p.x = v[m].x * x[c[m].x];
-                p.y = v[m].y * x[c[m].y];
-                p.z = v[m].z * x[c[m].z];
-                p.w = v[m].w * x[c[m].w];
-                *reinterpret_cast<float4 *>(s_prod + (k - cs)) = p;
-            } else {
-#pragma unroll
-                for (uint32_t q = 0; q < 4; ++q) {
-                    const uint32_t j = k + q;
-                    if (j >= lo && j < ce) s_prod[j - cs] = va[j] * x[ci[j]];
-                }
-            }
-        }
-        __syncthreads();
-        // ---- one lane per row: short overlaps summed in place, long ones queued
-        for (int r = tid; r < nr; r += kWG) {
-            const uint32_t a = max((uint32_t)s_rp[r], lo), b = min((uint32_t)s_rp[r + 1], ce);
-            if (b > a) {
-                if (b - a <= (uint32_t)kBmLong) {
-                    float acc = 0.f;
-                    for (uint32_t k = a; k < b; ++k) acc += s_prod[k - cs];
-                    s_y[r] += acc;
-                } else {
-                    s_long[atomicAdd(&s_nlong, 1)] = r;
-                }
-            }
-        }
-        __syncthreads();
-        // ---- one wave per queued row
-        const int nlong = s_nlong;
-        for (int q = tid / kWave; q < nlong; q += kWG / kWave) {
-            const int r = s_long[q];
-            const uint32_t a = max((uint32_t)s_rp[r], lo), b = min((uint32_t)s_rp[r + 1], ce);
-            float acc = 0.f;
-            for (uint32_t k = a + (uint32_t)(tid % kWave); k < b; k += kWave) acc += s_prod[k - cs];
-            acc = group_sum<64>(acc);
-            if (tid % kWave == 0) s_y[r] += acc;
-        }
-        __syncthreads();
-        if (tid == 0) s_nlong = 0;   // next use is after the next chunk's staging barrier
+        if (ce < e) __syncthreads();   // s_prod is overwritten by the next chunk
     }
-    for (int r = tid; r < nr; r += kWG) y[r0 + r] = s_y[r];
+#pragma unroll
+    for (int m = 0; m < RPT; ++m) {
+        const int r = tid + kWG * m;
+        if (r < nr) y[r0 + r] = acc[m];
+    }
 }
 
 // ------------------------------------------------------------------ launchers
@@ -201,16 +221,30 @@ void launch_wm(const SpmvArgs &a, int G, hipStream_t st)
     }
 }
 
-void launch_bm(const SpmvArgs &a, int rows_per_block, bool vec, hipStream_t st)
+template <int CH, bool VEC, bool NT>
+static void launch_bm_v(const SpmvArgs &a, int rows_per_block, hipStream_t st)
 {
     const uint32_t n_tiles = ((uint32_t)a.rows + rows_per_block - 1) / (uint32_t)rows_per_block;
-    const dim3 grid(grid_for(n_tiles, a.remap));
-    if (vec)
-        hipLaunchKernelGGL((spmv_bm_kernel<kBmChunk, true>), grid, dim3(kWG), 0, st,
-                           a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, n_tiles, a.remap);
-    else
-        hipLaunchKernelGGL((spmv_bm_kernel<kBmChunk, false>), grid, dim3(kWG), 0, st,
-                           a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, n_tiles, a.remap);
+    hipLaunchKernelGGL((spmv_bm_kernel<CH, VEC, NT>), dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
+                       a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, n_tiles, a.remap);
+}
+
+template <int CH>
+static void launch_bm_c(const SpmvArgs &a, int rows_per_block, bool vec, hipStream_t st)
+{
+    if (vec) {
+        if (a.nt) launch_bm_v<CH, true, true>(a, rows_per_block, st);
+        else launch_bm_v<CH, true, false>(a, rows_per_block, st);
+    } else {
+        if (a.nt) launch_bm_v<CH, false, true>(a, rows_per_block, st);
+        else launch_bm_v<CH, false, false>(a, rows_per_block, st);
+    }
+}
+
+void launch_bm(const SpmvArgs &a, int rows_per_block, int chunk, bool vec, hipStream_t st)
+{
+    if (chunk == 4096) launch_bm_c<4096>(a, rows_per_block, vec, st);
+    else launch_bm_c<2048>(a, rows_per_block, vec, st);
 }
 
 } // namespace seer

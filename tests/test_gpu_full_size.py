@@ -1,0 +1,59 @@
+"""GPU parity at the full sizes of the BASELINE configs, every row compared with the
+oracle, in the launch configuration bench.py times (default launch shapes)."""
+import numpy as np
+import pytest
+
+import paper_2403_17017_amd as S
+from oracle import seer_oracle as O
+from workloads import csr_gen as G
+
+from gpu_util import announce, assert_features_equal, assert_parity, oracle_of, run_spmv, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def check_all(A, kernels=(0, 1, 2, 3)):
+    import torch
+    x = G.dense_vector(A.cols, 4242)
+    y_ref, bound = oracle_of(A, x)
+    dA = upload(A)
+    xd = torch.from_numpy(x).cuda()
+    announce(f"full size {A.name}: features")
+    assert_features_equal(S.seer_features(dA), O.features(A.rows, A.cols, A.row_ptr), A.name)
+    for kid in kernels:
+        announce(f"full size {A.name}: kernel {kid} rows={A.rows} nnz={A.nnz}")
+        y = run_spmv(kid, dA, xd, A.rows)
+        assert_parity(y, y_ref, bound, f"kernel {kid} on {A.name}")
+    return dA, xd
+
+
+def test_config2_laplacian_1024():
+    import torch
+    A = G.laplacian_5pt(1024)
+    dA, _ = check_all(A)
+    # closed form on top of the oracle: x = 1 gives 4 - (number of neighbours), exactly
+    ones = torch.ones(A.cols, device="cuda:0")
+    r, c = np.divmod(np.arange(A.rows), 1024)
+    want = (((r == 0) | (r == 1023)).astype(np.float32) + ((c == 0) | (c == 1023)).astype(np.float32))
+    for kid in range(4):
+        assert np.array_equal(run_spmv(kid, dA, ones, A.rows), want)
+
+
+def test_config4_empty_rows_poisson_8M():
+    A = G.empty_poisson()
+    assert A.rows == 8_000_000 and A.cols == 1_000_000
+    check_all(A)
+
+
+def test_config3_zipf_nnz_matched():
+    """Zipf exponent 1.85: the variant whose nonzero count (~47 M) matches the stated one."""
+    A = G.zipf_rows(s=1.85)
+    assert A.rows == 2_000_000 and int(np.diff(A.row_ptr).max()) == 200_000
+    check_all(A)
+
+
+def test_config3_zipf_literal_parameters():
+    """Zipf exponent 1.6 as stated (~4.8e8 nonzeros, 3.8 GB of entries)."""
+    A = G.zipf_rows(s=1.6)
+    assert A.nnz > 4e8 and int(np.diff(A.row_ptr).max()) == 200_000
+    check_all(A)
