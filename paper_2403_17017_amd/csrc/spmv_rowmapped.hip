@@ -78,12 +78,20 @@ __global__ __launch_bounds__(kWG) void spmv_wm_kernel(
 // to), the products val * x[col] are parked in LDS, and after one barrier each lane
 // adds up the slice of the chunk that belongs to each of its rows.  A row whose
 // slice is longer than kBmLong is instead reduced by the whole wave that owns it.
-// Row bounds live in registers (lane t owns rows t, t + 256, ... of the block), so
-// the only LDS traffic is the products.
-constexpr int kBmLong = 32;
+// Row bounds live in registers, so the only LDS traffic is the products.
+//
+// Ownership: with 256 or more rows per block, lane t owns rows t, t + 256, ...;
+// with fewer, the rows are spread evenly over the 256 lanes (every 256/P-th lane
+// owns one, P = rows per block rounded up to a power of two) so that all four waves
+// share the per-row work.
+// LDS index i is stored at i + i/32: a lane walking its row with a stride that is a
+// multiple of 32 words would otherwise hit one bank with the whole wave.
+constexpr int kBmLong = 128;
+
+__device__ __forceinline__ uint32_t lds_pad(uint32_t i) { return i + (i >> 5); }
 
 // Stage val * x[col] for entries [lo, ce) of the chunk starting at cs (cs % 4 == 0)
-// into s_prod[k - cs].  All loads are issued before the first gather.
+// into s_prod[lds_pad(k - cs)].  All loads are issued before the first gather.
 template <int CH, bool VEC, bool NT>
 __device__ __forceinline__ void stage_products(
     const int *__restrict__ ci, const float *__restrict__ va, const float *__restrict__ x,
@@ -106,17 +114,16 @@ __device__ __forceinline__ void stage_products(
     for (int m = 0; m < NV; ++m) {
         const uint32_t k = cs + 4u * (uint32_t)(tid + kWG * m);
         if (full[m]) {
-            v4f p;
-            p.x = v[m].x * x[c[m].x];
-            p.y = v[m].y * x[c[m].y];
-            p.z = v[m].z * x[c[m].z];
-            p.w = v[m].w * x[c[m].w];
-            *reinterpret_cast<v4f *>(s_prod + (k - cs)) = p;
+            float *dst = s_prod + lds_pad(k - cs);   // k - cs is a multiple of 4: no pad inside the quad
+            dst[0] = v[m].x * x[c[m].x];
+            dst[1] = v[m].y * x[c[m].y];
+            dst[2] = v[m].z * x[c[m].z];
+            dst[3] = v[m].w * x[c[m].w];
         } else {
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
                 const uint32_t j = k + q;
-                if (j >= lo && j < ce) s_prod[j - cs] = load_1<NT>(va + j) * x[load_1<NT>(ci + j)];
+                if (j >= lo && j < ce) s_prod[lds_pad(j - cs)] = load_1<NT>(va + j) * x[load_1<NT>(ci + j)];
             }
         }
     }
@@ -126,11 +133,11 @@ template <int CH, bool VEC, bool NT>
 __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     int rows, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
-    int rows_per_block, uint32_t n_tiles, int remap)
+    int rows_per_block, int own_shift, uint32_t n_tiles, int remap)
 {
     static_assert(CH % (4 * kWG) == 0, "chunk must be whole 16-byte rounds");
     constexpr int RPT = kBmMaxRows / kWG;   // most rows one lane owns
-    __shared__ __attribute__((aligned(16))) float s_prod[CH];
+    __shared__ float s_prod[CH + CH / 32];
 
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
@@ -139,12 +146,16 @@ __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     const int nr = (int)min((uint32_t)rows_per_block, (uint32_t)rows - r0);
 
     const uint32_t s = (uint32_t)rp[r0], e = (uint32_t)rp[r0 + nr];   // block-uniform
+    // lane's m-th row: ((tid >> own_shift) + 256 * m) if tid is a multiple of 2^own_shift
+    // (own_shift > 0 only when rows_per_block < 256, and then m = 0 is the only one)
+    const bool owner_lane = (tid & ((1 << own_shift) - 1)) == 0;
+    const int row_base = tid >> own_shift;
     uint32_t ra[RPT], rb[RPT];
     float acc[RPT];
 #pragma unroll
     for (int m = 0; m < RPT; ++m) {
-        const int r = tid + kWG * m;
-        const bool own = r < nr;
+        const int r = row_base + kWG * m;
+        const bool own = owner_lane && r < nr;
         ra[m] = own ? (uint32_t)load_1<NT>(rp + r0 + r) : 0u;
         rb[m] = own ? (uint32_t)load_1<NT>(rp + r0 + r + 1) : 0u;
         acc[m] = 0.f;
@@ -163,7 +174,7 @@ __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
             const bool is_long = has && b - a > (uint32_t)kBmLong;
             if (has && !is_long) {
                 float t = 0.f;
-                for (uint32_t k = a; k < b; ++k) t += s_prod[k - cs];
+                for (uint32_t k = a; k < b; ++k) t += s_prod[lds_pad(k - cs)];
                 acc[m] += t;
             }
             // rows that are long inside this chunk: the owning wave reduces them together
@@ -173,7 +184,7 @@ __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
                 todo &= todo - 1;
                 const uint32_t la = (uint32_t)__shfl((int)a, src), lb = (uint32_t)__shfl((int)b, src);
                 float t = 0.f;
-                for (uint32_t k = la + (uint32_t)lane; k < lb; k += kWave) t += s_prod[k - cs];
+                for (uint32_t k = la + (uint32_t)lane; k < lb; k += kWave) t += s_prod[lds_pad(k - cs)];
                 t = group_sum<64>(t);
                 if (lane == src) acc[m] += t;
             }
@@ -182,8 +193,8 @@ __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     }
 #pragma unroll
     for (int m = 0; m < RPT; ++m) {
-        const int r = tid + kWG * m;
-        if (r < nr) y[r0 + r] = acc[m];
+        const int r = row_base + kWG * m;
+        if (owner_lane && r < nr) y[r0 + r] = acc[m];
     }
 }
 
@@ -225,8 +236,10 @@ template <int CH, bool VEC, bool NT>
 static void launch_bm_v(const SpmvArgs &a, int rows_per_block, hipStream_t st)
 {
     const uint32_t n_tiles = ((uint32_t)a.rows + rows_per_block - 1) / (uint32_t)rows_per_block;
+    int own_shift = 0;   // rows spread over the lanes when there are fewer rows than lanes
+    while ((rows_per_block << (own_shift + 1)) <= kWG) ++own_shift;
     hipLaunchKernelGGL((spmv_bm_kernel<CH, VEC, NT>), dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                       a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, n_tiles, a.remap);
+                       a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, own_shift, n_tiles, a.remap);
 }
 
 template <int CH>

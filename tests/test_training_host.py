@@ -1,0 +1,68 @@
+"""CPU-only checks of the training-side harness: the sweep recipe is deterministic,
+matrices it builds are valid CSR, and the CART fit recovers a planted rule."""
+import csv
+
+import numpy as np
+
+import paper_2403_17017_amd as S
+from paper_2403_17017_amd import training as T
+from workloads import sweep_gen as W
+
+
+def test_sweep_specs_are_deterministic_and_capped():
+    fams = set()
+    for m in range(40):
+        a, b = W.sweep_spec(m, nnz_cap=2_000_000), W.sweep_spec(m, nnz_cap=2_000_000)
+        assert a.family == b.family and a.rows == b.rows and np.array_equal(a.lens, b.lens)
+        assert a.nnz <= 2_000_000 and a.lens.min() >= 0 and a.lens.max() <= a.rows
+        fams.add(a.family)
+    assert fams == set(W.FAMILIES)
+
+
+def test_build_gives_valid_sorted_csr():
+    import torch
+    for m in range(12):
+        spec = W.sweep_spec(m, nnz_cap=300_000, max_rows_exp=4.5)
+        rp, ci, va, x = W.build_on_device(spec, "cpu")
+        rp, ci = rp.numpy().astype(np.int64), ci.numpy().astype(np.int64)
+        assert rp[0] == 0 and rp[-1] == ci.size == va.numel() and x.numel() == spec.rows
+        assert np.array_equal(np.diff(rp), spec.lens)
+        if ci.size:
+            assert ci.min() >= 0 and ci.max() < spec.rows
+            row = np.repeat(np.arange(spec.rows), spec.lens)
+            key = row * spec.rows + ci
+            assert np.all(np.diff(key) >= 0)          # ascending inside rows
+            if spec.family == "banded":
+                assert np.all(np.abs(ci - row) <= spec.params["b"]) and np.all(np.diff(key) > 0)
+        assert float(va.abs().max()) <= 1.0 if va.numel() else True
+
+
+def test_fit_recovers_planted_rule(tmp_path):
+    # kernel 2 is fastest iff var_len <= 40, else kernel 3; features cost 5 us
+    rng = np.random.default_rng(0)
+    p = tmp_path / "sweep.csv"
+    with open(p, "w", newline="") as fh:
+        w = csv.DictWriter(fh, fieldnames=T.CSV_FIELDS)
+        w.writeheader()
+        for m in range(300):
+            f = np.exp(rng.normal(2, 2, S.NUM_FEATURES)).astype(np.float32)
+            fast = 2 if f[6] <= 40 else 3
+            t = [100.0, 90.0, 80.0, 70.0]
+            t[fast] = 10.0
+            row = {"m": m, "family": "x", "rows": 1, "cols": 1, "nnz": 1, "t_features_us": 5.0,
+                   "max_disagreement": 0.0}
+            row.update({f"f_{n}": repr(float(v)) for n, v in zip(S.FEATURE_NAMES, f)})
+            row.update({f"t_k{k}_us": t[k] for k in range(4)})
+            w.writerow(row)
+    out = tmp_path / "tree.json"
+    tree = T.fit_tree(str(p), str(out))
+    rep = tree["report"]
+    assert rep["test"]["accuracy"] == 1.0 and rep["train"]["accuracy"] == 1.0
+    assert rep["all"]["speedup_vs_best_fixed"] > 1.2
+    # the shipped format round-trips through the C ABI walker
+    t, _ = T.load_tree(str(out))
+    from paper_2403_17017_amd import binding as B
+    for v, want in ((10.0, 2), (400.0, 3)):
+        f = B.seer_features_t()
+        f.f[6] = v
+        assert S.seer_select(f, t) == want
