@@ -141,6 +141,28 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y,
               void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
 
+/* The three steps above as one asynchronous call: the feature reduction, the tree
+ * walk (on the device: the tree travels in the kernel arguments) and the SpMV with
+ * the chosen schedule are enqueued on `stream` back to back and the call returns;
+ * no device result is waited for, so the sequence can also be captured in a HIP
+ * graph.  This is the runtime flow of Sec. III-B with the cost of feature
+ * collection (Sec. III-C) cut down to the reduction kernel itself.
+ * y is the same as seer_spmv would give with the id seer_select would return for
+ * the features seer_features would return (all three bit for bit).
+ * tree: HOST, at most 127 nodes and SEER_NUM_KERNELS classes, no cycles (SEER_ETREE
+ * otherwise; validated before anything is enqueued).
+ * workspace: DEVICE, 16-byte aligned, >= seer_spmv_auto_workspace_bytes(rows, nnz);
+ * it must stay untouched until the work has run. */
+int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y,
+                   void *workspace, size_t workspace_bytes, void *stream);
+size_t seer_spmv_auto_workspace_bytes(int32_t rows, int32_t nnz);
+
+/* Waits for `stream`, then reports what the last seer_spmv_auto that used `workspace`
+ * decided: the features it gathered and the kernel id it ran (either may be NULL).
+ * SEER_EINVAL if no selection has been written there. */
+int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *features,
+                          int *kernel_id);
+
 /* Launch-shape overrides for experiments; the defaults (value < 0) derive every
  * launch shape from rows and nnz alone (the trivially known sizes of Sec. III-A).
  *   "wm_lanes"  lanes per row of CSR,WM: 2, 4, 8, 16, 32 or 64

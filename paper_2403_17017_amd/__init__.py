@@ -5,5 +5,5 @@ Python binding over it."""
 from .binding import (  # noqa: F401
     CSR_BM, CSR_MP, CSR_TM, CSR_WM, FEATURE_NAMES, NUM_FEATURES, NUM_KERNELS, DeviceCSR, SeerError, Tree,
     alloc_workspace, features_workspace_bytes, kernel_name, lib, seer_derive_features, seer_features, seer_known_features,
-    seer_select, seer_spmv, seer_stream_copy, seer_stream_sum, set_tuning, spmv_workspace_bytes, strerror,
+    seer_select, seer_spmv, seer_spmv_auto, seer_spmv_auto_result, spmv_auto_workspace_bytes, seer_stream_copy, seer_stream_sum, set_tuning, spmv_workspace_bytes, strerror,
 )

@@ -88,6 +88,12 @@ def lib():
         L.seer_spmv.restype = C.c_int
         L.seer_spmv_workspace_bytes.argtypes = [C.c_int, i32, i32]
         L.seer_spmv_workspace_bytes.restype = sz
+        L.seer_spmv_auto.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_tree), vp, vp, vp, sz, vp]
+        L.seer_spmv_auto.restype = C.c_int
+        L.seer_spmv_auto_workspace_bytes.argtypes = [i32, i32]
+        L.seer_spmv_auto_workspace_bytes.restype = sz
+        L.seer_spmv_auto_result.argtypes = [vp, vp, C.POINTER(seer_features_t), C.POINTER(C.c_int)]
+        L.seer_spmv_auto_result.restype = C.c_int
         L.seer_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.seer_set_tuning.restype = C.c_int
         L.seer_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -261,3 +267,26 @@ def seer_stream_sum(src, out64, stream=None) -> None:
     rc = lib().seer_stream_sum(src.data_ptr(), src.numel(), out64.data_ptr(), _stream_ptr(stream))
     if rc:
         raise SeerError(rc, "seer_stream_sum")
+
+
+def spmv_auto_workspace_bytes(rows: int, nnz: int) -> int:
+    return int(lib().seer_spmv_auto_workspace_bytes(rows, nnz))
+
+
+def seer_spmv_auto(A: DeviceCSR, tree: Tree, x, y, workspace, stream=None) -> None:
+    """Features, tree walk and SpMV enqueued back to back; returns without waiting."""
+    cs = A.c_struct()
+    rc = lib().seer_spmv_auto(C.byref(cs), C.byref(tree.c), x.data_ptr(), y.data_ptr(),
+                              workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_spmv_auto")
+
+
+def seer_spmv_auto_result(workspace, stream=None):
+    """(features, kernel id) of the last seer_spmv_auto on this workspace (waits)."""
+    f = seer_features_t()
+    k = C.c_int(-1)
+    rc = lib().seer_spmv_auto_result(workspace.data_ptr(), _stream_ptr(stream), C.byref(f), C.byref(k))
+    if rc:
+        raise SeerError(rc, "seer_spmv_auto_result")
+    return f, int(k.value)

@@ -1,79 +1,9 @@
-// Feature collection over the CSR offsets (Sec. IV-A of the Seer case study): one
-// pass over row_ptr gives the longest and shortest row, the sum of squared row
-// lengths and the number of empty rows.  Everything reduced here is an integer, so
-// the result does not depend on the order of the reduction; the floating-point
-// features are derived from these integers on the host.
-//
-// One launch: every workgroup reduces a grid-strided share of the rows and stores
-// its partial; the workgroup that draws the last ticket folds all partials and
-// writes the result straight into pinned host memory.
-#include "common.hiph"
-#include "launch.h"
+// seer_features: the feature-collection launch (Sec. IV-A), plus two measurement
+// aids (plain copy and read-only stream).  The reduction is in features_bodies.hiph.
+#include "features_bodies.hiph"
 
 namespace seer {
 
-struct FeatPartial {
-    int32_t max_len, min_len;
-    uint64_t sum_sq, empty;
-    uint64_t pad;
-};
-static_assert(sizeof(FeatPartial) == 32, "partials are 32 bytes apart");
-
-// Few, large workgroups: every workgroup ends with one atomic on a single counter,
-// and those are served one after the other (about 25 ns each), so their number,
-// not the streaming of row_ptr, would otherwise set the kernel's duration.
-constexpr uint32_t kFeatWG = 1024;
-constexpr uint32_t kFeatWaves = kFeatWG / kWave;
-constexpr uint32_t kFeatMaxBlocks = 64;
-constexpr uint32_t kFeatRowsPerBlock = kFeatWG * 8;   // two 16-byte loads of row_ptr per lane
-
-// Ticket counter of the one-launch reduction.  Zero when the module is loaded and
-// set back to zero by the workgroup that finishes a reduction, so back-to-back
-// calls need no clearing pass.  Overlapping feature reductions on one device would
-// share it and must not happen.
-__device__ unsigned int g_feat_ticket = 0;
-
-__device__ __forceinline__ void wave_fold(int32_t &mx, int32_t &mn, uint64_t &sq, uint64_t &em)
-{
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        mx = max(mx, __shfl_xor(mx, off));
-        mn = min(mn, __shfl_xor(mn, off));
-        sq += (uint64_t)__shfl_xor((unsigned long long)sq, off);
-        em += (uint64_t)__shfl_xor((unsigned long long)em, off);
-    }
-}
-
-// Folds the four statistics over the workgroup; the result is valid in thread 0.
-__device__ __forceinline__ void block_fold(int32_t &mx, int32_t &mn, uint64_t &sq, uint64_t &em,
-                                           FeatPartial *s_part /* LDS [kFeatWaves] */)
-{
-    wave_fold(mx, mn, sq, em);
-    const uint32_t lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    __syncthreads();   // s_part may still be read from an earlier fold
-    if (lane == 0) s_part[wave] = FeatPartial{mx, mn, sq, em, 0};
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (uint32_t w = 1; w < kFeatWaves; ++w) {
-            mx = max(mx, s_part[w].max_len);
-            mn = min(mn, s_part[w].min_len);
-            sq += s_part[w].sum_sq;
-            em += s_part[w].empty;
-        }
-    }
-}
-
-__device__ __forceinline__ void take_row(int32_t len, int32_t &mx, int32_t &mn, uint64_t &sq, uint64_t &em)
-{
-    mx = max(mx, len);
-    mn = min(mn, len);
-    sq += (uint64_t)((int64_t)len * (int64_t)len);
-    em += len == 0;
-}
-
-// VEC: row_ptr is 16-byte aligned; lane handles rows 4q .. 4q+3 from one 16-byte load
-// plus the first offset of the next quad.  row_ptr is loaded with plain (temporal)
-// loads on purpose: the SpMV that follows reads it again.
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_kernel(
     int rows, const int *__restrict__ rp, FeatPartial *__restrict__ part,
@@ -81,61 +11,9 @@ __global__ __launch_bounds__(kFeatWG) void features_kernel(
 {
     __shared__ FeatPartial s_part[kFeatWaves];
     __shared__ int s_last;
-    int32_t mx = INT32_MIN, mn = INT32_MAX;
-    uint64_t sq = 0, em = 0;
-    const uint32_t stride = gridDim.x * kFeatWG;
-    if constexpr (VEC) {
-        const uint32_t n_quads = (uint32_t)rows / 4u;
-        uint32_t q = blockIdx.x * kFeatWG + threadIdx.x;
-        for (; q + stride < n_quads; q += 2 * stride) {      // two independent quads in flight
-            const v4i v = *reinterpret_cast<const v4i *>(rp + 4u * q);
-            const v4i w = *reinterpret_cast<const v4i *>(rp + 4u * (q + stride));
-            const int32_t vn = rp[4u * q + 4u], wn = rp[4u * (q + stride) + 4u];
-            take_row(v.y - v.x, mx, mn, sq, em);
-            take_row(v.z - v.y, mx, mn, sq, em);
-            take_row(v.w - v.z, mx, mn, sq, em);
-            take_row(vn - v.w, mx, mn, sq, em);
-            take_row(w.y - w.x, mx, mn, sq, em);
-            take_row(w.z - w.y, mx, mn, sq, em);
-            take_row(w.w - w.z, mx, mn, sq, em);
-            take_row(wn - w.w, mx, mn, sq, em);
-        }
-        if (q < n_quads) {
-            const v4i v = *reinterpret_cast<const v4i *>(rp + 4u * q);
-            const int32_t vn = rp[4u * q + 4u];
-            take_row(v.y - v.x, mx, mn, sq, em);
-            take_row(v.z - v.y, mx, mn, sq, em);
-            take_row(v.w - v.z, mx, mn, sq, em);
-            take_row(vn - v.w, mx, mn, sq, em);
-        }
-        if (blockIdx.x == 0 && threadIdx.x < ((uint32_t)rows & 3u)) {   // the last 0..3 rows
-            const uint32_t i = n_quads * 4u + threadIdx.x;
-            take_row(rp[i + 1] - rp[i], mx, mn, sq, em);
-        }
-    } else {
-        for (uint32_t i = blockIdx.x * kFeatWG + threadIdx.x; i < (uint32_t)rows; i += stride)
-            take_row(rp[i + 1] - rp[i], mx, mn, sq, em);
-    }
-    block_fold(mx, mn, sq, em, s_part);
-    if (threadIdx.x == 0) {
-        part[blockIdx.x] = FeatPartial{mx, mn, sq, em, 0};
-        __threadfence();                                   // partial visible device-wide ...
-        const unsigned int t = atomicAdd(&g_feat_ticket, 1u);   // ... before the ticket is drawn
-        s_last = (t == gridDim.x - 1);
-    }
-    __syncthreads();
-    if (!s_last) return;
-
-    __threadfence();   // acquire: see every other workgroup's partial
-    mx = INT32_MIN; mn = INT32_MAX; sq = 0; em = 0;
-    for (uint32_t b = threadIdx.x; b < gridDim.x; b += kFeatWG) {
-        const FeatPartial p = part[b];
-        mx = max(mx, p.max_len);
-        mn = min(mn, p.min_len);
-        sq += p.sum_sq;
-        em += p.empty;
-    }
-    block_fold(mx, mn, sq, em, s_part);
+    int32_t mx, mn;
+    uint64_t sq, em;
+    if (!features_reduce<VEC>(rows, rp, part, s_part, &s_last, mx, mn, sq, em)) return;
     if (threadIdx.x == 0) {
         FeatureRaw r;
         r.max_len = mx; r.min_len = mn;

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/seer.h"
+
 namespace seer {
 
 constexpr int kBmMaxRows = 2048;  // most rows one CSR,BM workgroup owns (8 per lane, bounds in registers)
@@ -40,6 +42,37 @@ uint32_t features_num_blocks(int rows);
 size_t features_workspace_bytes(int rows);
 void launch_features(int rows, const int *rp, void *workspace, FeatureRaw *mailbox_dev,
                      uint64_t seq, hipStream_t st);
+
+// CSR,BM: when a block owns fewer rows than it has lanes, every 2^shift-th lane owns one
+inline int bm_own_shift(int rows_per_block)
+{
+    int shift = 0;
+    while ((rows_per_block << (shift + 1)) <= 256) ++shift;
+    return shift;
+}
+
+// ---- asynchronous path: selection on the device, one combined SpMV kernel
+constexpr int kAutoMaxNodes = 127;          // a depth-6 binary tree; fits the 4 KB kernel-argument block
+struct AutoTree {                           // passed to the kernel by value
+    int32_t n_nodes, pad;
+    seer_node nodes[kAutoMaxNodes];
+};
+struct AutoSel {                            // what the selection kernel leaves in the workspace
+    int32_t kernel_id, valid;
+    int64_t rows, cols, nnz;
+    int32_t max_len, min_len;
+    uint64_t sum_sq, empty;
+    float f[SEER_NUM_FEATURES];
+};
+struct AutoShape {                          // launch shapes, all from rows and nnz alone
+    uint32_t tiles[SEER_NUM_KERNELS];
+    int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
+};
+constexpr size_t kAutoSelOffset = 2048;     // after the 64 feature partials of 32 bytes
+constexpr size_t kAutoCarryOffset = 2048 + 256;
+size_t auto_workspace_bytes(int rows, int nnz);
+void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, void *workspace,
+                 hipStream_t st);
 
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);
 void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st);

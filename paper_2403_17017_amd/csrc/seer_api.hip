@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 using namespace seer;
 
@@ -155,6 +156,50 @@ void derive(seer_features_t *o)
     }
 }
 
+int check_tree(const seer_tree *t)
+{
+    if (!t->nodes || t->n_nodes < 1 || t->n_classes < 1 || t->n_features < 0 ||
+        t->n_features > SEER_NUM_FEATURES)
+        return SEER_ETREE;
+    for (int32_t n = 0; n < t->n_nodes; ++n) {
+        const seer_node &nd = t->nodes[n];
+        if (nd.feature < 0) {
+            if (nd.klass < 0 || nd.klass >= t->n_classes) return SEER_ETREE;
+        } else {
+            if (nd.feature >= t->n_features) return SEER_ETREE;
+            if (nd.left < 0 || nd.left >= t->n_nodes || nd.right < 0 || nd.right >= t->n_nodes) return SEER_ETREE;
+            if (nd.threshold != nd.threshold) return SEER_ETREE;   // NaN
+        }
+    }
+    return SEER_OK;
+}
+
+// True if no path from the root visits a node twice (iterative depth-first walk).
+bool tree_is_acyclic(const seer_tree *t)
+{
+    const int32_t n = t->n_nodes;
+    std::vector<uint8_t> state((size_t)n, 0);   // 0 unseen, 1 on the current path, 2 done
+    std::vector<int32_t> stack;
+    stack.push_back(0);
+    while (!stack.empty()) {
+        const int32_t v = stack.back();
+        if (state[v] == 0) {
+            state[v] = 1;
+            const seer_node &nd = t->nodes[v];
+            if (nd.feature >= 0) {
+                for (int32_t c : {nd.left, nd.right}) {
+                    if (state[c] == 1) return false;
+                    if (state[c] == 0) stack.push_back(c);
+                }
+            }
+        } else {
+            if (state[v] == 1) state[v] = 2;
+            stack.pop_back();
+        }
+    }
+    return true;
+}
+
 const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP"};
 
 } // namespace
@@ -288,19 +333,8 @@ int seer_features(const seer_csr *A, seer_features_t *out, void *workspace, size
 int seer_select(const seer_features_t *f, const seer_tree *t, int *kernel_id)
 {
     if (!f || !t || !kernel_id) return SEER_EINVAL;
-    if (!t->nodes || t->n_nodes < 1 || t->n_classes < 1 || t->n_features < 0 ||
-        t->n_features > SEER_NUM_FEATURES)
-        return SEER_ETREE;
-    for (int32_t n = 0; n < t->n_nodes; ++n) {
-        const seer_node &nd = t->nodes[n];
-        if (nd.feature < 0) {
-            if (nd.klass < 0 || nd.klass >= t->n_classes) return SEER_ETREE;
-        } else {
-            if (nd.feature >= t->n_features) return SEER_ETREE;
-            if (nd.left < 0 || nd.left >= t->n_nodes || nd.right < 0 || nd.right >= t->n_nodes) return SEER_ETREE;
-            if (nd.threshold != nd.threshold) return SEER_ETREE;   // NaN
-        }
-    }
+    const int rc = check_tree(t);
+    if (rc != SEER_OK) return rc;
     int32_t n = 0;
     for (int32_t steps = 0; steps <= t->n_nodes; ++steps) {
         const seer_node &nd = t->nodes[n];
@@ -311,6 +345,74 @@ int seer_select(const seer_features_t *f, const seer_tree *t, int *kernel_id)
         n = ((double)f->f[nd.feature] <= nd.threshold) ? nd.left : nd.right;
     }
     return SEER_ETREE;   // walked more nodes than exist: a cycle
+}
+
+size_t seer_spmv_auto_workspace_bytes(int32_t rows, int32_t nnz)
+{
+    if (rows < 0 || nnz < 0) return 0;
+    return auto_workspace_bytes(rows, nnz);
+}
+
+int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    const int rc = check_csr(A, true);
+    if (rc != SEER_OK) return rc;
+    if (!tree) return SEER_EINVAL;
+    const int trc = check_tree(tree);
+    if (trc != SEER_OK) return trc;
+    if (tree->n_nodes > kAutoMaxNodes || tree->n_classes > SEER_NUM_KERNELS) return SEER_ETREE;
+    // a cycle is only found by walking; make sure no walk can be longer than the tree
+    if (!tree_is_acyclic(tree)) return SEER_ETREE;
+    if (A->rows == 0) return SEER_OK;
+    if (!y || (!x && A->nnz > 0)) return SEER_EINVAL;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < auto_workspace_bytes(A->rows, A->nnz))
+        return SEER_EWORKSPACE;
+    AutoTree dt;
+    std::memset(&dt, 0, sizeof dt);
+    dt.n_nodes = tree->n_nodes;
+    std::memcpy(dt.nodes, tree->nodes, sizeof(seer_node) * (size_t)tree->n_nodes);
+    AutoShape sh;
+    sh.wm_lanes = wm_lanes(A->rows, A->nnz);
+    sh.bm_rows = bm_rows(A->rows, A->nnz);
+    sh.bm_own_shift = bm_own_shift(sh.bm_rows);
+    sh.mp_ipt = mp_ipt(A->rows, A->nnz);
+    const uint32_t rows = (uint32_t)A->rows;
+    sh.tiles[SEER_CSR_TM] = (rows + 255u) / 256u;
+    sh.tiles[SEER_CSR_WM] = (rows + (256u / sh.wm_lanes) - 1u) / (256u / sh.wm_lanes);
+    sh.tiles[SEER_CSR_BM] = (rows + (uint32_t)sh.bm_rows - 1u) / (uint32_t)sh.bm_rows;
+    sh.tiles[SEER_CSR_MP] = mp_num_tiles(A->rows, A->nnz, sh.mp_ipt);
+    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), 1};
+    const bool vec = aligned16(A->col_idx) && aligned16(A->values);
+    launch_auto(a, dt, sh, vec, workspace, static_cast<hipStream_t>(stream));
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *features, int *kernel_id)
+{
+    if (!workspace) return SEER_EINVAL;
+    AutoSel sel;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(&sel, static_cast<const char *>(workspace) + kAutoSelOffset, sizeof sel,
+                                  hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    if (sel.valid != 1) return SEER_EINVAL;
+    if (kernel_id) *kernel_id = sel.kernel_id;
+    if (features) {
+        std::memset(features, 0, sizeof *features);
+        features->nnz = sel.nnz;
+        features->max_len = sel.max_len;
+        features->min_len = sel.min_len;
+        features->empty_rows = (int64_t)sel.empty;
+        features->sum_sq_len = sel.sum_sq;
+        features->rows = sel.rows;
+        features->cols = sel.cols;
+        for (int i = 0; i < SEER_NUM_FEATURES; ++i) features->f[i] = sel.f[i];
+    }
+    return SEER_OK;
 }
 
 int seer_stream_copy(void *dst, const void *src, size_t n_words, void *stream)

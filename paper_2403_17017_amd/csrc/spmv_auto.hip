@@ -1,0 +1,189 @@
+// The whole runtime flow of Sec. III-B -- gather features, evaluate the decision tree,
+// run the chosen kernel -- as three launches with no host round trip in between:
+//
+//   1. features_select_kernel: the feature reduction; its last workgroup derives
+//      the feature vector on the device, walks the tree (handed over by value in
+//      the kernel arguments) and leaves the chosen kernel id in device memory;
+//   2. spmv_auto_kernel: one kernel that contains all four schedules; every
+//      workgroup reads the chosen id and runs that schedule's body (the grid is
+//      sized for the schedule that needs the most workgroups, the rest exit);
+//   3. spmv_auto_fixup_kernel: the merge-path carry fix-up; exits at once unless
+//      merge path was chosen.
+//
+// The host only enqueues; feature collection costs the reduction kernel itself
+// instead of a launch, a wait and a second launch.  The sequence has no host-side
+// dependency on device data, so it can be captured in a HIP graph.
+//
+// The derivation of the floating-point features repeats the host's, operation by
+// operation (exact integers, correctly rounded int -> fp64 conversions, one fp64
+// division, one rounding to fp32), so both give the same bits.
+#include "../../include/seer.h"
+#include "features_bodies.hiph"
+#include "spmv_bodies.hiph"
+
+namespace seer {
+
+// Correctly rounded (nearest-even) conversion of a 128-bit unsigned integer: keep
+// the top 64 bits, fold everything below into the lowest kept bit (sticky), convert
+// (64 -> 53 bits rounds once, and the sticky bit makes that the rounding of the
+// full number), scale back exactly.
+__device__ __forceinline__ double u128_to_double(unsigned __int128 n)
+{
+    const uint64_t hi = (uint64_t)(n >> 64);
+    if (hi == 0) return (double)(uint64_t)n;
+    const int s = 64 - __clzll((long long)hi);            // 1..64
+    uint64_t top = (uint64_t)(n >> s);
+    const unsigned __int128 below = n - ((unsigned __int128)top << s);
+    top |= (uint64_t)(below != 0);
+    return ldexp((double)top, s);
+}
+
+__device__ __forceinline__ void derive_features_device(
+    int64_t rows, int64_t cols, int64_t nnz, int64_t max_len, int64_t min_len, int64_t empty,
+    uint64_t sum_sq, float *f)
+{
+    for (int i = 0; i < SEER_NUM_FEATURES; ++i) f[i] = 0.0f;
+    f[SEER_F_COLS] = (float)(double)cols;
+    if (rows <= 0) return;
+    const double R = (double)rows;
+    const double mean = (double)nnz / R;
+    const unsigned __int128 num = (unsigned __int128)(uint64_t)rows * (unsigned __int128)sum_sq -
+                                  (unsigned __int128)(uint64_t)nnz * (unsigned __int128)(uint64_t)nnz;
+    const double var = u128_to_double(num) / (double)((uint64_t)rows * (uint64_t)rows);
+    f[SEER_F_ROWS] = (float)R;
+    f[SEER_F_NNZ] = (float)(double)nnz;
+    f[SEER_F_MEAN_LEN] = (float)mean;
+    f[SEER_F_MAX_LEN] = (float)(double)max_len;
+    f[SEER_F_MIN_LEN] = (float)(double)min_len;
+    f[SEER_F_VAR_LEN] = (float)var;
+    f[SEER_F_EMPTY_FRAC] = (float)((double)empty / R);
+    if (cols > 0) {
+        const double C = (double)cols;
+        f[SEER_F_MEAN_DENSITY] = (float)(mean / C);
+        f[SEER_F_MAX_DENSITY] = (float)((double)max_len / C);
+        f[SEER_F_MIN_DENSITY] = (float)((double)min_len / C);
+        f[SEER_F_VAR_DENSITY] = (float)(var / (C * C));
+    }
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kFeatWG) void features_select_kernel(
+    int rows, int cols, const int *__restrict__ rp, FeatPartial *__restrict__ part,
+    AutoSel *__restrict__ sel, const AutoTree tree)
+{
+    __shared__ FeatPartial s_part[kFeatWaves];
+    __shared__ int s_last;
+    __shared__ float s_f[SEER_NUM_FEATURES];
+    int32_t mx, mn;
+    uint64_t sq, em;
+    if (!features_reduce<VEC>(rows, rp, part, s_part, &s_last, mx, mn, sq, em)) return;
+    if (threadIdx.x == 0) {
+        // the feature vector lives in LDS so that the tree can index it without
+        // forcing it into private (scratch) memory
+        const int64_t nnz = (int64_t)rp[rows] - (int64_t)rp[0];
+        derive_features_device(rows, cols, nnz, mx, mn, (int64_t)em, sq, s_f);
+        int n = 0, k = SEER_CSR_MP;            // a malformed tree cannot get here (host checks); MP is the safe answer
+        for (int steps = 0; steps <= tree.n_nodes; ++steps) {
+            const int feature = tree.nodes[n].feature;
+            if (feature < 0) { k = tree.nodes[n].klass; break; }
+            n = ((double)s_f[feature] <= tree.nodes[n].threshold) ? tree.nodes[n].left : tree.nodes[n].right;
+        }
+        sel->kernel_id = (k >= 0 && k < SEER_NUM_KERNELS) ? k : SEER_CSR_MP;
+        sel->valid = 1;
+        sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
+        sel->max_len = mx; sel->min_len = mn;
+        sel->sum_sq = sq; sel->empty = em;
+#pragma unroll
+        for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
+        atomicExch(&g_feat_ticket, 0u);    // ready for the next call
+    }
+}
+
+static_assert(kFeatMaxBlocks * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(AutoSel) <= kAutoCarryOffset - kAutoSelOffset,
+              "workspace layout");
+
+constexpr int kAutoLds = mp_lds_words<kMpIptLarge>() > bm_lds_words<kBmChunk>() ? mp_lds_words<kMpIptLarge>()
+                                                                                 : bm_lds_words<kBmChunk>();
+
+template <int IPT, bool VEC>
+__global__ __launch_bounds__(kWG) void spmv_auto_kernel(
+    int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
+    const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
+    int *__restrict__ carry_row, float *__restrict__ carry_val, const AutoSel *__restrict__ sel,
+    const AutoShape shape, int remap)
+{
+    static_assert(mp_lds_words<IPT>() <= kAutoLds, "LDS overlay too small");
+    __shared__ int smem[kAutoLds];
+    const int k = sel->kernel_id;                           // same for the whole grid
+    const uint32_t n_tiles = shape.tiles[k];
+    const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
+    if (tile >= n_tiles) return;
+    if (k == SEER_CSR_TM) {
+        tm_body(rows, rp, ci, va, x, y, tile);
+    } else if (k == SEER_CSR_WM) {
+        switch (shape.wm_lanes) {
+        case 2: wm_body<2>(rows, rp, ci, va, x, y, tile); break;
+        case 4: wm_body<4>(rows, rp, ci, va, x, y, tile); break;
+        case 8: wm_body<8>(rows, rp, ci, va, x, y, tile); break;
+        case 16: wm_body<16>(rows, rp, ci, va, x, y, tile); break;
+        case 32: wm_body<32>(rows, rp, ci, va, x, y, tile); break;
+        default: wm_body<64>(rows, rp, ci, va, x, y, tile); break;
+        }
+    } else if (k == SEER_CSR_BM) {
+        bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
+                                     reinterpret_cast<float *>(smem));
+    } else {
+        mp_body<IPT, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile, smem);
+    }
+}
+
+__global__ __launch_bounds__(kWG) void spmv_auto_fixup_kernel(
+    int rows, uint32_t n_tiles, const int *__restrict__ carry_row, const float *__restrict__ carry_val,
+    float *__restrict__ y, const AutoSel *__restrict__ sel)
+{
+    if (sel->kernel_id != SEER_CSR_MP) return;
+    mp_fixup_body(rows, n_tiles, carry_row, carry_val, y);
+}
+
+size_t auto_workspace_bytes(int rows, int nnz)
+{
+    return kAutoCarryOffset + mp_workspace_bytes(rows, nnz, kMpIptSmall);
+}
+
+void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, void *workspace,
+                 hipStream_t st)
+{
+    char *ws = static_cast<char *>(workspace);
+    FeatPartial *part = reinterpret_cast<FeatPartial *>(ws);
+    AutoSel *sel = reinterpret_cast<AutoSel *>(ws + kAutoSelOffset);
+    const uint32_t n_mp = shape.tiles[SEER_CSR_MP];
+    const size_t one = ((size_t)n_mp * 4 + 255) & ~(size_t)255;
+    int *carry_row = reinterpret_cast<int *>(ws + kAutoCarryOffset);
+    float *carry_val = reinterpret_cast<float *>(ws + kAutoCarryOffset + one);
+
+    if ((reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0)
+        hipLaunchKernelGGL(features_select_kernel<true>, dim3(features_num_blocks(a.rows)), dim3(kFeatWG), 0, st,
+                           a.rows, a.cols, a.rp, part, sel, tree);
+    else
+        hipLaunchKernelGGL(features_select_kernel<false>, dim3(features_num_blocks(a.rows)), dim3(kFeatWG), 0, st,
+                           a.rows, a.cols, a.rp, part, sel, tree);
+
+    uint32_t grid = 0;
+    for (int k = 0; k < SEER_NUM_KERNELS; ++k) {
+        const uint32_t g = a.remap ? tiles_per_xcd(shape.tiles[k]) * kXCD : shape.tiles[k];
+        grid = g > grid ? g : grid;
+    }
+#define SEER_AUTO_LAUNCH(I, V)                                                                             \
+    hipLaunchKernelGGL((spmv_auto_kernel<I, V>), dim3(grid), dim3(kWG), 0, st, a.rows, a.nnz, a.rp, a.ci, \
+                       a.va, a.x, a.y, carry_row, carry_val, sel, shape, a.remap)
+    if (shape.mp_ipt == kMpIptSmall) {
+        if (vec) SEER_AUTO_LAUNCH(kMpIptSmall, true); else SEER_AUTO_LAUNCH(kMpIptSmall, false);
+    } else {
+        if (vec) SEER_AUTO_LAUNCH(kMpIptLarge, true); else SEER_AUTO_LAUNCH(kMpIptLarge, false);
+    }
+#undef SEER_AUTO_LAUNCH
+    hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_mp + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
+                       carry_row, carry_val, a.y, sel);
+}
+
+} // namespace seer

@@ -1,0 +1,148 @@
+"""GPU parity of the asynchronous path (seer_spmv_auto): device-side feature
+derivation and tree walk must match the oracle bit for bit, and y must match both
+the oracle (tolerance) and seer_spmv with the same kernel id (bit for bit)."""
+import numpy as np
+import pytest
+
+import paper_2403_17017_amd as S
+from oracle import seer_oracle as O
+from workloads import csr_gen as G
+
+from gpu_util import announce, assert_features_equal, assert_parity, oracle_of, run_spmv, upload
+from test_gpu_parity import ALL
+
+pytestmark = pytest.mark.gpu
+
+# var_len <= 50 ? (mean_len <= 8 ? (rows <= 20000 ? TM : BM) : WM) : MP
+REAL_TREE = ([6, 3, 0, -1, -1, -1, -1], [50.0, 8.0, 20000.0, 0, 0, 0, 0],
+             [1, 2, 3, -1, -1, -1, -1], [6, 5, 4, -1, -1, -1, -1], [-1, -1, -1, 0, 2, 1, 3])
+
+
+def run_auto(dA, tree, xd, rows, ws):
+    import torch
+    y = torch.full((max(rows, 1),), float("nan"), dtype=torch.float32, device="cuda:0")
+    S.seer_spmv_auto(dA, tree, xd, y, ws)
+    f, kid = S.seer_spmv_auto_result(ws)
+    return y[:rows].cpu().numpy(), f, kid
+
+
+@pytest.fixture(scope="module")
+def cases():
+    out = []
+    for A in ALL:
+        x = G.dense_vector(A.cols, 1000 + len(out))
+        y_ref, bound = oracle_of(A, x)
+        out.append((A, x, y_ref, bound))
+    return out
+
+
+@pytest.mark.parametrize("forced", [0, 1, 2, 3, "tree"])
+def test_auto_matches_oracle_and_three_call_path(cases, forced):
+    import torch
+    tree = S.Tree(*REAL_TREE) if forced == "tree" else S.Tree.constant(forced)
+    for A, x, y_ref, bound in cases:
+        announce(f"auto path tree={forced} {A.name} rows={A.rows} nnz={A.nnz}")
+        dA = upload(A)
+        xd = torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        y, f, kid = run_auto(dA, tree, xd, A.rows, ws)
+        want_f = O.features(A.rows, A.cols, A.row_ptr)
+        assert_features_equal(f, want_f, f"auto features {A.name}")
+        assert kid == O.select(want_f["f"], *tree.arrays)
+        assert_parity(y, y_ref, bound, f"auto (kernel {kid}) on {A.name}")
+        y3 = run_spmv(kid, dA, xd, A.rows)
+        assert y.tobytes() == y3.tobytes(), f"auto and seer_spmv({kid}) differ on {A.name}"
+        # and the three-call path agrees on the features and the id
+        f3 = S.seer_features(dA)
+        assert f3.vector().tobytes() == f.vector().tobytes() and S.seer_select(f3, tree) == kid
+
+
+def test_auto_misaligned_and_repeated(cases):
+    import torch
+    tree = S.Tree(*REAL_TREE)
+    for A, x, y_ref, bound in cases:
+        if A.nnz == 0:
+            continue
+        dA = upload(A, misalign=True)
+        xd = torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        announce(f"auto path misaligned {A.name}")
+        for _ in range(3):   # the ticket counter must come back to zero every time
+            y, f, kid = run_auto(dA, tree, xd, A.rows, ws)
+            assert_parity(y, y_ref, bound, f"auto misaligned on {A.name}")
+
+
+def test_auto_in_a_hip_graph(cases):
+    """The whole path captured once and replayed, with eager work between replays."""
+    import torch
+    tree = S.Tree(*REAL_TREE)
+    picks = [c for c in cases if c[0].name.startswith(("zipf1.6_20011", "laplace5_100", "unif0-40"))]
+    for A, x, y_ref, bound in picks:
+        dA = upload(A)
+        xd = torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_auto(dA, tree, xd, y, ws)
+        torch.cuda.synchronize()
+        eager = y.clone()
+        announce(f"auto path graph capture {A.name}")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            S.seer_spmv_auto(dA, tree, xd, y, ws)
+        for rep in range(4):
+            y.fill_(float("nan"))                       # eager work between replays
+            _ = S.seer_features(dA)                     # shares nothing with the graph but the device
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, eager), f"replay {rep} differs on {A.name}"
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"graph replay on {A.name}")
+
+
+def test_auto_status_codes():
+    import torch
+    A = G.random_lengths(1000, 500, 0, 9, 3)
+    dA = upload(A)
+    xd = torch.zeros(500, device="cuda:0")
+    y = torch.zeros(1000, device="cuda:0")
+    ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+    cyc = S.Tree([0, 0, -1], [1e30, 1e30, 0], [1, 0, -1], [2, 2, -1], [-1, -1, 0])
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_auto(dA, cyc, xd, y, ws)
+    assert ei.value.status == -3
+    big = S.Tree([0] * 127 + [-1] * 128, [1.0] * 255, list(range(1, 128)) + [-1] * 128,
+                 list(range(128, 255)) + [-1] * 128, [-1] * 127 + [0] * 128)
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_auto(dA, big, xd, y, ws)
+    assert ei.value.status == -3
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_auto(dA, S.Tree.constant(2), xd, y, torch.empty(64, dtype=torch.uint8, device="cuda:0"))
+    assert ei.value.status == -4
+    fresh = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(S.SeerError):
+        S.seer_spmv_auto_result(fresh)        # nothing has selected into this workspace
+
+
+def test_auto_wide_integer_features():
+    """rows * sum(len^2) beyond 2^64: the device's 128-bit variance numerator and its
+    conversion to fp64 against exact Python integers (all values 1, x = 1, so y = len)."""
+    import torch
+    rows, long_rows, L = 20_000, 1_000, 1_000_000
+    lens = np.zeros(rows, np.int64)
+    lens[::20] = L
+    assert int(lens.sum()) == long_rows * L < 2**31 and rows * int((lens**2).sum()) > 2**64
+    rp = np.zeros(rows + 1, np.int64)
+    rp[1:] = np.cumsum(lens)
+    nnz = int(rp[-1])
+    dA = S.DeviceCSR(rows, 64, torch.from_numpy(rp.astype(np.int32)).cuda(),
+                     torch.zeros(nnz, dtype=torch.int32, device="cuda:0"),
+                     torch.ones(nnz, dtype=torch.float32, device="cuda:0"), nnz)
+    xd = torch.ones(64, device="cuda:0")
+    ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(rows, nnz))
+    want = O.features(rows, 64, rp.astype(np.int32))
+    for forced in (3, 2, 1):
+        announce(f"auto path wide integers, kernel {forced}, nnz={nnz}")
+        y, f, kid = run_auto(dA, S.Tree.constant(forced), xd, rows, ws)
+        assert kid == forced
+        assert_features_equal(f, want, "wide-integer features (device)")
+        assert np.array_equal(y, lens.astype(np.float32))
+    assert_features_equal(S.seer_features(dA), want, "wide-integer features (host derivation)")
