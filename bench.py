@@ -2,16 +2,19 @@
 """Benchmark of the Seer SpMV hot path on one MI355X.
 
 One step = one pass of the whole path over one matrix that is already resident in
-HBM: seer_features (reduction kernel + wait), seer_select (tree walk on the host),
-seer_spmv with the selected schedule.  The matrix is BASELINE config 2 (5-point
-Laplacian on a 1024 x 1024 grid).  Because that matrix (54 MB) fits the 256 MB
-last-level cache, the step rotates through enough independent copies of (A, x, y)
-to exceed 1 GiB, so every launch streams its operands from HBM.
+HBM: gather the features of the matrix, walk the decision tree, run the SpMV schedule
+it names -- seer_spmv_auto, which does all three on the device, enqueued back to
+back.  The matrix is BASELINE config 2 (5-point Laplacian on a 1024 x 1024 grid).
+Because that matrix (54 MB) fits the 256 MB last-level cache, the step rotates
+through enough independent copies of (A, x, y) to exceed 1 GiB, so every launch
+streams its operands from HBM.
 
 Prints ONE JSON line.  value = model bytes per step / wall time per step, with
-model bytes = 8 nnz + 4 (rows + 1) + 4 cols + 4 rows.  The `roofline` object
-prices the SpMV kernel alone (HIP events around each launch in the timed region)
-against the 8 TB/s HBM peak; `cpu_baseline` is the CPU oracle on the same matrix.
+model bytes = 8 nnz + 4 (rows + 1) + 4 cols + 4 rows.  The `roofline` object prices
+the selected SpMV kernel alone against the 8 TB/s HBM peak; `cpu_baseline` is the CPU
+oracle on the same matrix; `extras` holds the same step through the three separate
+calls (seer_features / seer_select / seer_spmv, host in the loop), every fixed
+schedule cold and warm, and the selector measured on held-out sweep matrices.
 """
 from __future__ import annotations
 
@@ -30,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0
 METRIC = "SpMV achieved HBM GB/s (% of peak) + selected-vs-best-single-kernel speedup"
 COLD_BYTES = 1 << 30
 CAL_WORDS = 1 << 26   # the calibration copy moves 256 MiB in and 256 MiB out
-TREE_PATH = os.path.join(ROOT, "paper_2403_17017_amd", "selector_tree.json")
+MODEL_PATH = os.path.join(ROOT, "paper_2403_17017_amd", "selector_model.json")
 
 
 def make_workload(name: str):
@@ -50,15 +53,17 @@ def make_workload(name: str):
     raise SystemExit(f"unknown workload {name}")
 
 
-def load_tree():
+def load_model():
+    """The shipped trees (known, gathered, classifier selection); a hand-written
+    gathered tree only if the trained file is missing."""
     import paper_2403_17017_amd as S
-    if os.path.exists(TREE_PATH):
-        with open(TREE_PATH) as fh:
-            t = json.load(fh)
-        return S.Tree(t["feature"], t["threshold"], t["left"], t["right"], t["klass"]), t.get("note", "trained")
-    # fallback tree used only until a trained one is shipped:
+    if os.path.exists(MODEL_PATH):
+        from paper_2403_17017_amd.training import load_model as _load
+        model, meta = _load(MODEL_PATH)
+        return model, meta, meta.get("note", "trained")
     # var_len <= 50 ? CSR,BM : CSR,MP
-    return S.Tree([6, -1, -1], [50.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 2, 3]), "hand-written default"
+    t = S.Tree([6, -1, -1], [50.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 2, 3])
+    return S.Model(t), {}, "hand-written default (no trained model file)"
 
 
 def load_traffic_summary(workload, kernel):
@@ -93,7 +98,7 @@ class Rotation:
         self.sets = []
         base = S.DeviceCSR.from_host(A)
         xb = torch.from_numpy(x).cuda()
-        ws_bytes = max(S.spmv_workspace_bytes(3, A.rows, A.nnz), S.features_workspace_bytes(A.rows))
+        ws_bytes = max(S.spmv_auto_workspace_bytes(A.rows, A.nnz), S.features_workspace_bytes(A.rows))
         for i in range(n):
             d = base if i == 0 else S.DeviceCSR(A.rows, A.cols, base.row_ptr.clone(), base.col_idx.clone(),
                                                 base.values.clone(), A.nnz)
@@ -171,6 +176,41 @@ def stream_copy_ceiling(nbytes=1 << 31, reps=10):
     return 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def selector_eval(model, meta, count):
+    """Selected-vs-best-single-kernel on held-out matrices of the sweep population,
+    every path timed on the GPU timeline (HIP graph replay, warm buffers)."""
+    import torch
+
+    import paper_2403_17017_amd as S
+    from paper_2403_17017_amd import training as T
+    from workloads.sweep_gen import build_on_device, sweep_spec
+    tk, ta, tm = [], [], []
+    for m in meta["test_matrices"][:count]:
+        spec = sweep_spec(m)
+        rp, ci, va, x = build_on_device(spec)
+        dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(dA.rows, dA.nnz))
+        y = torch.empty(dA.rows, device="cuda:0")
+        tk.append([T.time_kernel_us(k, dA, x, y, ws) for k in range(S.NUM_KERNELS)])
+        ta.append(T.time_graph_us(lambda: S.seer_spmv_auto(dA, model.gathered, x, y, ws)))
+        tm.append(T.time_graph_us(lambda: S.seer_spmv_model(dA, model, x, y, ws)))
+        del rp, ci, va, x, dA, y, ws
+    import numpy as np
+    tk, ta, tm = np.array(tk), np.array(ta), np.array(tm)
+    fixed = tk.sum(axis=0)
+    best = int(np.argmin(fixed))
+    geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
+    return {
+        "matrices": len(tk), "best_fixed_kernel": S.kernel_name(best),
+        "t_fixed_us": [round(float(v), 1) for v in fixed], "t_oracle_us": round(float(tk.min(axis=1).sum()), 1),
+        "t_always_gather_us": round(float(ta.sum()), 1), "t_classifier_selection_us": round(float(tm.sum()), 1),
+        "aggregate_speedup_vs_best_fixed": {"always_gather": round(float(fixed[best] / ta.sum()), 4),
+                                            "classifier_selection": round(float(fixed[best] / tm.sum()), 4)},
+        "per_matrix_geomean_vs_best_fixed": {"always_gather": round(geo(tk[:, best], ta), 4),
+                                             "classifier_selection": round(geo(tk[:, best], tm), 4)},
+    }
+
+
 def cpu_baseline(A, x, tree, budget_s=10.0):
     """The oracle's whole step (features, tree walk, SpMV) on the host, single thread."""
     from oracle import seer_oracle as O
@@ -208,6 +248,8 @@ def main():
     ap.add_argument("--workload", default="laplace5_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel table and copy ceiling")
+    ap.add_argument("--selector-matrices", type=int, default=60,
+                    help="held-out sweep matrices for the selector figures in extras (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
@@ -226,18 +268,19 @@ def main():
     mb = model_bytes(A.rows, A.cols, A.nnz)
     n_sets = max(1, math.ceil(COLD_BYTES / mb)) + 1
     rot = Rotation(A, x, n_sets)
-    tree, tree_note = load_tree()
+    model, model_meta, tree_note = load_model()
+    tree = model.gathered
 
-    def step(i, ev=None):
+    def step(i):
+        d, xd, y, ws = rot[i]
+        S.seer_spmv_auto(d, tree, xd, y, ws)
+
+    def three_call_step(i):
         d, xd, y, ws = rot[i]
         f = S.seer_features(d, workspace=ws)
-        kid = S.seer_select(f, tree)
-        if ev is not None:
-            ev[0].record()
-        S.seer_spmv(kid, d, xd, y, workspace=ws)
-        if ev is not None:
-            ev[1].record()
-        return kid
+        k = S.seer_select(f, tree)
+        S.seer_spmv(k, d, xd, y, workspace=ws)
+        return k
 
     # one plain copy of known size first: the calibration dispatch for byte counters
     cal_src = torch.empty(CAL_WORDS, dtype=torch.float32, device="cuda:0").normal_()
@@ -247,24 +290,20 @@ def main():
     del cal_src, cal_dst
 
     for i in range(args.warmup):
-        kid = step(i)
-    torch.cuda.synchronize()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+        step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        kid = step(args.warmup + i, events[i])
+        step(args.warmup + i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    spmv_us_in_step = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in events)
     value = mb / (ms_per_step * 1e-3) / 1e9
+    f_dev, kid = S.seer_spmv_auto_result(rot[args.warmup + args.steps - 1][3])
 
-    # Duration of the dominant kernel (the selected SpMV schedule): the same K launches
-    # on the same rotating copies, replayed from one HIP graph between two HIP events,
-    # so that the figure is kernel time and not the host's launch latency (which the
-    # per-step events above include, because the stream is idle when each step starts).
+    # Duration of the dominant kernel (the selected SpMV schedule): the same number of
+    # launches on the same rotating copies, replayed from one HIP graph between two HIP
+    # events, so that the figure is kernel time, free of launch gaps.
     spmv_avg_us = time_spmv_graph(kid, rot, args.steps)
     achieved = mb / (spmv_avg_us * 1e-6) / 1e9
     traffic = load_traffic_summary(args.workload, S.kernel_name(kid))
@@ -274,7 +313,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{A.name}: {A.rows}x{A.cols} CSR, nnz={A.nnz}, fp32 values, int32 indices"
                                + (" (BASELINE config 2)" if args.workload == "laplace5_1024" else ""),
-                   "step": "seer_features + seer_select + seer_spmv(selected)",
+                   "step": "seer_spmv_auto = feature reduction + tree walk on the device + selected SpMV, "
+                           "steps enqueued back to back",
                    "model_bytes_per_step": mb, "cache_protocol": f"cold: rotates {n_sets} copies of (A,x,y), "
                    f"{n_sets * mb / 2**30:.2f} GiB", "selected_kernel": S.kernel_name(kid), "tree": tree_note},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -282,8 +322,7 @@ def main():
                      "kernel": S.kernel_name(kid), "avg_launch_us": round(spmv_avg_us, 3),
                      "how": f"{args.steps} launches of the selected kernel on the rotating cold copies, "
                             "one HIP graph replay bracketed by HIP events",
-                     "algorithmic_bytes_per_launch": mb,
-                     "in_step_event_us_median": round(spmv_us_in_step[len(spmv_us_in_step) // 2], 3)},
+                     "algorithmic_bytes_per_launch": mb},
     }
 
     if not args.no_extras:
@@ -296,14 +335,30 @@ def main():
             extras["per_kernel_warm_us"][S.kernel_name(k)] = round(w, 2)
         best = min(extras["per_kernel_cold_us"].values())
         extras["best_fixed_kernel_cold_gbps"] = round(mb / (best * 1e-6) / 1e9, 1)
-        # features alone
+        # the same step with the host in the loop: three calls, one wait
+        for i in range(10):
+            three_call_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(100):
+            three_call_step(i)
+        torch.cuda.synchronize()
+        extras["three_call_step_us"] = round((time.perf_counter() - t0) / 100 * 1e6, 2)
         t0 = time.perf_counter()
         for i in range(50):
             d, xd, y, ws = rot[i]
             S.seer_features(d, workspace=ws)
         extras["features_call_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 2)
+        # the classifier-selection path on this matrix (may skip gathering)
+        d, xd, y, ws = rot[0]
+        path, k_known = S.seer_spmv_model(d, model, xd, y, ws)
+        extras["classifier_selection_on_this_matrix"] = {
+            "path": "gathered" if path == 1 else "known",
+            "kernel": S.kernel_name(S.seer_spmv_auto_result(ws)[1] if path == 1 else k_known)}
         del warm
         extras["stream_copy_ceiling_gbps"] = round(stream_copy_ceiling(), 1)
+        if model_meta.get("test_matrices") and args.selector_matrices > 0:
+            extras["selector_on_held_out_matrices"] = selector_eval(model, model_meta, args.selector_matrices)
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

@@ -122,9 +122,12 @@ size_t seer_features_workspace_bytes(int32_t rows);
  * and min_len > max_len.  HOST only. */
 int seer_derive_features(seer_features_t *io);
 
-/* Fills out->f[] (and the three known integers) from rows, cols, nnz alone, with
- * the gathered entries set to 0: the input of a "known features" model (Sec. III-A),
- * which costs nothing at run time.  HOST only, no GPU work. */
+/* Fills out->f[] from rows, cols, nnz alone: the input of a "known features" model
+ * (Sec. III-A), which costs nothing at run time.  Besides the three integers it sets
+ * the two statistics that follow from them without looking at the matrix,
+ * f[SEER_F_MEAN_LEN] = nnz / rows and f[SEER_F_MEAN_DENSITY] = nnz / rows / cols
+ * (same rounding rule as seer_features_t); every other gathered entry is 0.
+ * HOST only, no GPU work. */
 int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t *out);
 
 /* Tree inference (Sec. III-B: nested if/else over the input vector, yielding an
@@ -156,6 +159,28 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
 int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y,
                    void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_auto_workspace_bytes(int32_t rows, int32_t nnz);
+
+/* The three models of Sec. III-A.  `selector` is the classifier-selection model: it
+ * sees only the known features (seer_known_features) and answers 0 = "the known
+ * model is good enough" or 1 = "gather the features first".  `known` maps the known
+ * features to a kernel id, `gathered` maps the full feature vector to a kernel id.
+ * selector == NULL means: always gather.  All pointers HOST. */
+typedef struct {
+    const seer_tree *selector;
+    const seer_tree *known;
+    const seer_tree *gathered;
+} seer_model;
+
+/* Runtime inference with the classifier-selection model (Sec. III-B): the selector is
+ * evaluated on the host at no GPU cost; on 0 the known model's kernel is launched
+ * directly (seer_spmv), on 1 the features are gathered and the gathered model is
+ * applied on the device (seer_spmv_auto).  Asynchronous on `stream` either way.
+ * *path (may be NULL) receives 0 or 1; *kernel_id (may be NULL) receives the kernel id
+ * when the known model was used and -1 otherwise (ask seer_spmv_auto_result then).
+ * workspace: >= seer_spmv_auto_workspace_bytes(rows, nnz). */
+int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, float *y,
+                    void *workspace, size_t workspace_bytes, void *stream,
+                    int *path, int *kernel_id);
 
 /* Waits for `stream`, then reports what the last seer_spmv_auto that used `workspace`
  * decided: the features it gathered and the kernel id it ran (either may be NULL).

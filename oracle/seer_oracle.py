@@ -17,6 +17,10 @@ What it defines
                    empty rows.
   * select      -- decision-tree inference (Sec. III-B: nested if/else over the
                    feature vector, returning an integer class index).
+  * known_features, model_select -- the feature vector that costs nothing
+                   (Sec. III-A) and inference with the classifier-selection
+                   model that chooses between the known and the gathered model
+                   (Sec. III-B).
 
 Readings where the paper is silent (all listed again in the design document):
   * variance is the population variance (divide by rows);
@@ -154,6 +158,32 @@ def features(rows: int, cols: int, row_ptr) -> dict:
         f[1] = _f32(float(cols))
     out["f"] = f
     return out
+
+
+def known_features(rows: int, cols: int, nnz: int) -> np.ndarray:
+    """The feature vector of a known-features model (Sec. III-A: rows, columns and
+    nonzeros come with the dataset at no cost).  The mean row length and mean row
+    density follow from those three numbers alone, so they are known as well; every
+    entry that needs a look at the matrix stays 0."""
+    f = np.zeros(NUM_FEATURES, dtype=np.float32)
+    f[0] = _f32(float(rows)); f[1] = _f32(float(cols)); f[2] = _f32(float(nnz))
+    if rows > 0:
+        mean64 = float(nnz) / float(rows)
+        f[3] = _f32(mean64)
+        if cols > 0:
+            f[8] = _f32(mean64 / float(cols))
+    return f
+
+
+def model_select(rows, cols, nnz, f_gathered, selector, known, gathered):
+    """Classifier-selection inference (Sec. III-B).  Each tree is a 5-tuple of parallel
+    arrays; selector may be None (always gather).  Returns (path, kernel id) with
+    path 0 = known model, 1 = gathered model."""
+    if selector is not None:
+        kf = known_features(rows, cols, nnz)
+        if select(kf, *selector) == 0:
+            return 0, select(kf, *known)
+    return 1, select(f_gathered, *gathered)
 
 
 def select(f, feature, threshold, left, right, klass) -> int:

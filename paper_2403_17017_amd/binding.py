@@ -56,10 +56,17 @@ class seer_node(C.Structure):
                 ("klass", C.c_int32), ("threshold", C.c_double)]
 
 
+class seer_model(C.Structure):
+    pass
+
+
 class seer_tree(C.Structure):
     _fields_ = [("n_nodes", C.c_int32), ("n_features", C.c_int32), ("n_classes", C.c_int32),
                 ("nodes", C.POINTER(seer_node))]
 
+
+seer_model._fields_ = [("selector", C.POINTER(seer_tree)), ("known", C.POINTER(seer_tree)),
+                       ("gathered", C.POINTER(seer_tree))]
 
 _lib = None
 
@@ -94,6 +101,9 @@ def lib():
         L.seer_spmv_auto_workspace_bytes.restype = sz
         L.seer_spmv_auto_result.argtypes = [vp, vp, C.POINTER(seer_features_t), C.POINTER(C.c_int)]
         L.seer_spmv_auto_result.restype = C.c_int
+        L.seer_spmv_model.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_model), vp, vp, vp, sz, vp,
+                                      C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.seer_spmv_model.restype = C.c_int
         L.seer_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.seer_set_tuning.restype = C.c_int
         L.seer_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -290,3 +300,26 @@ def seer_spmv_auto_result(workspace, stream=None):
     if rc:
         raise SeerError(rc, "seer_spmv_auto_result")
     return f, int(k.value)
+
+
+class Model:
+    """The three trees of the classifier-selection scheme (selector may be None)."""
+
+    def __init__(self, gathered: Tree, known: Tree = None, selector: Tree = None):
+        self.gathered, self.known, self.selector = gathered, known, selector
+        self.c = seer_model(C.pointer(selector.c) if selector is not None else None,
+                            C.pointer(known.c) if known is not None else None,
+                            C.pointer(gathered.c))
+
+
+def seer_spmv_model(A: DeviceCSR, model: Model, x, y, workspace, stream=None):
+    """Classifier-selection inference; returns (path, kernel_id): path 0 = known model
+    (kernel_id valid), 1 = features gathered on the device (kernel_id -1)."""
+    cs = A.c_struct()
+    path, kid = C.c_int(-1), C.c_int(-1)
+    rc = lib().seer_spmv_model(C.byref(cs), C.byref(model.c), x.data_ptr(), y.data_ptr(),
+                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream),
+                               C.byref(path), C.byref(kid))
+    if rc:
+        raise SeerError(rc, "seer_spmv_model")
+    return int(path.value), int(kid.value)

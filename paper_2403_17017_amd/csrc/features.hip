@@ -22,7 +22,7 @@ __global__ __launch_bounds__(kFeatWG) void features_kernel(
         *mailbox = r;
         __threadfence_system();            // the statistics land before the sequence number
         *reinterpret_cast<volatile uint64_t *>(&mailbox->seq) = seq;
-        atomicExch(&g_feat_ticket, 0u);    // ready for the next call
+        if (gridDim.x > 1) atomicExch(&g_feat_ticket, 0u);    // ready for the next call
     }
 }
 

@@ -271,6 +271,11 @@ int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t
     o.f[SEER_F_ROWS] = (float)(double)rows;
     o.f[SEER_F_COLS] = (float)(double)cols;
     o.f[SEER_F_NNZ] = (float)(double)nnz;
+    if (rows > 0) {
+        const double mean = (double)nnz / (double)rows;
+        o.f[SEER_F_MEAN_LEN] = (float)mean;
+        if (cols > 0) o.f[SEER_F_MEAN_DENSITY] = (float)(mean / (double)cols);
+    }
     *out = o;
     return SEER_OK;
 }
@@ -387,6 +392,38 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     launch_auto(a, dt, sh, vec, workspace, static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, float *y, void *workspace,
+                    size_t workspace_bytes, void *stream, int *path, int *kernel_id)
+{
+    if (!A || !model || !model->gathered) return SEER_EINVAL;
+    if (model->selector && !model->known) return SEER_EINVAL;
+    if (A->rows < 0 || A->cols < 0 || A->nnz < 0) return SEER_EINVAL;
+    int use_gathered = 1;
+    int kid = -1;
+    if (model->selector) {
+        seer_features_t kf;
+        int rc = seer_known_features(A->rows, A->cols, A->nnz, &kf);
+        if (rc != SEER_OK) return rc;
+        if (model->selector->n_classes > 2) return SEER_ETREE;
+        rc = seer_select(&kf, model->selector, &use_gathered);
+        if (rc != SEER_OK) return rc;
+        if (!use_gathered) {
+            if (model->known->n_classes > SEER_NUM_KERNELS) return SEER_ETREE;
+            rc = seer_select(&kf, model->known, &kid);
+            if (rc != SEER_OK) return rc;
+        }
+    }
+    if (A->rows > 0 && (!workspace || !aligned16(workspace) ||
+                        workspace_bytes < auto_workspace_bytes(A->rows, A->nnz)))
+        return SEER_EWORKSPACE;
+    const int rc = use_gathered ? seer_spmv_auto(A, model->gathered, x, y, workspace, workspace_bytes, stream)
+                                : seer_spmv(kid, A, x, y, workspace, workspace_bytes, stream);
+    if (rc != SEER_OK) return rc;
+    if (path) *path = use_gathered;
+    if (kernel_id) *kernel_id = kid;
+    return SEER_OK;
 }
 
 int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *features, int *kernel_id)

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
         sel->sum_sq = sq; sel->empty = em;
 #pragma unroll
         for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
-        atomicExch(&g_feat_ticket, 0u);    // ready for the next call
+        if (gridDim.x > 1) atomicExch(&g_feat_ticket, 0u);    // ready for the next call
     }
 }
 

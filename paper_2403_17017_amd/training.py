@@ -1,12 +1,17 @@
 """Training side of the selector (Sec. III-A and III-D of the Seer paper): benchmark
 every SpMV schedule and the feature collection on a representative population, label
-each matrix with its fastest schedule, fit a CART decision tree (scikit-learn, Gini,
-depth-capped, 80/20 split, no hyper-parameter tuning) and store it as the flat node
-array `seer_select` walks.
+each matrix with its fastest schedule, and fit the three CART decision trees of the
+training abstraction (scikit-learn, Gini, depth-capped, 80/20 split, no
+hyper-parameter tuning): the known-features model, the gathered-features model, and
+the classifier-selection model that decides, from the known features alone, whether
+gathering is worth its cost.  The trees are stored as the flat node arrays that
+`seer_select` / `seer_spmv_auto` / `seer_spmv_model` walk.
 
     python -m paper_2403_17017_amd.training sweep --count 1000 --out gpurun_out/sweep.csv
     python -m paper_2403_17017_amd.training fit --csv gpurun_out/sweep.csv \
-           --out paper_2403_17017_amd/selector_tree.json
+           --out paper_2403_17017_amd/selector_model.json
+    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv \
+           --model paper_2403_17017_amd/selector_model.json --out gpurun_out/eval.csv
 
 Timing protocol as in Sec. IV-B: 10 warm-up runs, mean of 10 timed runs, on the same
 buffers; the timed runs are replayed from a HIP graph so that kernel time, not host
@@ -28,7 +33,9 @@ from . import binding as S
 
 MAX_DEPTH = 6   # fixed before looking at any test data (the paper caps depth, value unstated)
 CSV_FIELDS = (["m", "family", "rows", "cols", "nnz"] + [f"f_{n}" for n in S.FEATURE_NAMES]
-              + ["t_features_us"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)] + ["max_disagreement"])
+              + ["t_features_us"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)]
+              + ["t_auto_mp_us", "max_disagreement"])
+KNOWN_IDX = [0, 1, 2, 3, 8]   # rows, cols, nnz, mean_len, mean_density: what seer_known_features fills
 
 
 def time_kernel_us(kid, dA, x, y, ws, warmup=10, reps=10):
@@ -40,6 +47,26 @@ def time_kernel_us(kid, dA, x, y, ws, warmup=10, reps=10):
     with torch.cuda.graph(g):
         for _ in range(reps):
             S.seer_spmv(kid, dA, x, y, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def time_graph_us(enqueue, warmup=3, reps=10):
+    """Mean time of `enqueue()` (which only enqueues GPU work) replayed from a HIP graph."""
+    import torch
+    for _ in range(warmup):
+        enqueue()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(reps):
+            enqueue()
+    g.replay()
+    torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     g.replay()
@@ -64,7 +91,7 @@ def measure_matrix(spec, device="cuda:0"):
     from workloads.sweep_gen import build_on_device
     rp, ci, va, x = build_on_device(spec, device)
     dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
-    ws = S.alloc_workspace(max(S.spmv_workspace_bytes(S.CSR_MP, dA.rows, dA.nnz),
+    ws = S.alloc_workspace(max(S.spmv_auto_workspace_bytes(dA.rows, dA.nnz),
                                S.features_workspace_bytes(dA.rows)), device)
     t_feat, f = time_features_us(dA, ws)
     row = {"m": spec.m, "family": spec.family, "rows": dA.rows, "cols": dA.cols, "nnz": dA.nnz,
@@ -76,6 +103,10 @@ def measure_matrix(spec, device="cuda:0"):
         y = torch.empty(dA.rows, device=device)
         row[f"t_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
         ys.append(y)
+    # the asynchronous path with a constant tree: its excess over the bare kernel is the
+    # device-side cost of gathering and selecting
+    mp_only = S.Tree.constant(S.CSR_MP)
+    row["t_auto_mp_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, mp_only, x, ys[3], ws)), 3)
     # the schedules must agree with each other (a sanity check, not the parity test)
     scale = float(ys[3].abs().max().item()) + 1e-30
     row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item() for k in range(3)) / scale)
@@ -113,6 +144,19 @@ def load_csv(path):
     T = np.array([[float(r[f"t_k{k}_us"]) for k in range(S.NUM_KERNELS)] for r in rows])
     tf = np.array([float(r["t_features_us"]) for r in rows])
     return rows, X, T, tf
+
+
+def gather_overhead_us(rows_csv, T):
+    """Device-side cost of gathering + selecting per matrix, from the sweep: the excess
+    of the asynchronous path (constant merge-path tree) over the bare merge-path
+    kernel, smoothed by a least-squares line in the number of rows (single timings of
+    millisecond kernels are noisier than the few microseconds being estimated)."""
+    r = np.array([float(x["rows"]) for x in rows_csv])
+    d = np.array([float(x["t_auto_mp_us"]) for x in rows_csv]) - T[:, S.CSR_MP]
+    keep = T[:, S.CSR_MP] < 200.0            # short kernels give clean differences
+    A = np.stack([np.ones(keep.sum()), r[keep]], axis=1)
+    (a, b), *_ = np.linalg.lstsq(A, d[keep], rcond=None)
+    return np.maximum(a + b * r, 1.0), (float(a), float(b))
 
 
 def tree_to_arrays(clf):
@@ -158,25 +202,176 @@ def selector_report(T, tf, pred, t_select_us=0.2):
     }
 
 
-def fit_tree(csv_path, out_json, test_frac=0.2, seed=0):
-    from sklearn.model_selection import train_test_split
+def _fit(X, y, cols=None, weight=None):
     from sklearn.tree import DecisionTreeClassifier
+    Xs = X if cols is None else X[:, cols]
+    clf = DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0).fit(Xs, y, sample_weight=weight)
+    tree = tree_to_arrays(clf)
+    if cols is not None:   # the stored tree indexes the full 12-entry vector
+        tree["feature"] = [cols[f] if f >= 0 else -1 for f in tree["feature"]]
+    assert np.array_equal(predict_with_arrays(tree, X), clf.predict(Xs))
+    return tree
+
+
+def model_report(T, ovh, pred_known, pred_gath, use_gath):
+    """Aggregate times in the paper's sense (Sec. IV-D).  'oracle' = best kernel per
+    matrix; the gathered model pays the device-side gathering cost on every matrix,
+    the classifier-selection model only where the selector says so."""
+    idx = np.arange(len(T))
+    t_known = T[idx, pred_known]
+    t_gath = T[idx, pred_gath] + ovh
+    t_model = np.where(use_gath == 1, t_gath, t_known)
+    t_fixed = T.sum(axis=0)
+    best = int(np.argmin(t_fixed))
+    truth = T.argmin(axis=1)
+    geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
+    return {
+        "matrices": int(len(T)),
+        "accuracy": {"known": float(np.mean(pred_known == truth)), "gathered": float(np.mean(pred_gath == truth)),
+                     "classifier_selection": float(np.mean(np.where(use_gath == 1, pred_gath, pred_known) == truth))},
+        "gathered_fraction": float(np.mean(use_gath)),
+        "t_us": {"known": float(t_known.sum()), "gathered": float(t_gath.sum()),
+                 "classifier_selection": float(t_model.sum()), "oracle": float(T.min(axis=1).sum()),
+                 "fixed": [float(v) for v in t_fixed]},
+        "best_fixed_kernel": best,
+        "aggregate_speedup_vs_best_fixed": {"known": float(t_fixed[best] / t_known.sum()),
+                                            "gathered": float(t_fixed[best] / t_gath.sum()),
+                                            "classifier_selection": float(t_fixed[best] / t_model.sum())},
+        "per_matrix_geomean_vs_best_fixed": {"known": geo(T[:, best], t_known), "gathered": geo(T[:, best], t_gath),
+                                             "classifier_selection": geo(T[:, best], t_model)},
+        "geomean_over_fixed_kernels_of_aggregate_speedup": float(np.exp(np.mean(np.log(t_fixed / t_model.sum())))),
+        "time_lost_vs_oracle": float(t_model.sum() / T.min(axis=1).sum()),
+    }
+
+
+def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
+    from sklearn.model_selection import train_test_split
     rows, X, T, tf = load_csv(csv_path)
-    y = T.argmin(axis=1)            # ties -> lowest kernel id
+    y = T.argmin(axis=1)            # label = fastest kernel; ties -> lowest kernel id
     idx = np.arange(len(rows))
     tr, te = train_test_split(idx, test_size=test_frac, random_state=seed)
-    clf = DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0).fit(X[tr], y[tr])
-    tree = tree_to_arrays(clf)
-    assert np.array_equal(predict_with_arrays(tree, X), clf.predict(X))
-    report = {"train": selector_report(T[tr], tf[tr], clf.predict(X[tr])),
-              "test": selector_report(T[te], tf[te], clf.predict(X[te])),
-              "all": selector_report(T, tf, clf.predict(X))}
-    tree.update({"note": f"CART gini max_depth={MAX_DEPTH}, {len(tr)} training matrices",
-                 "feature_names": list(S.FEATURE_NAMES), "n_classes": S.NUM_KERNELS,
-                 "label_counts": np.bincount(y, minlength=S.NUM_KERNELS).tolist(), "report": report})
+    ovh, ovh_fit = gather_overhead_us(rows, T)
+    Xk = np.zeros_like(X)
+    Xk[:, KNOWN_IDX] = X[:, KNOWN_IDX]          # what the known-features vector looks like at run time
+    gathered = _fit(X[tr], y[tr])
+    # The known model sees too little to tell a skewed matrix from a regular one; there a
+    # wrong guess costs orders of magnitude, so each training matrix counts by the mean
+    # time lost over the wrong choices (the paper scores models by runtime lost, Sec. IV-C).
+    regret = T.mean(axis=1) - T.min(axis=1) + 1e-3
+    known = _fit(Xk[tr], y[tr], KNOWN_IDX, weight=regret[tr])
+    pk, pg = predict_with_arrays(known, Xk), predict_with_arrays(gathered, X)
+    # Classifier selection: gather exactly where it pays.  The two models are judged on
+    # training matrices they were not fitted on (5-fold out-of-fold predictions);
+    # judged on their own training data they look better than they are and the selector
+    # would learn never to gather.
+    from sklearn.model_selection import cross_val_predict
+    from sklearn.tree import DecisionTreeClassifier
+    mk = lambda: DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0)
+    oof_k = cross_val_predict(mk(), Xk[tr][:, KNOWN_IDX], y[tr], cv=5, params={"sample_weight": regret[tr]})
+    oof_g = cross_val_predict(mk(), X[tr], y[tr], cv=5)
+    want_gather = np.zeros(len(rows), dtype=int)
+    t_if_gather, t_if_known = T[tr, oof_g] + ovh[tr], T[tr, oof_k]
+    want_gather[tr] = (t_if_gather < t_if_known).astype(int)
+    # each training matrix counts by the time that is at stake on it: a wrong "do not
+    # gather" on a skewed matrix costs milliseconds, a wrong "gather" a few microseconds
+    selector = _fit(Xk[tr], want_gather[tr], KNOWN_IDX, weight=np.abs(t_if_gather - t_if_known) + 1e-3)
+    if len(set(want_gather[tr])) == 1:          # a one-class fit stores that class as index 0
+        selector["klass"] = [int(want_gather[tr][0]) if k >= 0 else -1 for k in selector["klass"]]
+    ug = predict_with_arrays(selector, Xk)
+    model = {
+        "gathered": gathered, "known": known, "selector": selector,
+        "note": f"CART gini max_depth={MAX_DEPTH}, {len(tr)} training matrices",
+        "feature_names": list(S.FEATURE_NAMES), "known_features": KNOWN_IDX,
+        "gather_overhead_us": {"intercept": ovh_fit[0], "per_row": ovh_fit[1]},
+        "label_counts": np.bincount(y, minlength=S.NUM_KERNELS).tolist(),
+        "report": {"train": model_report(T[tr], ovh[tr], pk[tr], pg[tr], ug[tr]),
+                   "test": model_report(T[te], ovh[te], pk[te], pg[te], ug[te]),
+                   "all": model_report(T, ovh, pk, pg, ug)},
+        "test_matrices": [int(rows[i]["m"]) for i in te],
+    }
     with open(out_json, "w") as fh:
-        json.dump(tree, fh, indent=1)
-    return tree
+        json.dump(model, fh, indent=1)
+    return model
+
+
+def fit_tree(csv_path, out_json, test_frac=0.2, seed=0):
+    """Gathered-features tree only (kept for callers that want a single tree)."""
+    m = fit_model(csv_path, out_json, test_frac, seed)
+    t = dict(m["gathered"])
+    t["report"] = m["report"]
+    return t
+
+
+def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
+    """Runs the held-out matrices again and times, end to end on the GPU timeline (HIP
+    graph replay): every fixed kernel, the always-gather path (seer_spmv_auto) and the
+    classifier-selection path (seer_spmv_model)."""
+    import torch
+
+    from workloads.sweep_gen import build_on_device, sweep_spec
+    model, meta = load_model(model_json)
+    fields = ["m", "family", "rows", "nnz"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)] + \
+             ["t_auto_us", "t_model_us", "auto_kernel", "model_path", "model_kernel"]
+    with open(out_csv, "w", newline="") as fh:
+        w = csv.DictWriter(fh, fieldnames=fields)
+        w.writeheader()
+        for m in meta["test_matrices"]:
+            spec = sweep_spec(m)
+            rp, ci, va, x = build_on_device(spec)
+            dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
+            ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(dA.rows, dA.nnz))
+            y = torch.empty(dA.rows, device="cuda:0")
+            row = {"m": m, "family": spec.family, "rows": dA.rows, "nnz": dA.nnz}
+            for k in range(S.NUM_KERNELS):
+                row[f"t_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
+            row["t_auto_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, model.gathered, x, y, ws)), 3)
+            _, row["auto_kernel"] = S.seer_spmv_auto_result(ws)
+            row["t_model_us"] = round(time_graph_us(lambda: S.seer_spmv_model(dA, model, x, y, ws)), 3)
+            row["model_path"], row["model_kernel"] = S.seer_spmv_model(dA, model, x, y, ws)
+            if row["model_path"] == 1:
+                _, row["model_kernel"] = S.seer_spmv_auto_result(ws)
+            w.writerow(row)
+            fh.flush()
+            print(f"[eval] m={m} {spec.family} nnz={dA.nnz} kernels={[row[f't_k{k}_us'] for k in range(4)]} "
+                  f"auto={row['t_auto_us']} (k{row['auto_kernel']}) model={row['t_model_us']} "
+                  f"(path {row['model_path']}, k{row['model_kernel']})", file=log, flush=True)
+    return summarize_evaluation(out_csv)
+
+
+def summarize_evaluation(eval_csv):
+    with open(eval_csv) as fh:
+        rows = list(csv.DictReader(fh))
+    T = np.array([[float(r[f"t_k{k}_us"]) for k in range(S.NUM_KERNELS)] for r in rows])
+    ta = np.array([float(r["t_auto_us"]) for r in rows])
+    tm = np.array([float(r["t_model_us"]) for r in rows])
+    t_fixed = T.sum(axis=0)
+    best = int(np.argmin(t_fixed))
+    geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
+    return {
+        "matrices": len(rows), "t_fixed_us": [float(v) for v in t_fixed], "best_fixed_kernel": best,
+        "t_oracle_us": float(T.min(axis=1).sum()), "t_always_gather_us": float(ta.sum()),
+        "t_classifier_selection_us": float(tm.sum()),
+        "aggregate_speedup_vs_best_fixed": {"always_gather": float(t_fixed[best] / ta.sum()),
+                                            "classifier_selection": float(t_fixed[best] / tm.sum())},
+        "per_matrix_geomean_vs_best_fixed": {"always_gather": geo(T[:, best], ta),
+                                             "classifier_selection": geo(T[:, best], tm)},
+        "geomean_over_fixed_kernels_of_aggregate_speedup": float(np.exp(np.mean(np.log(t_fixed / tm.sum())))),
+        "time_lost_vs_oracle": {"always_gather": float(ta.sum() / T.min(axis=1).sum()),
+                                "classifier_selection": float(tm.sum() / T.min(axis=1).sum())},
+        "gathered_fraction": float(np.mean([int(r["model_path"]) for r in rows])),
+    }
+
+
+def _tree_from(d):
+    return S.Tree(d["feature"], d["threshold"], d["left"], d["right"], d["klass"])
+
+
+def load_model(path):
+    with open(path) as fh:
+        m = json.load(fh)
+    sel = _tree_from(m["selector"])
+    sel.c.n_classes = 2
+    return S.Model(_tree_from(m["gathered"]), _tree_from(m["known"]), sel), m
 
 
 def load_tree(path):
@@ -196,13 +391,19 @@ def main(argv=None):
     a.add_argument("--max-rows-exp", type=float, default=7.0)
     b = sub.add_parser("fit")
     b.add_argument("--csv", required=True)
-    b.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_tree.json"))
+    b.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
+    c = sub.add_parser("evaluate")
+    c.add_argument("--csv", required=True)
+    c.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
+    c.add_argument("--out", default="gpurun_out/eval.csv")
     args = ap.parse_args(argv)
     if args.cmd == "sweep":
         run_sweep(range(args.first, args.first + args.count), args.out, args.nnz_cap, args.max_rows_exp)
+    elif args.cmd == "fit":
+        m = fit_model(args.csv, args.out)
+        print(json.dumps(m["report"], indent=1))
     else:
-        t = fit_tree(args.csv, args.out)
-        print(json.dumps(t["report"], indent=1))
+        print(json.dumps(evaluate_model(args.csv, args.model, args.out), indent=1))
 
 
 if __name__ == "__main__":

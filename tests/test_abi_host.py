@@ -87,7 +87,16 @@ def test_derivation_extremes():
 def test_known_features():
     f = S.seer_known_features(1000, 2000, 30000)
     v = f.vector()
-    assert v[0] == 1000 and v[1] == 2000 and v[2] == 30000 and np.all(v[3:] == 0)
+    assert v[0] == 1000 and v[1] == 2000 and v[2] == 30000
+    assert v[3] == 30 and v[8] == np.float32(30 / 2000)
+    assert np.all(v[[4, 5, 6, 7, 9, 10, 11]] == 0)
+
+
+@settings(max_examples=300, deadline=None)
+@given(st.integers(0, 2**31 - 1), st.integers(0, 2**31 - 1), st.integers(0, 2**31 - 1))
+def test_known_features_bit_exact_vs_oracle(rows, cols, nnz):
+    got = S.seer_known_features(rows, cols, nnz).vector()
+    assert got.tobytes() == O.known_features(rows, cols, nnz).tobytes()
 
 
 def random_tree(rng, n_internal, n_classes=4):

@@ -164,3 +164,31 @@ def test_against_sklearn_predict(seed):
     want = clf.predict(allX)
     got = np.array([O.select(r, *arrs) for r in allX])
     assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- known features / model
+def test_known_features_are_the_free_part_of_the_gathered_vector():
+    # closed form (config 1) and agreement with the gathered vector wherever both are defined
+    k = O.known_features(4096, 4096, 65536)
+    assert (k[0], k[1], k[2], k[3]) == (4096, 4096, 65536, 16) and k[8] == np.float32(16 / 4096)
+    assert np.all(k[[4, 5, 6, 7, 9, 10, 11]] == 0)
+    for A in (G.laplacian_5pt(37), G.empty_poisson(5000, 300, 0.3, 4.0, seed=2), G.zipf_rows(3000, s=1.5, cap=500, seed=3)):
+        f = O.features(A.rows, A.cols, A.row_ptr)["f"]
+        k = O.known_features(A.rows, A.cols, A.nnz)
+        assert np.array_equal(k[[0, 1, 2, 3, 8]], f[[0, 1, 2, 3, 8]])
+    assert np.count_nonzero(O.known_features(0, 9, 0)) == 1
+
+
+def test_model_select_hand_cases():
+    # selector: rows <= 100 -> known model, else gather.  known: constant kernel 1.
+    # gathered: var_len <= 5 ? 2 : 3
+    selector = ([0, -1, -1], [100.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1])
+    known = ([-1], [0.0], [-1], [-1], [1])
+    gathered = ([6, -1, -1], [5.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 2, 3])
+    fg = np.zeros(12, np.float32)
+    fg[6] = 7.0
+    assert O.model_select(100, 50, 10, fg, selector, known, gathered) == (0, 1)
+    assert O.model_select(101, 50, 10, fg, selector, known, gathered) == (1, 3)
+    fg[6] = 5.0
+    assert O.model_select(101, 50, 10, fg, selector, known, gathered) == (1, 2)
+    assert O.model_select(5, 50, 10, fg, None, None, gathered) == (1, 2)

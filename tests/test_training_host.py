@@ -49,20 +49,27 @@ def test_fit_recovers_planted_rule(tmp_path):
             fast = 2 if f[6] <= 40 else 3
             t = [100.0, 90.0, 80.0, 70.0]
             t[fast] = 10.0
-            row = {"m": m, "family": "x", "rows": 1, "cols": 1, "nnz": 1, "t_features_us": 5.0,
+            row = {"m": m, "family": "x", "rows": int(f[0]) + 1, "cols": 1, "nnz": 1, "t_features_us": 5.0,
                    "max_disagreement": 0.0}
             row.update({f"f_{n}": repr(float(v)) for n, v in zip(S.FEATURE_NAMES, f)})
             row.update({f"t_k{k}_us": t[k] for k in range(4)})
+            row["t_auto_mp_us"] = t[3] + 4.0          # gathering on the device costs 4 us
             w.writerow(row)
-    out = tmp_path / "tree.json"
-    tree = T.fit_tree(str(p), str(out))
-    rep = tree["report"]
-    assert rep["test"]["accuracy"] == 1.0 and rep["train"]["accuracy"] == 1.0
-    assert rep["all"]["speedup_vs_best_fixed"] > 1.2
+    out = tmp_path / "model.json"
+    model = T.fit_model(str(p), str(out))
+    rep = model["report"]
+    assert rep["test"]["accuracy"]["gathered"] == 1.0 and rep["train"]["accuracy"]["gathered"] == 1.0
+    assert rep["test"]["accuracy"]["known"] < 0.9          # var_len is not a known feature
+    assert abs(model["gather_overhead_us"]["intercept"] - 4.0) < 0.5
+    assert rep["all"]["aggregate_speedup_vs_best_fixed"]["gathered"] > 1.2
+    # gathering costs 4 us and saves 60-70 us whenever the known model is wrong: the selector gathers
+    assert rep["all"]["gathered_fraction"] > 0.5
+    assert rep["all"]["t_us"]["classifier_selection"] <= rep["all"]["t_us"]["known"]
     # the shipped format round-trips through the C ABI walker
-    t, _ = T.load_tree(str(out))
+    m, _ = T.load_model(str(out))
     from paper_2403_17017_amd import binding as B
     for v, want in ((10.0, 2), (400.0, 3)):
         f = B.seer_features_t()
         f.f[6] = v
-        assert S.seer_select(f, t) == want
+        assert S.seer_select(f, m.gathered) == want
+    assert all(f in (-1, 0, 1, 2, 3, 8) for f in model["known"]["feature"] + model["selector"]["feature"])
