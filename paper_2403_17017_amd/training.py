@@ -12,6 +12,7 @@ gathering is worth its cost.  The trees are stored as the flat node arrays that
            --out paper_2403_17017_amd/selector_model.json
     python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv \
            --model paper_2403_17017_amd/selector_model.json --out gpurun_out/eval.csv
+    python -m paper_2403_17017_amd.training export-header      # trees as nested if/else in C
 
 Timing protocol as in Sec. IV-B: 10 warm-up runs, mean of 10 timed runs, on the same
 buffers; the timed runs are replayed from a HIP graph so that kernel time, not host
@@ -362,6 +363,46 @@ def summarize_evaluation(eval_csv):
     }
 
 
+def _emit_node(tree, n, depth, lines):
+    pad = "    " * depth
+    if tree["feature"][n] < 0:
+        lines.append(f"{pad}return {int(tree['klass'][n])};")
+        return
+    # hexadecimal floating constants are exact
+    lines.append(f"{pad}if ((double)f[{int(tree['feature'][n])}] <= {float(tree['threshold'][n]).hex()}) {{")
+    _emit_node(tree, tree["left"][n], depth + 1, lines)
+    lines.append(f"{pad}}} else {{")
+    _emit_node(tree, tree["right"][n], depth + 1, lines)
+    lines.append(f"{pad}}}")
+
+
+def export_header(model_json, out_h, prefix="seer_model"):
+    """Writes the trained trees as a C header of nested if/else statements (the form the
+    paper deploys its models in, Sec. III-D): one `static inline int <prefix>_<tree>(const
+    float *f)` per tree, f being the 12-entry feature vector.  Readable, diffable, and
+    equivalent to walking the node arrays."""
+    with open(model_json) as fh:
+        m = json.load(fh)
+    names = m.get("feature_names", list(S.FEATURE_NAMES))
+    lines = ["/* Generated by paper_2403_17017_amd.training export-header; do not edit.",
+             f" * {m.get('note', '')}", " * Feature vector f[]: " + ", ".join(f"{i} {n}" for i, n in enumerate(names)),
+             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP;",
+             " * the selector returns 0 = use the known model, 1 = gather features first. */",
+             "#ifndef SEER_MODEL_GENERATED_H", "#define SEER_MODEL_GENERATED_H", ""]
+    for key in ("known", "gathered", "selector"):
+        if key not in m:
+            continue
+        lines.append(f"static inline int {prefix}_{key}(const float *f)")
+        lines.append("{")
+        _emit_node(m[key], 0, 1, lines)
+        lines.append("}")
+        lines.append("")
+    lines.append("#endif")
+    with open(out_h, "w") as fh:
+        fh.write("\n".join(lines) + "\n")
+    return out_h
+
+
 def _tree_from(d):
     return S.Tree(d["feature"], d["threshold"], d["left"], d["right"], d["klass"])
 
@@ -396,7 +437,13 @@ def main(argv=None):
     c.add_argument("--csv", required=True)
     c.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     c.add_argument("--out", default="gpurun_out/eval.csv")
+    d = sub.add_parser("export-header")
+    d.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
+    d.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model_generated.h"))
     args = ap.parse_args(argv)
+    if args.cmd == "export-header":
+        print(export_header(args.model, args.out))
+        return
     if args.cmd == "sweep":
         run_sweep(range(args.first, args.first + args.count), args.out, args.nnz_cap, args.max_rows_exp)
     elif args.cmd == "fit":

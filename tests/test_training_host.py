@@ -73,3 +73,41 @@ def test_fit_recovers_planted_rule(tmp_path):
         f.f[6] = v
         assert S.seer_select(f, m.gathered) == want
     assert all(f in (-1, 0, 1, 2, 3, 8) for f in model["known"]["feature"] + model["selector"]["feature"])
+
+
+def test_exported_header_is_equivalent_to_the_node_arrays(tmp_path):
+    """The generated if/else header, compiled with gcc, answers like the oracle's tree
+    walk on random vectors and on vectors that sit exactly on thresholds."""
+    import ctypes
+    import json
+    import os
+    import subprocess
+
+    from oracle import seer_oracle as O
+    model_path = os.path.join(os.path.dirname(T.__file__), "selector_model.json")
+    hdr = T.export_header(model_path, str(tmp_path / "model.h"))
+    src = tmp_path / "wrap.c"
+    src.write_text('#include "model.h"\n'
+                   "int known(const float *f) { return seer_model_known(f); }\n"
+                   "int gathered(const float *f) { return seer_model_gathered(f); }\n"
+                   "int selector(const float *f) { return seer_model_selector(f); }\n")
+    so = tmp_path / "wrap.so"
+    subprocess.check_call(["gcc", "-O1", "-shared", "-fPIC", "-I", str(tmp_path), "-o", str(so), str(src)])
+    lib = ctypes.CDLL(str(so))
+    m = json.load(open(model_path))
+    rng = np.random.default_rng(3)
+    for key in ("known", "gathered", "selector"):
+        t = m[key]
+        arrs = (t["feature"], t["threshold"], t["left"], t["right"], t["klass"])
+        thr = [(f, th) for f, th in zip(t["feature"], t["threshold"]) if f >= 0]
+        fn = getattr(lib, key)
+        fn.argtypes = [ctypes.POINTER(ctypes.c_float)]
+        for i in range(400):
+            v = np.exp(rng.normal(4, 4, 12)).astype(np.float32)
+            v[7] = rng.random()
+            if thr and i % 2:
+                f, th = thr[int(rng.integers(len(thr)))]
+                v[f] = np.float32(th) if i % 4 == 1 else np.nextafter(np.float32(th), np.float32(np.inf))
+            got = fn(v.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+            assert got == O.select(v, *arrs)
+    assert "if ((double)f[" in open(hdr).read()
