@@ -70,8 +70,8 @@ int wm_lanes(int rows, int nnz)
 // Rows per workgroup for CSR,BM, from measurements over banded / random matrices:
 // short rows want fat blocks (5 K to 8 K nonzeros: fewer blocks, longer streams),
 // rows longer than a wave want about one LDS chunk per block, because those rows are
-// reduced one at a time by their wave.  A small matrix is cut finer (down to one
-// 16-byte load per lane) so that every CU gets several blocks.
+// reduced one at a time by their wave.  A small matrix is cut finer (down to about
+// one LDS chunk per block) so that every CU gets at least four blocks.
 int bm_rows(int rows, int nnz)
 {
     const int t = g_tune_bm_rows.load();
@@ -80,7 +80,7 @@ int bm_rows(int rows, int nnz)
     const double target = mean > 64.0 ? 1536.0 : (mean > 24.0 ? 8192.0 : 5120.0);
     int r = 1;
     while (r < 1024 && (double)r * mean * 1.41421356 < target) r <<= 1;   // nearest power of two
-    while (r > 1 && rows / r < 1024 && (double)r * mean > 1024.0) r >>= 1;
+    while (r > 1 && rows / r < 1024 && (double)r * mean > 2048.0) r >>= 1;
     return r;
 }
 

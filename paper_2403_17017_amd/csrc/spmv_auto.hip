@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kWG) void spmv_auto_kernel(
     const AutoShape shape, int remap)
 {
     static_assert(mp_lds_words<IPT>() <= kAutoLds, "LDS overlay too small");
-    __shared__ int smem[kAutoLds];
+    __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
     const int k = sel->kernel_id;                           // same for the whole grid
     const uint32_t n_tiles = shape.tiles[k];
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);

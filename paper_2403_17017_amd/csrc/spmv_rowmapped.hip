@@ -25,16 +25,16 @@ __global__ __launch_bounds__(kWG) void spmv_wm_kernel(
     wm_body<G>(rows, rp, ci, va, x, y, tile);
 }
 
-template <int CH, bool VEC, bool NT>
+template <int CH, bool VEC, bool NT, bool PIPE = true, bool PAD = false>
 __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     int rows, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
     int rows_per_block, int own_shift, uint32_t n_tiles, int remap)
 {
-    __shared__ float s_prod[bm_lds_words<CH>()];
+    __shared__ __attribute__((aligned(16))) float s_prod[bm_lds_words<CH>()];
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
-    bm_body<CH, VEC, NT>(rows, rp, ci, va, x, y, rows_per_block, own_shift, tile, s_prod);
+    bm_body<CH, VEC, NT, PIPE, PAD>(rows, rp, ci, va, x, y, rows_per_block, own_shift, tile, s_prod);
 }
 
 // ------------------------------------------------------------------ launchers
