@@ -19,10 +19,10 @@
  *   - Every call returns SEER_OK (0) or a negative seer_status; on error no output
  *     is written.  Nothing throws or aborts.  Matrix contents (monotone row_ptr,
  *     column range) are NOT validated: they are the caller's contract.
- *   - The first call on a device allocates one 64-byte pinned host buffer per
- *     process (result mailbox of seer_features); no other state is kept.
- *   - Calls that use the same workspace, or seer_features calls on the same device,
- *     must not overlap in time.
+ *   - The first seer_features call allocates one 64-byte pinned host buffer per
+ *     process (its result mailbox); no other state is kept, on the host or the device.
+ *   - Calls that use the same workspace must not overlap in time; seer_features calls
+ *     are serialised inside the library (they share the mailbox).
  */
 #ifndef SEER_H
 #define SEER_H
@@ -107,11 +107,11 @@ typedef struct {
 } seer_tree;
 
 /* Feature collection (Sec. IV-A: parallel kernels that loop over the CSR offsets).
- * Reads A->row_ptr only (col_idx / values may be NULL).  Enqueues one reduction
- * kernel on `stream`, waits for its result (the kernel's last act is to write it to
+ * Reads A->row_ptr only (col_idx / values may be NULL).  Enqueues the reduction (one
+ * launch up to 8192 rows, two above) on `stream`, waits for its result (the kernel's last act is to write it to
  * pinned host memory; on return the stream may still be retiring that kernel), and
  * fills *out.  workspace: DEVICE, at least
- * seer_features_workspace_bytes(A->rows) bytes. */
+ * seer_features_workspace_bytes(A->rows) bytes (per-workgroup partial results). */
 int seer_features(const seer_csr *A, seer_features_t *out,
                   void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_features_workspace_bytes(int32_t rows);

@@ -1,28 +1,26 @@
-// seer_features: the feature-collection launch (Sec. IV-A), plus two measurement
+// seer_features: the feature-collection launches (Sec. IV-A), plus two measurement
 // aids (plain copy and read-only stream).  The reduction is in features_bodies.hiph.
 #include "features_bodies.hiph"
 
 namespace seer {
 
+// Finishing (or only) launch of seer_features: the result goes into pinned host memory,
+// first the statistics, then, after a system-wide fence, the sequence number.
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_kernel(
-    int rows, const int *__restrict__ rp, FeatPartial *__restrict__ part,
+    int rows, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
     FeatureRaw *__restrict__ mailbox, uint64_t seq)
 {
-    __shared__ FeatPartial s_part[kFeatWaves];
-    __shared__ int s_last;
-    int32_t mx, mn;
-    uint64_t sq, em;
-    if (!features_reduce<VEC>(rows, rp, part, s_part, &s_last, mx, mn, sq, em)) return;
+    __shared__ FeatLds s;
+    features_total<VEC>(rows, rp, part, n_part, &s);
     if (threadIdx.x == 0) {
         FeatureRaw r;
-        r.max_len = mx; r.min_len = mn;
+        r.max_len = s.mx; r.min_len = s.mn;
         r.first = rp[0]; r.last = rp[rows];
-        r.sum_sq = sq; r.empty = em; r.seq = 0;
+        r.sum_sq = s.sq; r.empty = s.em; r.seq = 0;
         *mailbox = r;
         __threadfence_system();            // the statistics land before the sequence number
         *reinterpret_cast<volatile uint64_t *>(&mailbox->seq) = seq;
-        if (gridDim.x > 1) atomicExch(&g_feat_ticket, 0u);    // ready for the next call
     }
 }
 
@@ -82,28 +80,28 @@ void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t 
                            static_cast<const uint32_t *>(src), n_vec * 4, n_words);
 }
 
-uint32_t features_num_blocks(int rows)
-{
-    if (rows <= 0) return 0;
-    const uint32_t want = ((uint32_t)rows + kFeatRowsPerBlock - 1) / kFeatRowsPerBlock;
-    return want < kFeatMaxBlocks ? want : kFeatMaxBlocks;
-}
-
 size_t features_workspace_bytes(int rows)
 {
     (void)rows;
-    return (size_t)kFeatMaxBlocks * sizeof(FeatPartial);
+    return (size_t)kFeatMaxParts * sizeof(FeatPartial);
 }
 
 void launch_features(int rows, const int *rp, void *workspace, FeatureRaw *mailbox_dev,
                      uint64_t seq, hipStream_t st)
 {
-    if ((reinterpret_cast<uintptr_t>(rp) & 15u) == 0)
-        hipLaunchKernelGGL(features_kernel<true>, dim3(features_num_blocks(rows)), dim3(kFeatWG), 0, st, rows, rp,
-                           static_cast<FeatPartial *>(workspace), mailbox_dev, seq);
-    else
-        hipLaunchKernelGGL(features_kernel<false>, dim3(features_num_blocks(rows)), dim3(kFeatWG), 0, st, rows, rp,
-                           static_cast<FeatPartial *>(workspace), mailbox_dev, seq);
+    FeatPartial *part = static_cast<FeatPartial *>(workspace);
+    const uint32_t n_part = features_num_parts(rows);
+    if ((reinterpret_cast<uintptr_t>(rp) & 15u) == 0) {
+        if (n_part)
+            hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, rows, rp, part);
+        hipLaunchKernelGGL(features_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, rows, rp, part, n_part,
+                           mailbox_dev, seq);
+    } else {
+        if (n_part)
+            hipLaunchKernelGGL(features_partial_kernel<false>, dim3(n_part), dim3(kFeatPartWG), 0, st, rows, rp, part);
+        hipLaunchKernelGGL(features_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, rows, rp, part, n_part,
+                           mailbox_dev, seq);
+    }
 }
 
 } // namespace seer

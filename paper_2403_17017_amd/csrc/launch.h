@@ -38,7 +38,6 @@ struct FeatureRaw {           // written by the device into pinned host memory
     uint64_t sum_sq, empty;
     uint64_t seq;             // call counter echoed back (host checks it moved)
 };
-uint32_t features_num_blocks(int rows);
 size_t features_workspace_bytes(int rows);
 void launch_features(int rows, const int *rp, void *workspace, FeatureRaw *mailbox_dev,
                      uint64_t seq, hipStream_t st);
@@ -68,8 +67,8 @@ struct AutoShape {                          // launch shapes, all from rows and 
     uint32_t tiles[SEER_NUM_KERNELS];
     int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
 };
-constexpr size_t kAutoSelOffset = 2048;     // after the 64 feature partials of 32 bytes
-constexpr size_t kAutoCarryOffset = 2048 + 256;
+constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
+constexpr size_t kAutoCarryOffset = 32768 + 256;
 size_t auto_workspace_bytes(int rows, int nnz);
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, void *workspace,
                  hipStream_t st);

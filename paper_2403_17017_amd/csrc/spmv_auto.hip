@@ -1,9 +1,10 @@
 // The whole runtime flow of Sec. III-B -- gather features, evaluate the decision tree,
-// run the chosen kernel -- as three launches with no host round trip in between:
+// run the chosen kernel -- as a few launches with no host round trip in between:
 //
-//   1. features_select_kernel: the feature reduction; its last workgroup derives
-//      the feature vector on the device, walks the tree (handed over by value in
-//      the kernel arguments) and leaves the chosen kernel id in device memory;
+//   1. the feature reduction (one launch for a small matrix, two for a large one);
+//      its finishing workgroup (features_select_kernel) derives the feature vector
+//      on the device, walks the tree (handed over by value in the kernel arguments)
+//      and leaves the chosen kernel id in device memory;
 //   2. spmv_auto_kernel: one kernel that contains all four schedules; every
 //      workgroup reads the chosen id and runs that schedule's body (the grid is
 //      sized for the schedule that needs the most workgroups, the rest exit);
@@ -68,20 +69,17 @@ __device__ __forceinline__ void derive_features_device(
 
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
-    int rows, int cols, const int *__restrict__ rp, FeatPartial *__restrict__ part,
+    int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
     AutoSel *__restrict__ sel, const AutoTree tree)
 {
-    __shared__ FeatPartial s_part[kFeatWaves];
-    __shared__ int s_last;
+    __shared__ FeatLds s;
     __shared__ float s_f[SEER_NUM_FEATURES];
-    int32_t mx, mn;
-    uint64_t sq, em;
-    if (!features_reduce<VEC>(rows, rp, part, s_part, &s_last, mx, mn, sq, em)) return;
+    features_total<VEC>(rows, rp, part, n_part, &s);
     if (threadIdx.x == 0) {
         // the feature vector lives in LDS so that the tree can index it without
         // forcing it into private (scratch) memory
         const int64_t nnz = (int64_t)rp[rows] - (int64_t)rp[0];
-        derive_features_device(rows, cols, nnz, mx, mn, (int64_t)em, sq, s_f);
+        derive_features_device(rows, cols, nnz, s.mx, s.mn, (int64_t)s.em, s.sq, s_f);
         int n = 0, k = SEER_CSR_MP;            // a malformed tree cannot get here (host checks); MP is the safe answer
         for (int steps = 0; steps <= tree.n_nodes; ++steps) {
             const int feature = tree.nodes[n].feature;
@@ -91,15 +89,14 @@ __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
         sel->kernel_id = (k >= 0 && k < SEER_NUM_KERNELS) ? k : SEER_CSR_MP;
         sel->valid = 1;
         sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
-        sel->max_len = mx; sel->min_len = mn;
-        sel->sum_sq = sq; sel->empty = em;
+        sel->max_len = s.mx; sel->min_len = s.mn;
+        sel->sum_sq = s.sq; sel->empty = s.em;
 #pragma unroll
         for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
-        if (gridDim.x > 1) atomicExch(&g_feat_ticket, 0u);    // ready for the next call
     }
 }
 
-static_assert(kFeatMaxBlocks * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(AutoSel) <= kAutoCarryOffset - kAutoSelOffset,
+static_assert(kFeatMaxParts * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(AutoSel) <= kAutoCarryOffset - kAutoSelOffset,
               "workspace layout");
 
 constexpr int kAutoLds = mp_lds_words<kMpIptLarge>() > bm_lds_words<kBmChunk>() ? mp_lds_words<kMpIptLarge>()
@@ -161,12 +158,18 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
     int *carry_row = reinterpret_cast<int *>(ws + kAutoCarryOffset);
     float *carry_val = reinterpret_cast<float *>(ws + kAutoCarryOffset + one);
 
-    if ((reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0)
-        hipLaunchKernelGGL(features_select_kernel<true>, dim3(features_num_blocks(a.rows)), dim3(kFeatWG), 0, st,
-                           a.rows, a.cols, a.rp, part, sel, tree);
-    else
-        hipLaunchKernelGGL(features_select_kernel<false>, dim3(features_num_blocks(a.rows)), dim3(kFeatWG), 0, st,
-                           a.rows, a.cols, a.rp, part, sel, tree);
+    const uint32_t n_part = features_num_parts(a.rows);
+    if ((reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0) {
+        if (n_part)
+            hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+        hipLaunchKernelGGL(features_select_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
+                           n_part, sel, tree);
+    } else {
+        if (n_part)
+            hipLaunchKernelGGL(features_partial_kernel<false>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+        hipLaunchKernelGGL(features_select_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
+                           n_part, sel, tree);
+    }
 
     uint32_t grid = 0;
     for (int k = 0; k < SEER_NUM_KERNELS; ++k) {

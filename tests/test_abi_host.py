@@ -197,4 +197,4 @@ def test_workspace_sizes():
     assert S.spmv_workspace_bytes(2, 10**6, 10**7) == 0
     n_tiles = -(-(10**6 + 10**7) // (256 * 7))
     assert S.spmv_workspace_bytes(3, 10**6, 10**7) >= 8 * n_tiles
-    assert S.features_workspace_bytes(10**6) >= 64 * 32
+    assert S.features_workspace_bytes(10**6) >= 1024 * 32
