@@ -24,6 +24,7 @@ std::atomic<int> g_tune_bm_chunk{-1};
 std::atomic<int> g_tune_mp_ipt{-1};
 std::atomic<int> g_tune_remap{-1};
 std::atomic<int> g_tune_nt{-1};
+std::atomic<int> g_tune_vec{-1};
 std::atomic<int> g_tune_poll{-1};
 
 std::mutex g_mailbox_mutex;
@@ -234,6 +235,7 @@ int seer_set_tuning(const char *name, int value)
     else if (!std::strcmp(name, "mp_ipt")) g_tune_mp_ipt.store(value);
     else if (!std::strcmp(name, "xcd_remap")) g_tune_remap.store(value);
     else if (!std::strcmp(name, "nt")) g_tune_nt.store(value);
+    else if (!std::strcmp(name, "vec")) g_tune_vec.store(value);
     else if (!std::strcmp(name, "poll")) g_tune_poll.store(value);
     else return SEER_EINVAL;
     return SEER_OK;
@@ -388,7 +390,7 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     sh.tiles[SEER_CSR_BM] = (rows + (uint32_t)sh.bm_rows - 1u) / (uint32_t)sh.bm_rows;
     sh.tiles[SEER_CSR_MP] = mp_num_tiles(A->rows, A->nnz, sh.mp_ipt);
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), 1};
-    const bool vec = aligned16(A->col_idx) && aligned16(A->values);
+    const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
     launch_auto(a, dt, sh, vec, workspace, static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);
@@ -480,7 +482,7 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *
     if (!y || (!x && A->nnz > 0)) return SEER_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt()};
-    const bool vec = aligned16(A->col_idx) && aligned16(A->values);
+    const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
     switch (kernel_id) {
     case SEER_CSR_TM: launch_tm(a, st); break;
     case SEER_CSR_WM: launch_wm(a, wm_lanes(A->rows, A->nnz), st); break;

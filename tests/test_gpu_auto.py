@@ -146,3 +146,53 @@ def test_auto_wide_integer_features():
         assert_features_equal(f, want, "wide-integer features (device)")
         assert np.array_equal(y, lens.astype(np.float32))
     assert_features_equal(S.seer_features(dA), want, "wide-integer features (host derivation)")
+
+
+def test_classifier_selection_path(cases):
+    """seer_spmv_model: the selector runs on the host, the known model launches a kernel
+    directly, the gathered model goes through the asynchronous path; path and kernel id
+    must match the oracle's three-tree inference, y must match the oracle."""
+    import torch
+    # selector: nnz <= 100000 -> known model, else gather
+    selector = S.Tree([2, -1, -1], [100000.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1], n_classes=2)
+    # known: mean_len <= 6 ? BM : WM
+    known = S.Tree([3, -1, -1], [6.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 2, 1])
+    gathered = S.Tree(*REAL_TREE)
+    model = S.Model(gathered, known, selector)
+    paths = set()
+    for A, x, y_ref, bound in cases:
+        announce(f"model path {A.name}")
+        dA = upload(A)
+        xd = torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        y = torch.full((max(A.rows, 1),), float("nan"), device="cuda:0")
+        path, kid = S.seer_spmv_model(dA, model, xd, y, ws)
+        if path == 1:
+            _, kid = S.seer_spmv_auto_result(ws)
+        torch.cuda.synchronize()
+        fg = O.features(A.rows, A.cols, A.row_ptr)["f"]
+        assert (path, kid) == O.model_select(A.rows, A.cols, A.nnz, fg, selector.arrays, known.arrays, gathered.arrays)
+        assert_parity(y[:A.rows].cpu().numpy(), y_ref, bound, f"model path {path} kernel {kid} on {A.name}")
+        paths.add(path)
+    assert paths == {0, 1}
+    # no selector: always gather
+    A, x, y_ref, bound = cases[-1]
+    dA, xd = upload(A), torch.from_numpy(x).cuda()
+    ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+    y = torch.empty(A.rows, device="cuda:0")
+    assert S.seer_spmv_model(dA, S.Model(gathered), xd, y, ws)[0] == 1
+
+
+def test_shipped_model_loads_and_runs(cases):
+    import os
+    import torch
+    from paper_2403_17017_amd import training as T
+    path = os.path.join(os.path.dirname(T.__file__), "selector_model.json")
+    model, meta = T.load_model(path)
+    for A, x, y_ref, bound in cases[12:]:
+        dA, xd = upload(A), torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        p, kid = S.seer_spmv_model(dA, model, xd, y, ws)
+        torch.cuda.synchronize()
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"shipped model on {A.name}")
