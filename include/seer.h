@@ -49,8 +49,9 @@ enum {
     SEER_CSR_WM = 1, /* wavefront mapped: one row per group of 2..64 lanes of a wave  */
     SEER_CSR_BM = 2, /* block mapped: a block of consecutive rows per workgroup,
                         nonzeros staged through LDS                                   */
-    SEER_CSR_MP = 3, /* work oriented / merge path: equal shares of rows + nonzeros   */
-    SEER_NUM_KERNELS = 4
+    SEER_CSR_MP = 3, /* merge path: equal shares of rows + nonzeros (Table III's CSR,MP) */
+    SEER_CSR_WO = 4, /* work oriented: equal shares of nonzeros (Table III's CSR,WO)   */
+    SEER_NUM_KERNELS = 5
 };
 
 /* CSR matrix, fp32 values, int32 indices.  All pointers DEVICE, caller-owned.

@@ -17,8 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libseer.so")
 
 NUM_FEATURES = 12
-NUM_KERNELS = 4
-CSR_TM, CSR_WM, CSR_BM, CSR_MP = range(4)
+NUM_KERNELS = 5
+CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO = range(5)
 FEATURE_NAMES = (
     "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
     "mean_density", "max_density", "min_density", "var_density",

@@ -31,6 +31,13 @@ uint32_t mp_num_tiles(int rows, int nnz, int ipt);
 size_t mp_workspace_bytes(int rows, int nnz, int ipt);
 void launch_mp(const SpmvArgs &a, int ipt, bool vec, void *workspace, hipStream_t st);
 
+// work oriented (nonzero split); shares the carry arrays' layout and the fix-up with merge path
+uint32_t wo_num_tiles(int rows, int nnz);
+void launch_wo(const SpmvArgs &a, bool vec, void *workspace, hipStream_t st);
+size_t carry_workspace_bytes(uint32_t n_tiles);
+void launch_carry_fixup(int rows, uint32_t n_tiles, const int *carry_row, const float *carry_val, float *y,
+                        hipStream_t st);
+
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory
     int32_t max_len, min_len;

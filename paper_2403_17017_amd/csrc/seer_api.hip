@@ -201,7 +201,7 @@ bool tree_is_acyclic(const seer_tree *t)
     return true;
 }
 
-const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP"};
+const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO"};
 
 } // namespace
 
@@ -245,7 +245,9 @@ size_t seer_features_workspace_bytes(int32_t rows) { return rows < 0 ? 0 : featu
 
 size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz)
 {
-    if (kernel_id != SEER_CSR_MP || rows <= 0 || nnz < 0) return 0;
+    if (rows <= 0 || nnz < 0) return 0;
+    if (kernel_id == SEER_CSR_WO) return carry_workspace_bytes(wo_num_tiles(rows, nnz));
+    if (kernel_id != SEER_CSR_MP) return 0;
     // the small tile gives the larger count; cover either choice
     return mp_workspace_bytes(rows, nnz, kMpIptSmall);
 }
@@ -389,6 +391,7 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     sh.tiles[SEER_CSR_WM] = (rows + (256u / sh.wm_lanes) - 1u) / (256u / sh.wm_lanes);
     sh.tiles[SEER_CSR_BM] = (rows + (uint32_t)sh.bm_rows - 1u) / (uint32_t)sh.bm_rows;
     sh.tiles[SEER_CSR_MP] = mp_num_tiles(A->rows, A->nnz, sh.mp_ipt);
+    sh.tiles[SEER_CSR_WO] = wo_num_tiles(A->rows, A->nnz);
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), 1};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
     launch_auto(a, dt, sh, vec, workspace, static_cast<hipStream_t>(stream));
@@ -487,6 +490,12 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *
     case SEER_CSR_TM: launch_tm(a, st); break;
     case SEER_CSR_WM: launch_wm(a, wm_lanes(A->rows, A->nnz), st); break;
     case SEER_CSR_BM: launch_bm(a, bm_rows(A->rows, A->nnz), bm_chunk(), vec, st); break;
+    case SEER_CSR_WO:
+        if (!workspace || !aligned16(workspace) ||
+            workspace_bytes < carry_workspace_bytes(wo_num_tiles(A->rows, A->nnz)))
+            return SEER_EWORKSPACE;
+        launch_wo(a, vec, workspace, st);
+        break;
     default: {
         const int ipt = mp_ipt(A->rows, A->nnz);
         if (!workspace || !aligned16(workspace) || workspace_bytes < mp_workspace_bytes(A->rows, A->nnz, ipt))

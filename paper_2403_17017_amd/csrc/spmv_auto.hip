@@ -101,6 +101,7 @@ static_assert(kFeatMaxParts * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(Au
 
 constexpr int kAutoLds = mp_lds_words<kMpIptLarge>() > bm_lds_words<kBmChunk>() ? mp_lds_words<kMpIptLarge>()
                                                                                  : bm_lds_words<kBmChunk>();
+static_assert(bm_lds_words<kWoChunk>() + 2 <= kAutoLds, "CSR,WO's products and its two bounds share the overlay");
 
 template <int IPT, bool VEC>
 __global__ __launch_bounds__(kWG) void spmv_auto_kernel(
@@ -129,22 +130,29 @@ __global__ __launch_bounds__(kWG) void spmv_auto_kernel(
     } else if (k == SEER_CSR_BM) {
         bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
                                      reinterpret_cast<float *>(smem));
+    } else if (k == SEER_CSR_WO) {
+        wo_body<kWoChunk, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile,
+                                     reinterpret_cast<float *>(smem),
+                                     reinterpret_cast<uint32_t *>(smem) + bm_lds_words<kWoChunk>());
     } else {
         mp_body<IPT, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile, smem);
     }
 }
 
 __global__ __launch_bounds__(kWG) void spmv_auto_fixup_kernel(
-    int rows, uint32_t n_tiles, const int *__restrict__ carry_row, const float *__restrict__ carry_val,
-    float *__restrict__ y, const AutoSel *__restrict__ sel)
+    int rows, uint32_t n_mp, uint32_t n_wo, const int *__restrict__ carry_row,
+    const float *__restrict__ carry_val, float *__restrict__ y, const AutoSel *__restrict__ sel)
 {
-    if (sel->kernel_id != SEER_CSR_MP) return;
-    mp_fixup_body(rows, n_tiles, carry_row, carry_val, y);
+    const int k = sel->kernel_id;
+    if (k != SEER_CSR_MP && k != SEER_CSR_WO) return;
+    mp_fixup_body(rows, k == SEER_CSR_MP ? n_mp : n_wo, carry_row, carry_val, y);
 }
 
 size_t auto_workspace_bytes(int rows, int nnz)
 {
-    return kAutoCarryOffset + mp_workspace_bytes(rows, nnz, kMpIptSmall);
+    const size_t mp = mp_workspace_bytes(rows, nnz, kMpIptSmall);
+    const size_t wo = carry_workspace_bytes(wo_num_tiles(rows, nnz));
+    return kAutoCarryOffset + (mp > wo ? mp : wo);
 }
 
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, void *workspace,
@@ -153,8 +161,9 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
     char *ws = static_cast<char *>(workspace);
     FeatPartial *part = reinterpret_cast<FeatPartial *>(ws);
     AutoSel *sel = reinterpret_cast<AutoSel *>(ws + kAutoSelOffset);
-    const uint32_t n_mp = shape.tiles[SEER_CSR_MP];
-    const size_t one = ((size_t)n_mp * 4 + 255) & ~(size_t)255;
+    const uint32_t n_mp = shape.tiles[SEER_CSR_MP], n_wo = shape.tiles[SEER_CSR_WO];
+    const uint32_t n_carry = n_mp > n_wo ? n_mp : n_wo;
+    const size_t one = carry_workspace_bytes(n_carry) / 2;
     int *carry_row = reinterpret_cast<int *>(ws + kAutoCarryOffset);
     float *carry_val = reinterpret_cast<float *>(ws + kAutoCarryOffset + one);
 
@@ -185,8 +194,8 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
         if (vec) SEER_AUTO_LAUNCH(kMpIptLarge, true); else SEER_AUTO_LAUNCH(kMpIptLarge, false);
     }
 #undef SEER_AUTO_LAUNCH
-    hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_mp + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
-                       carry_row, carry_val, a.y, sel);
+    hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_carry + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
+                       n_wo, carry_row, carry_val, a.y, sel);
 }
 
 } // namespace seer

@@ -32,10 +32,14 @@ uint32_t mp_num_tiles(int rows, int nnz, int ipt)
 
 size_t mp_workspace_bytes(int rows, int nnz, int ipt)
 {
-    // carry_row then carry_val, each padded to a multiple of 256 bytes
-    const size_t n = mp_num_tiles(rows, nnz, ipt);
-    const size_t one = (n * 4 + 255) & ~(size_t)255;
-    return 2 * one;
+    return carry_workspace_bytes(mp_num_tiles(rows, nnz, ipt));
+}
+
+void launch_carry_fixup(int rows, uint32_t n_tiles, const int *carry_row, const float *carry_val, float *y,
+                        hipStream_t st)
+{
+    hipLaunchKernelGGL(spmv_mp_fixup_kernel, dim3((n_tiles + kWG - 1) / kWG), dim3(kWG), 0, st, rows, n_tiles,
+                       carry_row, carry_val, y);
 }
 
 template <int IPT>
@@ -43,7 +47,7 @@ static void launch_mp_ipt(const SpmvArgs &a, bool vec, void *workspace, hipStrea
 {
     const uint32_t n_tiles = mp_num_tiles(a.rows, a.nnz, IPT);
     if (n_tiles == 0) return;
-    const size_t one = ((size_t)n_tiles * 4 + 255) & ~(size_t)255;
+    const size_t one = carry_workspace_bytes(n_tiles) / 2;
     int *carry_row = static_cast<int *>(workspace);
     float *carry_val = reinterpret_cast<float *>(static_cast<char *>(workspace) + one);
     const dim3 grid(a.remap ? tiles_per_xcd(n_tiles) * kXCD : n_tiles);
@@ -56,8 +60,7 @@ static void launch_mp_ipt(const SpmvArgs &a, bool vec, void *workspace, hipStrea
         if (a.nt) SEER_MP_LAUNCH(false, true); else SEER_MP_LAUNCH(false, false);
     }
 #undef SEER_MP_LAUNCH
-    hipLaunchKernelGGL(spmv_mp_fixup_kernel, dim3((n_tiles + kWG - 1) / kWG), dim3(kWG), 0, st,
-                       a.rows, n_tiles, carry_row, carry_val, a.y);
+    launch_carry_fixup(a.rows, n_tiles, carry_row, carry_val, a.y, st);
 }
 
 void launch_mp(const SpmvArgs &a, int ipt, bool vec, void *workspace, hipStream_t st)

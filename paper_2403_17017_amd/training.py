@@ -110,7 +110,7 @@ def measure_matrix(spec, device="cuda:0"):
     row["t_auto_mp_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, mp_only, x, ys[3], ws)), 3)
     # the schedules must agree with each other (a sanity check, not the parity test)
     scale = float(ys[3].abs().max().item()) + 1e-30
-    row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item() for k in range(3)) / scale)
+    row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item() for k in range(S.NUM_KERNELS) if k != 3) / scale)
     return row
 
 
@@ -134,7 +134,7 @@ def run_sweep(ms, out_csv, nnz_cap=200_000_000, max_rows_exp=7.0, log=sys.stderr
             w.writerow(row)
             fh.flush()
             print(f"[sweep] m={m} {spec.family} rows={row['rows']} nnz={row['nnz']} "
-                  f"t={[row[f't_k{k}_us'] for k in range(4)]} feat={row['t_features_us']} "
+                  f"t={[row[f't_k{k}_us'] for k in range(S.NUM_KERNELS)]} feat={row['t_features_us']} "
                   f"({time.time() - t_start:.0f}s)", file=log, flush=True)
 
 
@@ -333,7 +333,7 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
                 _, row["model_kernel"] = S.seer_spmv_auto_result(ws)
             w.writerow(row)
             fh.flush()
-            print(f"[eval] m={m} {spec.family} nnz={dA.nnz} kernels={[row[f't_k{k}_us'] for k in range(4)]} "
+            print(f"[eval] m={m} {spec.family} nnz={dA.nnz} kernels={[row[f't_k{k}_us'] for k in range(S.NUM_KERNELS)]} "
                   f"auto={row['t_auto_us']} (k{row['auto_kernel']}) model={row['t_model_us']} "
                   f"(path {row['model_path']}, k{row['model_kernel']})", file=log, flush=True)
     return summarize_evaluation(out_csv)
@@ -386,7 +386,7 @@ def export_header(model_json, out_h, prefix="seer_model"):
     names = m.get("feature_names", list(S.FEATURE_NAMES))
     lines = ["/* Generated by paper_2403_17017_amd.training export-header; do not edit.",
              f" * {m.get('note', '')}", " * Feature vector f[]: " + ", ".join(f"{i} {n}" for i, n in enumerate(names)),
-             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP;",
+             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO;",
              " * the selector returns 0 = use the known model, 1 = gather features first. */",
              "#ifndef SEER_MODEL_GENERATED_H", "#define SEER_MODEL_GENERATED_H", ""]
     for key in ("known", "gathered", "selector"):

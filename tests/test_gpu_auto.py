@@ -36,7 +36,7 @@ def cases():
     return out
 
 
-@pytest.mark.parametrize("forced", [0, 1, 2, 3, "tree"])
+@pytest.mark.parametrize("forced", [0, 1, 2, 3, 4, "tree"])
 def test_auto_matches_oracle_and_three_call_path(cases, forced):
     import torch
     tree = S.Tree(*REAL_TREE) if forced == "tree" else S.Tree.constant(forced)
@@ -67,7 +67,7 @@ def test_auto_misaligned_and_repeated(cases):
         xd = torch.from_numpy(x).cuda()
         ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
         announce(f"auto path misaligned {A.name}")
-        for _ in range(3):   # the ticket counter must come back to zero every time
+        for _ in range(3):   # the workspace is reused as it was left
             y, f, kid = run_auto(dA, tree, xd, A.rows, ws)
             assert_parity(y, y_ref, bound, f"auto misaligned on {A.name}")
 
@@ -139,7 +139,7 @@ def test_auto_wide_integer_features():
     xd = torch.ones(64, device="cuda:0")
     ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(rows, nnz))
     want = O.features(rows, 64, rp.astype(np.int32))
-    for forced in (3, 2, 1):
+    for forced in (3, 4, 2, 1):
         announce(f"auto path wide integers, kernel {forced}, nnz={nnz}")
         y, f, kid = run_auto(dA, S.Tree.constant(forced), xd, rows, ws)
         assert kid == forced

@@ -12,7 +12,7 @@ from gpu_util import announce, assert_features_equal, assert_parity, oracle_of, 
 pytestmark = pytest.mark.gpu
 
 
-def check_all(A, kernels=(0, 1, 2, 3)):
+def check_all(A, kernels=(0, 1, 2, 3, 4)):
     import torch
     x = G.dense_vector(A.cols, 4242)
     y_ref, bound = oracle_of(A, x)
@@ -35,7 +35,7 @@ def test_config2_laplacian_1024():
     ones = torch.ones(A.cols, device="cuda:0")
     r, c = np.divmod(np.arange(A.rows), 1024)
     want = (((r == 0) | (r == 1023)).astype(np.float32) + ((c == 0) | (c == 1023)).astype(np.float32))
-    for kid in range(4):
+    for kid in range(S.NUM_KERNELS):
         assert np.array_equal(run_spmv(kid, dA, ones, A.rows), want)
 
 

@@ -10,7 +10,7 @@ from workloads import csr_gen as G
 from gpu_util import (announce, assert_features_equal, assert_parity, oracle_of, run_spmv, upload)
 
 pytestmark = pytest.mark.gpu
-KERNELS = [0, 1, 2, 3]
+KERNELS = [0, 1, 2, 3, 4]
 
 
 def edge_cases():
@@ -161,14 +161,15 @@ def test_rows_zero_and_status_codes():
     B = G.random_lengths(100, 50, 0, 5, 3)
     dB = upload(B)
     with pytest.raises(S.SeerError) as ei:
-        S.seer_spmv(4, dB, torch.zeros(50, device="cuda:0"), torch.zeros(100, device="cuda:0"))
+        S.seer_spmv(S.NUM_KERNELS, dB, torch.zeros(50, device="cuda:0"), torch.zeros(100, device="cuda:0"))
     assert ei.value.status == -2
     small = torch.empty(16, dtype=torch.uint8, device="cuda:0")
     big = G.random_lengths(100_000, 50, 0, 5, 3)
-    with pytest.raises(S.SeerError) as ei:
-        S.seer_spmv(3, upload(big), torch.zeros(50, device="cuda:0"), torch.zeros(100_000, device="cuda:0"),
-                    workspace=small)
-    assert ei.value.status == -4
+    for kid in (S.CSR_MP, S.CSR_WO):
+        with pytest.raises(S.SeerError) as ei:
+            S.seer_spmv(kid, upload(big), torch.zeros(50, device="cuda:0"), torch.zeros(100_000, device="cuda:0"),
+                        workspace=small)
+        assert ei.value.status == -4
 
 
 # ------------------------------------------------------------------ features + select
@@ -180,9 +181,9 @@ def test_features_bit_exact(cases):
         assert_features_equal(got, O.features(A.rows, A.cols, A.row_ptr), A.name)
 
 
-def test_features_repeated_calls_reuse_ticket():
-    """Back-to-back reductions of different sizes: the ticket counter must return to
-    zero after every call (one block, many blocks, the block cap)."""
+def test_features_repeated_calls_reuse_workspace():
+    """Back-to-back reductions of different sizes through one workspace (one workgroup,
+    many partials, the cap on partials): nothing left by one call may leak into the next."""
     mats = [G.random_lengths(r, 1000, 0, 9, 300 + i) for i, r in enumerate([1, 4096, 4097, 70_000, 5_000_000, 17])]
     dev = [upload(A) for A in mats]
     want = [O.features(A.rows, A.cols, A.row_ptr) for A in mats]

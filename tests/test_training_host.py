@@ -47,12 +47,12 @@ def test_fit_recovers_planted_rule(tmp_path):
         for m in range(300):
             f = np.exp(rng.normal(2, 2, S.NUM_FEATURES)).astype(np.float32)
             fast = 2 if f[6] <= 40 else 3
-            t = [100.0, 90.0, 80.0, 70.0]
+            t = [100.0, 90.0, 80.0, 70.0, 75.0]
             t[fast] = 10.0
             row = {"m": m, "family": "x", "rows": int(f[0]) + 1, "cols": 1, "nnz": 1, "t_features_us": 5.0,
                    "max_disagreement": 0.0}
             row.update({f"f_{n}": repr(float(v)) for n, v in zip(S.FEATURE_NAMES, f)})
-            row.update({f"t_k{k}_us": t[k] for k in range(4)})
+            row.update({f"t_k{k}_us": t[k] for k in range(S.NUM_KERNELS)})
             row["t_auto_mp_us"] = t[3] + 4.0          # gathering on the device costs 4 us
             w.writerow(row)
     out = tmp_path / "model.json"
