@@ -20,7 +20,16 @@ What it defines
   * known_features, model_select -- the feature vector that costs nothing
                    (Sec. III-A) and inference with the classifier-selection
                    model that chooses between the known and the gathered model
-                   (Sec. III-B).
+                   (Sec. III-B).  The number of SpMV iterations the caller is
+                   about to run is one more known feature (Sec. V, multiple
+                   iteration evaluation); it is 1 unless stated.
+  * adaptive_plan -- the preprocessing result of the Adaptive-CSR schedule
+                   (Sec. IV: rows are grouped by size ahead of the first
+                   product): row blocks of about `chunk` nonzeros, long rows
+                   split between blocks.  The paper gives no data structure;
+                   the one defined here is this build's reading, and
+                   plan_spmv_python executes it literally so that tests can
+                   check it assigns every nonzero to its row exactly once.
 
 Readings where the paper is silent (all listed again in the design document):
   * variance is the population variance (divide by rows);
@@ -45,10 +54,10 @@ import subprocess
 
 import numpy as np
 
-NUM_FEATURES = 12
+NUM_FEATURES = 13
 FEATURE_NAMES = (
     "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
-    "mean_density", "max_density", "min_density", "var_density",
+    "mean_density", "max_density", "min_density", "var_density", "iterations",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -122,7 +131,7 @@ def _f32(v: float) -> np.float32:
     return np.float32(np.float64(v))
 
 
-def features(rows: int, cols: int, row_ptr) -> dict:
+def features(rows: int, cols: int, row_ptr, iterations: int = 1) -> dict:
     """O2.  One pass over the CSR offsets; exact integers, then the derived vector."""
     out = dict(rows=int(rows), cols=int(cols), nnz=0, max_len=0, min_len=0,
                empty_rows=0, sum_sq_len=0)
@@ -156,11 +165,12 @@ def features(rows: int, cols: int, row_ptr) -> dict:
             f[11] = _f32(var64 / (C * C))
     else:
         f[1] = _f32(float(cols))
+    f[12] = _f32(float(iterations))
     out["f"] = f
     return out
 
 
-def known_features(rows: int, cols: int, nnz: int) -> np.ndarray:
+def known_features(rows: int, cols: int, nnz: int, iterations: int = 1) -> np.ndarray:
     """The feature vector of a known-features model (Sec. III-A: rows, columns and
     nonzeros come with the dataset at no cost).  The mean row length and mean row
     density follow from those three numbers alone, so they are known as well; every
@@ -172,15 +182,17 @@ def known_features(rows: int, cols: int, nnz: int) -> np.ndarray:
         f[3] = _f32(mean64)
         if cols > 0:
             f[8] = _f32(mean64 / float(cols))
+    f[12] = _f32(float(iterations))
     return f
 
 
-def model_select(rows, cols, nnz, f_gathered, selector, known, gathered):
+def model_select(rows, cols, nnz, f_gathered, selector, known, gathered, iterations: int = 1):
     """Classifier-selection inference (Sec. III-B).  Each tree is a 5-tuple of parallel
     arrays; selector may be None (always gather).  Returns (path, kernel id) with
-    path 0 = known model, 1 = gathered model."""
+    path 0 = known model, 1 = gathered model.  f_gathered must carry the same
+    iteration count in its last entry."""
     if selector is not None:
-        kf = known_features(rows, cols, nnz)
+        kf = known_features(rows, cols, nnz, iterations)
         if select(kf, *selector) == 0:
             return 0, select(kf, *known)
     return 1, select(f_gathered, *gathered)
@@ -197,3 +209,50 @@ def select(f, feature, threshold, left, right, klass) -> int:
         if steps > len(feature):
             raise ValueError("tree has a cycle")
     return int(klass[n])
+
+
+def adaptive_plan(rows: int, row_ptr, chunk: int):
+    """Row blocks of the Adaptive-CSR schedule.  With n = max(1, ceil(nnz / chunk))
+    blocks, block k covers rows [row[k], row[k+1]) and nonzeros [start[k], start[k+1]):
+        row[0] = 0, start[0] = 0, row[n] = rows, start[n] = nnz, and for 0 < k < n
+        row[k]   = the first row that ends after nonzero k*chunk,
+        start[k] = k*chunk      if that row is also row[k-1] (the row runs through the
+                                whole of block k-1, which then holds nothing else),
+                   row_ptr[row[k]] otherwise (blocks begin on a row boundary).
+    A block with row[k] == row[k+1] lies inside one long row and contributes a partial
+    sum to it; every other row is summed by the one block that holds its end.
+    Returns (row, start) as int64 arrays of n + 1 entries; rows == 0 gives n = 0."""
+    if rows == 0:
+        return np.zeros(1, np.int64), np.zeros(1, np.int64)
+    rp = np.asarray(row_ptr[: rows + 1], dtype=np.int64)
+    nnz = int(rp[rows])
+    n = max(1, -(-nnz // chunk))
+    row = np.zeros(n + 1, np.int64)
+    start = np.zeros(n + 1, np.int64)
+    ends = rp[1:].tolist()
+    i = 0
+    for k in range(1, n):
+        while ends[i] <= k * chunk:             # rows that end at or before nonzero k*chunk
+            i += 1                              # (row ends never decrease, so i only moves forward)
+        row[k] = i
+        start[k] = k * chunk if row[k - 1] == i else int(rp[i])
+    row[n] = rows
+    start[n] = nnz
+    return row, start
+
+
+def plan_spmv_python(rows, row_ptr, col_idx, values, x, row, start):
+    """Executes a plan literally, block by block, in exact Python arithmetic on whatever
+    number type the inputs hold (tests use small integers): the rows a block owns take
+    the part of themselves that lies inside the block's nonzero range, a block inside
+    one long row adds its whole range to that row."""
+    y = [0] * rows
+    for k in range(len(row) - 1):
+        lo, hi, s, e = int(row[k]), int(row[k + 1]), int(start[k]), int(start[k + 1])
+        if lo == hi:
+            y[lo] += sum(values[j] * x[col_idx[j]] for j in range(s, e))
+            continue
+        for i in range(lo, hi):
+            a, b = max(int(row_ptr[i]), s), min(int(row_ptr[i + 1]), e)
+            y[i] += sum(values[j] * x[col_idx[j]] for j in range(a, b))
+    return y

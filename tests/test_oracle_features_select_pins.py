@@ -78,10 +78,10 @@ def test_variance_sign_and_transposition_mistakes_are_caught():
 def test_degenerate_shapes():
     F = O.features(0, 7, np.zeros(1, np.int32))
     assert F["nnz"] == 0 and F["max_len"] == 0 and F["min_len"] == 0
-    assert F["f"][IDX["cols"]] == 7 and np.count_nonzero(F["f"]) == 1
+    assert F["f"][IDX["cols"]] == 7 and F["f"][IDX["iterations"]] == 1 and np.count_nonzero(F["f"]) == 2
     F = O.features(3, 0, np.zeros(4, np.int32))
     assert F["empty_rows"] == 3 and F["f"][IDX["empty_frac"]] == 1.0
-    assert np.all(F["f"][8:] == 0)
+    assert np.all(F["f"][8:12] == 0)
 
 
 def test_large_values_need_wide_integers():
@@ -125,11 +125,11 @@ def tree_arrays(clf):
 
 def test_hand_built_trees():
     # depth 0
-    assert O.select(np.zeros(12, np.float32), [-1], [0.0], [-1], [-1], [3]) == 3
+    assert O.select(np.zeros(O.NUM_FEATURES, np.float32), [-1], [0.0], [-1], [-1], [3]) == 3
     # depth 2:  f4 <= 10 ? (f7 <= 0.5 ? 0 : 1) : 2
     feat, thr = [4, 7, -1, -1, -1], [10.0, 0.5, 0, 0, 0]
     left, right, kl = [1, 2, -1, -1, -1], [4, 3, -1, -1, -1], [-1, -1, 0, 1, 2]
-    f = np.zeros(12, np.float32)
+    f = np.zeros(O.NUM_FEATURES, np.float32)
     f[4], f[7] = 10.0, 0.5
     assert O.select(f, feat, thr, left, right, kl) == 0      # both ties go left
     f[7] = np.nextafter(np.float32(0.5), np.float32(1))
@@ -175,8 +175,8 @@ def test_known_features_are_the_free_part_of_the_gathered_vector():
     for A in (G.laplacian_5pt(37), G.empty_poisson(5000, 300, 0.3, 4.0, seed=2), G.zipf_rows(3000, s=1.5, cap=500, seed=3)):
         f = O.features(A.rows, A.cols, A.row_ptr)["f"]
         k = O.known_features(A.rows, A.cols, A.nnz)
-        assert np.array_equal(k[[0, 1, 2, 3, 8]], f[[0, 1, 2, 3, 8]])
-    assert np.count_nonzero(O.known_features(0, 9, 0)) == 1
+        assert np.array_equal(k[[0, 1, 2, 3, 8, 12]], f[[0, 1, 2, 3, 8, 12]])
+    assert np.count_nonzero(O.known_features(0, 9, 0)) == 2        # cols and the iteration count
 
 
 def test_model_select_hand_cases():
@@ -185,10 +185,28 @@ def test_model_select_hand_cases():
     selector = ([0, -1, -1], [100.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1])
     known = ([-1], [0.0], [-1], [-1], [1])
     gathered = ([6, -1, -1], [5.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 2, 3])
-    fg = np.zeros(12, np.float32)
+    fg = np.zeros(O.NUM_FEATURES, np.float32)
     fg[6] = 7.0
     assert O.model_select(100, 50, 10, fg, selector, known, gathered) == (0, 1)
     assert O.model_select(101, 50, 10, fg, selector, known, gathered) == (1, 3)
     fg[6] = 5.0
     assert O.model_select(101, 50, 10, fg, selector, known, gathered) == (1, 2)
     assert O.model_select(5, 50, 10, fg, None, None, gathered) == (1, 2)
+
+
+def test_iteration_count_is_a_known_feature():
+    """Sec. V (multiple iterations): the number of iterations is available to every
+    predictor.  It is the last entry of both vectors, 1 unless stated, and a tree may
+    split on it."""
+    rp = rp_of([1, 2, 3])
+    assert O.features(3, 4, rp)["f"][IDX["iterations"]] == 1
+    assert O.features(3, 4, rp, iterations=19)["f"][IDX["iterations"]] == 19
+    assert np.array_equal(O.features(3, 4, rp, iterations=19)["f"][:12], O.features(3, 4, rp)["f"][:12])
+    kf = O.known_features(3, 4, 6, iterations=19)
+    assert kf[IDX["iterations"]] == 19 and kf[IDX["nnz"]] == 6
+    # known: iterations <= 18.5 ? kernel 4 : kernel 5 (preprocessing amortised from 19 on)
+    known = ([12, -1, -1], [18.5, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 4, 5])
+    selector = ([-1], [0.0], [-1], [-1], [0])
+    fg = O.features(3, 4, rp, iterations=19)["f"]
+    assert O.model_select(3, 4, 6, fg, selector, known, known, iterations=18) == (0, 4)
+    assert O.model_select(3, 4, 6, fg, selector, known, known, iterations=19) == (0, 5)
