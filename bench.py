@@ -98,7 +98,8 @@ class Rotation:
         self.sets = []
         base = S.DeviceCSR.from_host(A)
         xb = torch.from_numpy(x).cuda()
-        ws_bytes = max(S.spmv_auto_workspace_bytes(A.rows, A.nnz), S.features_workspace_bytes(A.rows))
+        ws_bytes = max([S.spmv_auto_workspace_bytes(A.rows, A.nnz), S.features_workspace_bytes(A.rows)] +
+                       [S.spmv_workspace_bytes(k, A.rows, A.nnz) for k in range(S.NUM_KERNELS)])
         for i in range(n):
             d = base if i == 0 else S.DeviceCSR(A.rows, A.cols, base.row_ptr.clone(), base.col_idx.clone(),
                                                 base.values.clone(), A.nnz)
@@ -191,7 +192,7 @@ def selector_eval(model, meta, count):
         dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
         ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(dA.rows, dA.nnz))
         y = torch.empty(dA.rows, device="cuda:0")
-        tk.append([T.time_kernel_us(k, dA, x, y, ws) for k in range(S.NUM_KERNELS)])
+        tk.append([T.time_kernel_us(k, dA, x, y, ws) for k in range(S.NUM_DIRECT_KERNELS)])
         ta.append(T.time_graph_us(lambda: S.seer_spmv_auto(dA, model.gathered, x, y, ws)))
         tm.append(T.time_graph_us(lambda: S.seer_spmv_model(dA, model, x, y, ws)))
         del rp, ci, va, x, dA, y, ws

@@ -51,7 +51,12 @@ enum {
                         nonzeros staged through LDS                                   */
     SEER_CSR_MP = 3, /* merge path: equal shares of rows + nonzeros (Table III's CSR,MP) */
     SEER_CSR_WO = 4, /* work oriented: equal shares of nonzeros (Table III's CSR,WO)   */
-    SEER_NUM_KERNELS = 5
+    SEER_NUM_DIRECT_KERNELS = 5, /* ids below this need no preprocessing               */
+    SEER_CSR_A = 5,  /* adaptive: row blocks of about 2048 nonzeros found in a
+                        preprocessing pass over row_ptr, long rows split between
+                        blocks (Table II's Adaptive-CSR (A); Sec. IV on its
+                        preprocessing and when it is amortised)                        */
+    SEER_NUM_KERNELS = 6
 };
 
 /* CSR matrix, fp32 values, int32 indices.  All pointers DEVICE, caller-owned.
@@ -67,12 +72,16 @@ typedef struct {
 /* Feature vector indices.  0-2 are the "known" features of Sec. IV (rows, columns,
  * nonzeros); 8-11 are the gathered row-density statistics named there (density of
  * a row = its nonzero count / cols, Sec. IV-A); 3-7 are the same statistics on
- * row lengths (Table III: Most, Least, Avg, Var) plus the fraction of empty rows. */
+ * row lengths (Table III: Most, Least, Avg, Var) plus the fraction of empty rows;
+ * 12 is the number of products the caller is about to run with this matrix, known
+ * to every model at no cost (Sec. V, multiple iteration evaluation).  Every call here
+ * that fills a vector writes 1 there; seer_spmv_plan writes the caller's count. */
 enum {
     SEER_F_ROWS = 0, SEER_F_COLS, SEER_F_NNZ,
     SEER_F_MEAN_LEN, SEER_F_MAX_LEN, SEER_F_MIN_LEN, SEER_F_VAR_LEN, SEER_F_EMPTY_FRAC,
     SEER_F_MEAN_DENSITY, SEER_F_MAX_DENSITY, SEER_F_MIN_DENSITY, SEER_F_VAR_DENSITY,
-    SEER_NUM_FEATURES = 12
+    SEER_F_ITERATIONS,
+    SEER_NUM_FEATURES = 13
 };
 
 /* HOST struct filled by seer_features.  Integer fields are exact.  f[] is derived
@@ -140,7 +149,9 @@ int seer_select(const seer_features_t *f, const seer_tree *tree, int *kernel_id)
  * valid for every matrix and gives the same y up to fp32 summation order.
  * rows == 0: nothing is written.  Asynchronous on `stream`.
  * workspace: at least seer_spmv_workspace_bytes(kernel_id, rows, nnz) bytes (0 for
- * ids 0-2, then workspace may be NULL). */
+ * ids 0-2, then workspace may be NULL).
+ * SEER_CSR_A in this single call runs its preprocessing pass first, every time (what
+ * one product with it costs); seer_spmv_prepare / seer_spmv_prepared split the two. */
 int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y,
               void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
@@ -153,8 +164,9 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
  * collection (Sec. III-C) cut down to the reduction kernel itself.
  * y is the same as seer_spmv would give with the id seer_select would return for
  * the features seer_features would return (all three bit for bit).
- * tree: HOST, at most 127 nodes and SEER_NUM_KERNELS classes, no cycles (SEER_ETREE
- * otherwise; validated before anything is enqueued).
+ * tree: HOST, at most 127 nodes, no cycles, every leaf a kernel id below
+ * SEER_NUM_DIRECT_KERNELS (SEER_ETREE otherwise; validated before anything is
+ * enqueued).  f[SEER_F_ITERATIONS] is 1 on this path.
  * workspace: DEVICE, 16-byte aligned, >= seer_spmv_auto_workspace_bytes(rows, nnz);
  * it must stay untouched until the work has run. */
 int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y,
@@ -178,6 +190,7 @@ typedef struct {
  * applied on the device (seer_spmv_auto).  Asynchronous on `stream` either way.
  * *path (may be NULL) receives 0 or 1; *kernel_id (may be NULL) receives the kernel id
  * when the known model was used and -1 otherwise (ask seer_spmv_auto_result then).
+ * Both models must answer with ids below SEER_NUM_DIRECT_KERNELS (SEER_ETREE).
  * workspace: >= seer_spmv_auto_workspace_bytes(rows, nnz). */
 int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, float *y,
                     void *workspace, size_t workspace_bytes, void *stream,
@@ -189,6 +202,59 @@ int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, 
 int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *features,
                           int *kernel_id);
 
+/* Preprocessing split from the product (Sec. IV: a preprocessing step that occurs once
+ * over the span of the iterations and is amortised from some iteration count on).
+ * A seer_plan is a HOST struct the caller owns; `device` points into the caller's
+ * plan_mem.  It belongs to the matrix it was prepared for (same row_ptr contents) and
+ * stays valid until plan_mem is reused. */
+typedef struct {
+    int32_t kernel_id;
+    int32_t rows, nnz;    /* of the matrix it was prepared for                          */
+    int32_t n_blocks;     /* SEER_CSR_A: row blocks in the plan                         */
+    int32_t split_rows;   /* SEER_CSR_A: 1 if some row is shared between blocks (the
+                             product then needs the carry workspace and a second launch) */
+    int32_t reserved;
+    void *device;         /* DEVICE, inside plan_mem; NULL for kernels without a plan   */
+    size_t device_bytes;
+} seer_plan;
+
+/* Device bytes seer_spmv_prepare needs for `kernel_id` (0 for ids that need none). */
+size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz);
+
+/* Runs the preprocessing of `kernel_id` for A on `stream` and fills *plan.  For
+ * SEER_CSR_A: one pass over A->row_ptr that writes, for block k = 0 .. n-1 of
+ * n = max(1, ceil(nnz / 2048)), the pair {first row, first nonzero}:
+ *   block 0 starts at row 0, nonzero 0; block k > 0 starts with the first row that ends
+ *   after nonzero 2048 k, at that row's first nonzero, or at nonzero 2048 k if the row
+ *   also began block k - 1 (such a block holds nothing but part of that row);
+ *   entry n is {rows, nnz}.
+ * HOST-SYNCHRONOUS: returns after the pass has finished (it reads back whether any row
+ * is split).  plan_mem: DEVICE, 16-byte aligned, >= seer_plan_bytes(); may be NULL for
+ * kernels that need no plan (the call then only records the id).  Not capturable. */
+int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes,
+                      void *stream, seer_plan *plan);
+
+/* y = A x with a prepared plan; same contract as seer_spmv.  For kernels without
+ * preprocessing this is seer_spmv(plan->kernel_id, ...).  Asynchronous, capturable.
+ * workspace: >= seer_spmv_prepared_workspace_bytes(plan) (0 for SEER_CSR_A when no row
+ * is split).  SEER_EINVAL if rows / nnz differ from the matrix the plan was made for. */
+int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x, float *y,
+                       void *workspace, size_t workspace_bytes, void *stream);
+size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan);
+
+/* Selection for `iterations` >= 1 products with the same matrix (Sec. V, multiple
+ * iteration evaluation): classifier-selection inference as in seer_spmv_model, with
+ * f[SEER_F_ITERATIONS] = iterations in the vector every tree sees, so a model trained on
+ * (preprocessing + iterations * run time) can tell when preprocessing is amortised; then
+ * seer_spmv_prepare for the chosen kernel.  The features, when the selector asks for
+ * them, are gathered with seer_features.  HOST-SYNCHRONOUS.  Any kernel id may be
+ * chosen.  *path (may be NULL): 0 known model, 1 gathered model.
+ * workspace: >= seer_features_workspace_bytes(rows); plan_mem: >= seer_plan_bytes(
+ * SEER_CSR_A, rows, nnz) unless the model cannot answer SEER_CSR_A. */
+int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iterations,
+                   void *plan_mem, size_t plan_bytes, void *workspace, size_t workspace_bytes,
+                   void *stream, seer_plan *plan, int *path);
+
 /* Launch-shape overrides for experiments; the defaults (value < 0) derive every
  * launch shape from rows and nnz alone (the trivially known sizes of Sec. III-A).
  *   "wm_lanes"  lanes per row of CSR,WM: 2, 4, 8, 16, 32 or 64
@@ -198,6 +264,9 @@ int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *
  *   "xcd_remap" 1: consecutive tiles stay on one XCD (default), 0: round-robin
  *   "nt"        1: CSR,BM / CSR,MP load the matrix streams with the non-temporal
  *               hint (default), 0: plain loads
+ *   "vec"       0: CSR,BM / CSR,MP / CSR,WO / CSR,A take entries with lane-strided 4-byte
+ *               loads instead of 16-byte loads (what matrices whose col_idx / values
+ *               are not 16-byte aligned get anyway); default 1
  *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise
  *               (default) it first watches its pinned result word for up to 2 ms
  * Unknown name: SEER_EINVAL.  A value outside the listed set selects the default. */

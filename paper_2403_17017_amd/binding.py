@@ -16,13 +16,15 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libseer.so")
 
-NUM_FEATURES = 12
-NUM_KERNELS = 5
-CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO = range(5)
+NUM_FEATURES = 13
+NUM_KERNELS = 6
+NUM_DIRECT_KERNELS = 5          # ids below this need no preprocessing
+CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A = range(6)
 FEATURE_NAMES = (
     "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
-    "mean_density", "max_density", "min_density", "var_density",
+    "mean_density", "max_density", "min_density", "var_density", "iterations",
 )
+F_ITERATIONS = 12
 
 
 class SeerError(RuntimeError):
@@ -65,6 +67,12 @@ class seer_tree(C.Structure):
                 ("nodes", C.POINTER(seer_node))]
 
 
+class seer_plan(C.Structure):
+    _fields_ = [("kernel_id", C.c_int32), ("rows", C.c_int32), ("nnz", C.c_int32), ("n_blocks", C.c_int32),
+                ("split_rows", C.c_int32), ("reserved", C.c_int32), ("device", C.c_void_p),
+                ("device_bytes", C.c_size_t)]
+
+
 seer_model._fields_ = [("selector", C.POINTER(seer_tree)), ("known", C.POINTER(seer_tree)),
                        ("gathered", C.POINTER(seer_tree))]
 
@@ -104,6 +112,17 @@ def lib():
         L.seer_spmv_model.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_model), vp, vp, vp, sz, vp,
                                       C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.seer_spmv_model.restype = C.c_int
+        L.seer_plan_bytes.argtypes = [C.c_int, i32, i32]
+        L.seer_plan_bytes.restype = sz
+        L.seer_spmv_prepare.argtypes = [C.c_int, C.POINTER(seer_csr), vp, sz, vp, C.POINTER(seer_plan)]
+        L.seer_spmv_prepare.restype = C.c_int
+        L.seer_spmv_prepared.argtypes = [C.POINTER(seer_plan), C.POINTER(seer_csr), vp, vp, vp, sz, vp]
+        L.seer_spmv_prepared.restype = C.c_int
+        L.seer_spmv_prepared_workspace_bytes.argtypes = [C.POINTER(seer_plan)]
+        L.seer_spmv_prepared_workspace_bytes.restype = sz
+        L.seer_spmv_plan.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_model), i32, vp, sz, vp, sz, vp,
+                                     C.POINTER(seer_plan), C.POINTER(C.c_int)]
+        L.seer_spmv_plan.restype = C.c_int
         L.seer_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.seer_set_tuning.restype = C.c_int
         L.seer_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -323,3 +342,74 @@ def seer_spmv_model(A: DeviceCSR, model: Model, x, y, workspace, stream=None):
     if rc:
         raise SeerError(rc, "seer_spmv_model")
     return int(path.value), int(kid.value)
+
+
+class Plan:
+    """A prepared kernel for one matrix: the host-side record plus the device memory
+    the preprocessing wrote (kept alive here)."""
+
+    def __init__(self, c: seer_plan, plan_mem):
+        self.c, self.plan_mem = c, plan_mem
+
+    kernel_id = property(lambda self: int(self.c.kernel_id))
+    n_blocks = property(lambda self: int(self.c.n_blocks))
+    split_rows = property(lambda self: bool(self.c.split_rows))
+
+    def entries(self) -> np.ndarray:
+        """The (first row, first nonzero) pairs as an int32 [n_blocks + 1, 2] host array."""
+        import torch
+        n = (self.n_blocks + 1) * 2
+        return self.plan_mem[: n * 4].view(torch.int32).cpu().numpy().reshape(-1, 2)
+
+
+def plan_bytes(kernel_id: int, rows: int, nnz: int) -> int:
+    return int(lib().seer_plan_bytes(kernel_id, rows, nnz))
+
+
+def seer_spmv_prepare(kernel_id: int, A: DeviceCSR, plan_mem=None, stream=None) -> Plan:
+    """Runs the preprocessing of kernel_id for A (waits for it) and returns the plan."""
+    need = plan_bytes(kernel_id, A.rows, A.nnz)
+    if plan_mem is None and need:
+        plan_mem = alloc_workspace(need, A.row_ptr.device)
+    cs = A.c_struct()
+    c = seer_plan()
+    rc = lib().seer_spmv_prepare(int(kernel_id), C.byref(cs), plan_mem.data_ptr() if plan_mem is not None else None,
+                                 plan_mem.numel() if plan_mem is not None else 0, _stream_ptr(stream), C.byref(c))
+    if rc:
+        raise SeerError(rc, f"seer_spmv_prepare(kernel {kernel_id})")
+    return Plan(c, plan_mem)
+
+
+def spmv_prepared_workspace_bytes(plan: Plan) -> int:
+    return int(lib().seer_spmv_prepared_workspace_bytes(C.byref(plan.c)))
+
+
+def seer_spmv_prepared(plan: Plan, A: DeviceCSR, x, y, workspace=None, stream=None) -> None:
+    """y = A x with a prepared plan; asynchronous on the stream."""
+    need = spmv_prepared_workspace_bytes(plan)
+    if need and workspace is None:
+        workspace = alloc_workspace(need, A.row_ptr.device)
+    cs = A.c_struct()
+    rc = lib().seer_spmv_prepared(C.byref(plan.c), C.byref(cs), x.data_ptr(), y.data_ptr(),
+                                  workspace.data_ptr() if workspace is not None else None,
+                                  workspace.numel() if workspace is not None else 0, _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, f"seer_spmv_prepared(kernel {plan.kernel_id})")
+
+
+def seer_spmv_plan(A: DeviceCSR, model: Model, iterations: int, plan_mem=None, workspace=None, stream=None):
+    """Selection for `iterations` products, then the chosen kernel's preprocessing.
+    Returns (plan, path): path 0 = known model, 1 = features were gathered."""
+    if plan_mem is None:
+        plan_mem = alloc_workspace(plan_bytes(CSR_A, A.rows, A.nnz), A.row_ptr.device)
+    if workspace is None:
+        workspace = alloc_workspace(features_workspace_bytes(A.rows), A.row_ptr.device)
+    cs = A.c_struct()
+    c = seer_plan()
+    path = C.c_int(-1)
+    rc = lib().seer_spmv_plan(C.byref(cs), C.byref(model.c), int(iterations), plan_mem.data_ptr(), plan_mem.numel(),
+                              workspace.data_ptr(), workspace.numel(), _stream_ptr(stream), C.byref(c),
+                              C.byref(path))
+    if rc:
+        raise SeerError(rc, "seer_spmv_plan")
+    return Plan(c, plan_mem), int(path.value)

@@ -38,6 +38,14 @@ size_t carry_workspace_bytes(uint32_t n_tiles);
 void launch_carry_fixup(int rows, uint32_t n_tiles, const int *carry_row, const float *carry_val, float *y,
                         hipStream_t st);
 
+// adaptive (row blocks found by a preprocessing pass).  plan_mem: adaptive_plan_bytes();
+// carry_ws: carry_workspace_bytes(adaptive_num_tiles()) or null when the plan has no split row
+uint32_t adaptive_num_tiles(int rows, int nnz);
+size_t adaptive_plan_bytes(int rows, int nnz);
+int *adaptive_split_flag(void *plan_mem, int rows, int nnz);
+void launch_adaptive_plan(int rows, int nnz, const int *rp, void *plan_mem, bool want_flag, hipStream_t st);
+void launch_adaptive(const SpmvArgs &a, bool vec, const void *plan_mem, void *carry_ws, hipStream_t st);
+
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory
     int32_t max_len, min_len;
@@ -71,7 +79,7 @@ struct AutoSel {                            // what the selection kernel leaves 
     float f[SEER_NUM_FEATURES];
 };
 struct AutoShape {                          // launch shapes, all from rows and nnz alone
-    uint32_t tiles[SEER_NUM_KERNELS];
+    uint32_t tiles[SEER_NUM_DIRECT_KERNELS];
     int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
 };
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes

@@ -135,6 +135,7 @@ void derive(seer_features_t *o)
 {
     for (int i = 0; i < SEER_NUM_FEATURES; ++i) o->f[i] = 0.0f;
     o->f[SEER_F_COLS] = (float)(double)o->cols;
+    o->f[SEER_F_ITERATIONS] = 1.0f;
     if (o->rows <= 0) return;
     const double R = (double)o->rows;
     const double mean = (double)o->nnz / R;
@@ -155,6 +156,14 @@ void derive(seer_features_t *o)
         o->f[SEER_F_MIN_DENSITY] = (float)((double)o->min_len / C);
         o->f[SEER_F_VAR_DENSITY] = (float)(var / (C * C));
     }
+}
+
+// every leaf names a kernel id below `limit`
+bool leaves_below(const seer_tree *t, int limit)
+{
+    for (int i = 0; i < t->n_nodes; ++i)
+        if (t->nodes[i].feature < 0 && t->nodes[i].klass >= limit) return false;
+    return true;
 }
 
 int check_tree(const seer_tree *t)
@@ -201,7 +210,7 @@ bool tree_is_acyclic(const seer_tree *t)
     return true;
 }
 
-const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO"};
+const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A"};
 
 } // namespace
 
@@ -247,6 +256,8 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz)
 {
     if (rows <= 0 || nnz < 0) return 0;
     if (kernel_id == SEER_CSR_WO) return carry_workspace_bytes(wo_num_tiles(rows, nnz));
+    if (kernel_id == SEER_CSR_A)   // the carries, then the plan that the call builds for itself
+        return carry_workspace_bytes(adaptive_num_tiles(rows, nnz)) + adaptive_plan_bytes(rows, nnz);
     if (kernel_id != SEER_CSR_MP) return 0;
     // the small tile gives the larger count; cover either choice
     return mp_workspace_bytes(rows, nnz, kMpIptSmall);
@@ -275,6 +286,7 @@ int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t
     o.f[SEER_F_ROWS] = (float)(double)rows;
     o.f[SEER_F_COLS] = (float)(double)cols;
     o.f[SEER_F_NNZ] = (float)(double)nnz;
+    o.f[SEER_F_ITERATIONS] = 1.0f;
     if (rows > 0) {
         const double mean = (double)nnz / (double)rows;
         o.f[SEER_F_MEAN_LEN] = (float)mean;
@@ -371,6 +383,7 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     const int trc = check_tree(tree);
     if (trc != SEER_OK) return trc;
     if (tree->n_nodes > kAutoMaxNodes || tree->n_classes > SEER_NUM_KERNELS) return SEER_ETREE;
+    if (!leaves_below(tree, SEER_NUM_DIRECT_KERNELS)) return SEER_ETREE;
     // a cycle is only found by walking; make sure no walk can be longer than the tree
     if (!tree_is_acyclic(tree)) return SEER_ETREE;
     if (A->rows == 0) return SEER_OK;
@@ -418,6 +431,7 @@ int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, 
             if (model->known->n_classes > SEER_NUM_KERNELS) return SEER_ETREE;
             rc = seer_select(&kf, model->known, &kid);
             if (rc != SEER_OK) return rc;
+            if (kid >= SEER_NUM_DIRECT_KERNELS) return SEER_ETREE;   // needs preprocessing: seer_spmv_plan
         }
     }
     if (A->rows > 0 && (!workspace || !aligned16(workspace) ||
@@ -490,6 +504,16 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *
     case SEER_CSR_TM: launch_tm(a, st); break;
     case SEER_CSR_WM: launch_wm(a, wm_lanes(A->rows, A->nnz), st); break;
     case SEER_CSR_BM: launch_bm(a, bm_rows(A->rows, A->nnz), bm_chunk(), vec, st); break;
+    case SEER_CSR_A: {
+        // single call: the preprocessing pass runs first, on the same stream, every time
+        const size_t carry = carry_workspace_bytes(adaptive_num_tiles(A->rows, A->nnz));
+        if (!workspace || !aligned16(workspace) || workspace_bytes < carry + adaptive_plan_bytes(A->rows, A->nnz))
+            return SEER_EWORKSPACE;
+        void *plan_mem = static_cast<char *>(workspace) + carry;
+        launch_adaptive_plan(A->rows, A->nnz, A->row_ptr, plan_mem, false, st);
+        launch_adaptive(a, vec, plan_mem, workspace, st);
+        break;
+    }
     case SEER_CSR_WO:
         if (!workspace || !aligned16(workspace) ||
             workspace_bytes < carry_workspace_bytes(wo_num_tiles(A->rows, A->nnz)))
@@ -506,6 +530,113 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *
     }
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz)
+{
+    if (kernel_id != SEER_CSR_A || rows <= 0 || nnz < 0) return 0;
+    return adaptive_plan_bytes(rows, nnz);
+}
+
+int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream,
+                      seer_plan *plan)
+{
+    if (!plan) return SEER_EINVAL;
+    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS) return SEER_EKERNEL;
+    const int rc = check_csr(A, true);
+    if (rc != SEER_OK) return rc;
+    std::memset(plan, 0, sizeof *plan);
+    plan->kernel_id = kernel_id;
+    plan->rows = A->rows;
+    plan->nnz = A->nnz;
+    if (kernel_id != SEER_CSR_A || A->rows == 0) return SEER_OK;   // nothing to prepare
+    const size_t need = adaptive_plan_bytes(A->rows, A->nnz);
+    if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int *flag = adaptive_split_flag(plan_mem, A->rows, A->nnz);
+    hipError_t e = hipMemsetAsync(flag, 0, sizeof(int), st);
+    if (e != hipSuccess) return hip_fail(e);
+    launch_adaptive_plan(A->rows, A->nnz, A->row_ptr, plan_mem, true, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    int split = 0;
+    e = hipMemcpyAsync(&split, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    plan->n_blocks = (int32_t)adaptive_num_tiles(A->rows, A->nnz);
+    plan->split_rows = split != 0;
+    plan->device = plan_mem;
+    plan->device_bytes = need;
+    return SEER_OK;
+}
+
+size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan)
+{
+    if (!plan) return 0;
+    if (plan->kernel_id == SEER_CSR_A)
+        return plan->split_rows ? carry_workspace_bytes((uint32_t)plan->n_blocks) : 0;
+    return seer_spmv_workspace_bytes(plan->kernel_id, plan->rows, plan->nnz);
+}
+
+int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x, float *y, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!plan) return SEER_EINVAL;
+    if (plan->kernel_id != SEER_CSR_A)
+        return seer_spmv(plan->kernel_id, A, x, y, workspace, workspace_bytes, stream);
+    const int rc = check_csr(A, true);
+    if (rc != SEER_OK) return rc;
+    if (A->rows != plan->rows || A->nnz != plan->nnz) return SEER_EINVAL;   // a plan belongs to one matrix
+    if (A->rows == 0) return SEER_OK;
+    if (!y || (!x && A->nnz > 0) || !plan->device) return SEER_EINVAL;
+    void *carry = nullptr;
+    if (plan->split_rows) {
+        if (!workspace || !aligned16(workspace) ||
+            workspace_bytes < carry_workspace_bytes((uint32_t)plan->n_blocks))
+            return SEER_EWORKSPACE;
+        carry = workspace;
+    }
+    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt()};
+    const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
+    launch_adaptive(a, vec, plan->device, carry, static_cast<hipStream_t>(stream));
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iterations, void *plan_mem,
+                   size_t plan_bytes, void *workspace, size_t workspace_bytes, void *stream, seer_plan *plan,
+                   int *path)
+{
+    if (!A || !model || !model->gathered || !plan || iterations < 1) return SEER_EINVAL;
+    if (model->selector && !model->known) return SEER_EINVAL;
+    int rc = check_csr(A, true);
+    if (rc != SEER_OK) return rc;
+    int use_gathered = 1, kid = -1;
+    if (model->selector) {
+        seer_features_t kf;
+        rc = seer_known_features(A->rows, A->cols, A->nnz, &kf);
+        if (rc != SEER_OK) return rc;
+        kf.f[SEER_F_ITERATIONS] = (float)iterations;
+        if (model->selector->n_classes > 2) return SEER_ETREE;
+        rc = seer_select(&kf, model->selector, &use_gathered);
+        if (rc != SEER_OK) return rc;
+        if (!use_gathered) {
+            rc = seer_select(&kf, model->known, &kid);
+            if (rc != SEER_OK) return rc;
+        }
+    }
+    if (use_gathered) {
+        seer_features_t gf;
+        rc = seer_features(A, &gf, workspace, workspace_bytes, stream);
+        if (rc != SEER_OK) return rc;
+        gf.f[SEER_F_ITERATIONS] = (float)iterations;
+        rc = seer_select(&gf, model->gathered, &kid);
+        if (rc != SEER_OK) return rc;
+    }
+    if (kid < 0 || kid >= SEER_NUM_KERNELS) return SEER_ETREE;
+    if (path) *path = use_gathered;
+    return seer_spmv_prepare(kid, A, plan_mem, plan_bytes, stream, plan);
 }
 
 } // extern "C"

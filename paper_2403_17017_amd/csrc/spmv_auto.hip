@@ -45,6 +45,7 @@ __device__ __forceinline__ void derive_features_device(
 {
     for (int i = 0; i < SEER_NUM_FEATURES; ++i) f[i] = 0.0f;
     f[SEER_F_COLS] = (float)(double)cols;
+    f[SEER_F_ITERATIONS] = 1.0f;   // this path is the single product
     if (rows <= 0) return;
     const double R = (double)rows;
     const double mean = (double)nnz / R;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
             if (feature < 0) { k = tree.nodes[n].klass; break; }
             n = ((double)s_f[feature] <= tree.nodes[n].threshold) ? tree.nodes[n].left : tree.nodes[n].right;
         }
-        sel->kernel_id = (k >= 0 && k < SEER_NUM_KERNELS) ? k : SEER_CSR_MP;
+        sel->kernel_id = (k >= 0 && k < SEER_NUM_DIRECT_KERNELS) ? k : SEER_CSR_MP;
         sel->valid = 1;
         sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
         sel->max_len = s.mx; sel->min_len = s.mn;
@@ -181,7 +182,7 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
     }
 
     uint32_t grid = 0;
-    for (int k = 0; k < SEER_NUM_KERNELS; ++k) {
+    for (int k = 0; k < SEER_NUM_DIRECT_KERNELS; ++k) {
         const uint32_t g = a.remap ? tiles_per_xcd(shape.tiles[k]) * kXCD : shape.tiles[k];
         grid = g > grid ? g : grid;
     }

@@ -14,6 +14,12 @@ gathering is worth its cost.  The trees are stored as the flat node arrays that
            --model paper_2403_17017_amd/selector_model.json --out gpurun_out/eval.csv
     python -m paper_2403_17017_amd.training export-header      # trees as nested if/else in C
 
+The same sweep also feeds the multiple-iteration models (Sec. V): for every matrix
+and every iteration count n of a fixed grid the label is the kernel with the smallest
+preprocessing + n * run time, the iteration count is one more known feature, and the
+feature collection is paid once.  Those three trees are stored under "iterative" and are
+what `seer_spmv_plan` walks.
+
 Timing protocol as in Sec. IV-B: 10 warm-up runs, mean of 10 timed runs, on the same
 buffers; the timed runs are replayed from a HIP graph so that kernel time, not host
 launch time, is compared.  Feature collection is timed as the caller sees it (the
@@ -33,10 +39,18 @@ import numpy as np
 from . import binding as S
 
 MAX_DEPTH = 6   # fixed before looking at any test data (the paper caps depth, value unstated)
+# t_k{k}_us is the time of one product; for a kernel with preprocessing that is the
+# product with a prepared plan, t_prep_k{k}_us the seer_spmv_prepare call as the caller
+# sees it, t_single_k{k}_us the one-call form that prepares and multiplies.
+PREP_KERNELS = [S.CSR_A]
 CSV_FIELDS = (["m", "family", "rows", "cols", "nnz"] + [f"f_{n}" for n in S.FEATURE_NAMES]
               + ["t_features_us"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)]
+              + [f"t_prep_k{k}_us" for k in PREP_KERNELS] + [f"t_single_k{k}_us" for k in PREP_KERNELS]
               + ["t_auto_mp_us", "max_disagreement"])
 KNOWN_IDX = [0, 1, 2, 3, 8]   # rows, cols, nnz, mean_len, mean_density: what seer_known_features fills
+KNOWN_ITER_IDX = KNOWN_IDX + [S.F_ITERATIONS]
+ITER_GRID = [1, 2, 3, 5, 8, 12, 19, 30, 50, 100]   # iteration counts the iterative models are trained on
+ND = S.NUM_DIRECT_KERNELS
 
 
 def time_kernel_us(kid, dA, x, y, ws, warmup=10, reps=10):
@@ -76,6 +90,15 @@ def time_graph_us(enqueue, warmup=3, reps=10):
     return e0.elapsed_time(e1) * 1e3 / reps
 
 
+def time_prepare_us(kid, dA, plan_mem, warmup=3, reps=10):
+    for _ in range(warmup):
+        plan = S.seer_spmv_prepare(kid, dA, plan_mem)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        plan = S.seer_spmv_prepare(kid, dA, plan_mem)
+    return (time.perf_counter() - t0) / reps * 1e6, plan
+
+
 def time_features_us(dA, ws, warmup=3, reps=10):
     for _ in range(warmup):
         f = S.seer_features(dA, workspace=ws)
@@ -92,8 +115,8 @@ def measure_matrix(spec, device="cuda:0"):
     from workloads.sweep_gen import build_on_device
     rp, ci, va, x = build_on_device(spec, device)
     dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
-    ws = S.alloc_workspace(max(S.spmv_auto_workspace_bytes(dA.rows, dA.nnz),
-                               S.features_workspace_bytes(dA.rows)), device)
+    ws = S.alloc_workspace(max([S.spmv_auto_workspace_bytes(dA.rows, dA.nnz), S.features_workspace_bytes(dA.rows)]
+                               + [S.spmv_workspace_bytes(k, dA.rows, dA.nnz) for k in range(S.NUM_KERNELS)]), device)
     t_feat, f = time_features_us(dA, ws)
     row = {"m": spec.m, "family": spec.family, "rows": dA.rows, "cols": dA.cols, "nnz": dA.nnz,
            "t_features_us": round(t_feat, 3)}
@@ -102,7 +125,14 @@ def measure_matrix(spec, device="cuda:0"):
     ys = []
     for k in range(S.NUM_KERNELS):
         y = torch.empty(dA.rows, device=device)
-        row[f"t_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
+        if k in PREP_KERNELS:
+            plan_mem = S.alloc_workspace(S.plan_bytes(k, dA.rows, dA.nnz), device)
+            t_prep, plan = time_prepare_us(k, dA, plan_mem)
+            row[f"t_prep_k{k}_us"] = round(t_prep, 3)
+            row[f"t_single_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
+            row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws), warmup=10), 3)
+        else:
+            row[f"t_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
         ys.append(y)
     # the asynchronous path with a constant tree: its excess over the bare kernel is the
     # device-side cost of gathering and selecting
@@ -110,7 +140,8 @@ def measure_matrix(spec, device="cuda:0"):
     row["t_auto_mp_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, mp_only, x, ys[3], ws)), 3)
     # the schedules must agree with each other (a sanity check, not the parity test)
     scale = float(ys[3].abs().max().item()) + 1e-30
-    row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item() for k in range(S.NUM_KERNELS) if k != 3) / scale)
+    row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item()
+                                        for k in range(S.NUM_KERNELS) if k != 3) / scale)
     return row
 
 
@@ -145,6 +176,14 @@ def load_csv(path):
     T = np.array([[float(r[f"t_k{k}_us"]) for k in range(S.NUM_KERNELS)] for r in rows])
     tf = np.array([float(r["t_features_us"]) for r in rows])
     return rows, X, T, tf
+
+
+def load_prep(rows):
+    """Preprocessing time per matrix and kernel (zero for kernels that have none)."""
+    P = np.zeros((len(rows), S.NUM_KERNELS))
+    for k in PREP_KERNELS:
+        P[:, k] = [float(r[f"t_prep_k{k}_us"]) for r in rows]
+    return P
 
 
 def gather_overhead_us(rows_csv, T):
@@ -208,7 +247,7 @@ def _fit(X, y, cols=None, weight=None):
     Xs = X if cols is None else X[:, cols]
     clf = DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0).fit(Xs, y, sample_weight=weight)
     tree = tree_to_arrays(clf)
-    if cols is not None:   # the stored tree indexes the full 12-entry vector
+    if cols is not None:   # the stored tree indexes the full feature vector
         tree["feature"] = [cols[f] if f >= 0 else -1 for f in tree["feature"]]
     assert np.array_equal(predict_with_arrays(tree, X), clf.predict(Xs))
     return tree
@@ -247,7 +286,9 @@ def model_report(T, ovh, pred_known, pred_gath, use_gath):
 
 def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
     from sklearn.model_selection import train_test_split
-    rows, X, T, tf = load_csv(csv_path)
+    rows, X, T_all, tf = load_csv(csv_path)
+    P = load_prep(rows)
+    T = T_all[:, :ND]               # the single-product models choose among the kernels without preprocessing
     y = T.argmin(axis=1)            # label = fastest kernel; ties -> lowest kernel id
     idx = np.arange(len(rows))
     tr, te = train_test_split(idx, test_size=test_frac, random_state=seed)
@@ -284,7 +325,8 @@ def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
         "note": f"CART gini max_depth={MAX_DEPTH}, {len(tr)} training matrices",
         "feature_names": list(S.FEATURE_NAMES), "known_features": KNOWN_IDX,
         "gather_overhead_us": {"intercept": ovh_fit[0], "per_row": ovh_fit[1]},
-        "label_counts": np.bincount(y, minlength=S.NUM_KERNELS).tolist(),
+        "label_counts": np.bincount(y, minlength=ND).tolist(),
+        "iterative": fit_iterative(X, T_all, P, tf, tr, te),
         "report": {"train": model_report(T[tr], ovh[tr], pk[tr], pg[tr], ug[tr]),
                    "test": model_report(T[te], ovh[te], pk[te], pg[te], ug[te]),
                    "all": model_report(T, ovh, pk, pg, ug)},
@@ -293,6 +335,91 @@ def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
     with open(out_json, "w") as fh:
         json.dump(model, fh, indent=1)
     return model
+
+
+def iterative_report(C, tf, pred_known, pred_gath, use_gath):
+    """Times for n products per matrix: C[m, k] = preprocessing + n * run time.  The
+    gathered model pays the feature collection once, the classifier-selection model only
+    where the selector asks for it."""
+    idx = np.arange(len(C))
+    t_known = C[idx, pred_known]
+    t_gath = C[idx, pred_gath] + tf
+    t_model = np.where(use_gath == 1, t_gath, t_known)
+    t_fixed = C.sum(axis=0)
+    best = int(np.argmin(t_fixed))
+    truth = C.argmin(axis=1)
+    chosen = np.where(use_gath == 1, pred_gath, pred_known)
+    prep = np.isin(chosen, PREP_KERNELS)
+    geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
+    return {
+        "matrices": int(len(C)),
+        "accuracy": {"known": float(np.mean(pred_known == truth)), "gathered": float(np.mean(pred_gath == truth)),
+                     "classifier_selection": float(np.mean(chosen == truth))},
+        # did the model call the amortisation right: preprocessing chosen iff it pays
+        "amortisation_accuracy": float(np.mean(prep == np.isin(truth, PREP_KERNELS))),
+        "preprocessing_chosen_fraction": float(np.mean(prep)),
+        "preprocessing_best_fraction": float(np.mean(np.isin(truth, PREP_KERNELS))),
+        "gathered_fraction": float(np.mean(use_gath)),
+        "t_us": {"known": float(t_known.sum()), "gathered": float(t_gath.sum()),
+                 "classifier_selection": float(t_model.sum()), "oracle": float(C.min(axis=1).sum()),
+                 "fixed": [float(v) for v in t_fixed]},
+        "best_fixed_kernel": best,
+        "aggregate_speedup_vs_best_fixed": float(t_fixed[best] / t_model.sum()),
+        "per_matrix_geomean_vs_best_fixed": geo(C[:, best], t_model),
+        "time_lost_vs_oracle": float(t_model.sum() / C.min(axis=1).sum()),
+    }
+
+
+def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
+    """The three trees for n products with one matrix (Sec. V): every training matrix
+    appears once per iteration count of the grid, labelled with the kernel of least
+    preprocessing + n * run time among all kernels; folds are split by matrix."""
+    from sklearn.model_selection import GroupKFold, cross_val_predict
+    from sklearn.tree import DecisionTreeClassifier
+
+    def expand(sel):
+        Xe = np.repeat(X[sel], len(grid), axis=0)
+        n = np.tile(np.array(grid, dtype=np.float64), len(sel))
+        Xe[:, S.F_ITERATIONS] = n.astype(np.float32)
+        C = np.repeat(P[sel], len(grid), axis=0) + n[:, None] * np.repeat(T[sel], len(grid), axis=0)
+        return Xe, C, np.repeat(tf[sel], len(grid)), np.repeat(sel, len(grid)), n
+
+    Xtr, Ctr, tftr, gtr, _ = expand(tr)
+    ytr = Ctr.argmin(axis=1)
+    Xk = np.zeros_like(Xtr)
+    Xk[:, KNOWN_ITER_IDX] = Xtr[:, KNOWN_ITER_IDX]
+    regret = Ctr.mean(axis=1) - Ctr.min(axis=1) + 1e-3
+    # every (matrix, n) sample counts by the time at stake on it, for both models: with
+    # n in the label a wrong choice at n = 100 costs a hundred times the one at n = 1
+    gathered = _fit(Xtr, ytr, weight=regret)
+    known = _fit(Xk, ytr, KNOWN_ITER_IDX, weight=regret)
+    mk = lambda: DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0)
+    cv = GroupKFold(n_splits=5)
+    oof_k = cross_val_predict(mk(), Xk[:, KNOWN_ITER_IDX], ytr, cv=cv, groups=gtr, params={"sample_weight": regret})
+    oof_g = cross_val_predict(mk(), Xtr, ytr, cv=cv, groups=gtr, params={"sample_weight": regret})
+    idx = np.arange(len(Ctr))
+    t_if_gather, t_if_known = Ctr[idx, oof_g] + tftr, Ctr[idx, oof_k]
+    want = (t_if_gather < t_if_known).astype(int)
+    selector = _fit(Xk, want, KNOWN_ITER_IDX, weight=np.abs(t_if_gather - t_if_known) + 1e-3)
+    if len(set(want)) == 1:
+        selector["klass"] = [int(want[0]) if k >= 0 else -1 for k in selector["klass"]]
+
+    def report(sel):
+        out = {}
+        for n in grid:
+            Xe = X[sel].copy()
+            Xe[:, S.F_ITERATIONS] = n
+            Xke = np.zeros_like(Xe)
+            Xke[:, KNOWN_ITER_IDX] = Xe[:, KNOWN_ITER_IDX]
+            C = P[sel] + n * T[sel]
+            out[str(n)] = iterative_report(C, tf[sel], predict_with_arrays(known, Xke),
+                                           predict_with_arrays(gathered, Xe), predict_with_arrays(selector, Xke))
+        return out
+
+    return {"gathered": gathered, "known": known, "selector": selector, "iterations_grid": list(grid),
+            "known_features": KNOWN_ITER_IDX,
+            "label_counts": np.bincount(ytr, minlength=S.NUM_KERNELS).tolist(),
+            "report": {"train": report(tr), "test": report(te)}}
 
 
 def fit_tree(csv_path, out_json, test_frac=0.2, seed=0):
@@ -311,7 +438,7 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
 
     from workloads.sweep_gen import build_on_device, sweep_spec
     model, meta = load_model(model_json)
-    fields = ["m", "family", "rows", "nnz"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)] + \
+    fields = ["m", "family", "rows", "nnz"] + [f"t_k{k}_us" for k in range(ND)] + \
              ["t_auto_us", "t_model_us", "auto_kernel", "model_path", "model_kernel"]
     with open(out_csv, "w", newline="") as fh:
         w = csv.DictWriter(fh, fieldnames=fields)
@@ -323,7 +450,7 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
             ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(dA.rows, dA.nnz))
             y = torch.empty(dA.rows, device="cuda:0")
             row = {"m": m, "family": spec.family, "rows": dA.rows, "nnz": dA.nnz}
-            for k in range(S.NUM_KERNELS):
+            for k in range(ND):
                 row[f"t_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
             row["t_auto_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, model.gathered, x, y, ws)), 3)
             _, row["auto_kernel"] = S.seer_spmv_auto_result(ws)
@@ -333,7 +460,7 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
                 _, row["model_kernel"] = S.seer_spmv_auto_result(ws)
             w.writerow(row)
             fh.flush()
-            print(f"[eval] m={m} {spec.family} nnz={dA.nnz} kernels={[row[f't_k{k}_us'] for k in range(S.NUM_KERNELS)]} "
+            print(f"[eval] m={m} {spec.family} nnz={dA.nnz} kernels={[row[f't_k{k}_us'] for k in range(ND)]} "
                   f"auto={row['t_auto_us']} (k{row['auto_kernel']}) model={row['t_model_us']} "
                   f"(path {row['model_path']}, k{row['model_kernel']})", file=log, flush=True)
     return summarize_evaluation(out_csv)
@@ -342,7 +469,7 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
 def summarize_evaluation(eval_csv):
     with open(eval_csv) as fh:
         rows = list(csv.DictReader(fh))
-    T = np.array([[float(r[f"t_k{k}_us"]) for k in range(S.NUM_KERNELS)] for r in rows])
+    T = np.array([[float(r[f"t_k{k}_us"]) for k in range(ND)] for r in rows])
     ta = np.array([float(r["t_auto_us"]) for r in rows])
     tm = np.array([float(r["t_model_us"]) for r in rows])
     t_fixed = T.sum(axis=0)
@@ -379,24 +506,28 @@ def _emit_node(tree, n, depth, lines):
 def export_header(model_json, out_h, prefix="seer_model"):
     """Writes the trained trees as a C header of nested if/else statements (the form the
     paper deploys its models in, Sec. III-D): one `static inline int <prefix>_<tree>(const
-    float *f)` per tree, f being the 12-entry feature vector.  Readable, diffable, and
+    float *f)` per tree, f being the 13-entry feature vector.  Readable, diffable, and
     equivalent to walking the node arrays."""
     with open(model_json) as fh:
         m = json.load(fh)
     names = m.get("feature_names", list(S.FEATURE_NAMES))
     lines = ["/* Generated by paper_2403_17017_amd.training export-header; do not edit.",
              f" * {m.get('note', '')}", " * Feature vector f[]: " + ", ".join(f"{i} {n}" for i, n in enumerate(names)),
-             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO;",
+             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO  5 CSR,A;",
              " * the selector returns 0 = use the known model, 1 = gather features first. */",
              "#ifndef SEER_MODEL_GENERATED_H", "#define SEER_MODEL_GENERATED_H", ""]
-    for key in ("known", "gathered", "selector"):
-        if key not in m:
-            continue
-        lines.append(f"static inline int {prefix}_{key}(const float *f)")
-        lines.append("{")
-        _emit_node(m[key], 0, 1, lines)
-        lines.append("}")
-        lines.append("")
+    groups = [("", m)] + ([("_iterative", m["iterative"])] if "iterative" in m else [])
+    for suffix, grp in groups:
+        if suffix:
+            lines += ["/* Models for several products with one matrix: f[12] is the iteration count. */", ""]
+        for key in ("known", "gathered", "selector"):
+            if key not in grp:
+                continue
+            lines.append(f"static inline int {prefix}{suffix}_{key}(const float *f)")
+            lines.append("{")
+            _emit_node(grp[key], 0, 1, lines)
+            lines.append("}")
+            lines.append("")
     lines.append("#endif")
     with open(out_h, "w") as fh:
         fh.write("\n".join(lines) + "\n")
@@ -407,12 +538,15 @@ def _tree_from(d):
     return S.Tree(d["feature"], d["threshold"], d["left"], d["right"], d["klass"])
 
 
-def load_model(path):
+def load_model(path, iterative=False):
+    """The single-product model, or with iterative=True the one for several products
+    with one matrix (what seer_spmv_plan takes)."""
     with open(path) as fh:
         m = json.load(fh)
-    sel = _tree_from(m["selector"])
+    grp = m["iterative"] if iterative else m
+    sel = _tree_from(grp["selector"])
     sel.c.n_classes = 2
-    return S.Model(_tree_from(m["gathered"]), _tree_from(m["known"]), sel), m
+    return S.Model(_tree_from(grp["gathered"]), _tree_from(grp["known"]), sel), m
 
 
 def load_tree(path):

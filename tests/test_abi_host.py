@@ -32,15 +32,16 @@ def test_header_symbols_are_exported():
 
 def test_struct_layouts_match_header():
     assert C.sizeof(B.seer_csr) == 40
-    assert C.sizeof(B.seer_features_t) == 7 * 8 + 12 * 4
+    assert C.sizeof(B.seer_features_t) == 7 * 8 + 13 * 4 + 4      # 13 floats, padded to 8
+    assert C.sizeof(B.seer_plan) == 6 * 4 + 8 + 8 and B.seer_plan.device.offset == 24
     assert C.sizeof(B.seer_node) == 24 and B.seer_node.threshold.offset == 16
     assert C.sizeof(B.seer_tree) == 24
 
 
 def test_names_and_errors():
-    assert S.lib().seer_num_kernels() == 5
-    assert [S.kernel_name(k) for k in range(5)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO"]
-    assert S.lib().seer_kernel_name(5) is None
+    assert S.lib().seer_num_kernels() == 6 == S.NUM_KERNELS
+    assert [S.kernel_name(k) for k in range(6)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A"]
+    assert S.lib().seer_kernel_name(6) is None
     assert S.strerror(0) == "ok" and "tree" in S.strerror(-3)
     with pytest.raises(S.SeerError):
         S.set_tuning("no_such_knob", 1)
@@ -158,8 +159,8 @@ def test_malformed_trees_are_rejected():
     bad = [
         S.Tree([0, -1, -1], [1.0, 0, 0], [1, -1, -1], [7, -1, -1], [-1, 0, 1]),     # child out of range
         S.Tree([0, 0], [1e30, 1e30], [1, 0], [1, 0], [0, 0]),                       # cycle
-        S.Tree([12, -1, -1], [1.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),    # feature index too large
-        S.Tree([-1], [0.0], [-1], [-1], [5]),                                       # class out of range
+        S.Tree([13, -1, -1], [1.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),    # feature index too large
+        S.Tree([-1], [0.0], [-1], [-1], [6]),                                       # class out of range
         S.Tree([0, -1, -1], [float("nan"), 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),
     ]
     for t in bad:

@@ -117,6 +117,9 @@ def test_auto_status_codes():
     with pytest.raises(S.SeerError) as ei:
         S.seer_spmv_auto(dA, S.Tree.constant(2), xd, y, torch.empty(64, dtype=torch.uint8, device="cuda:0"))
     assert ei.value.status == -4
+    with pytest.raises(S.SeerError) as ei:     # a kernel that needs preprocessing cannot be a leaf here
+        S.seer_spmv_auto(dA, S.Tree.constant(S.CSR_A), xd, y, ws)
+    assert ei.value.status == -3
     fresh = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
     with pytest.raises(S.SeerError):
         S.seer_spmv_auto_result(fresh)        # nothing has selected into this workspace

@@ -12,7 +12,7 @@ from gpu_util import announce, assert_features_equal, assert_parity, oracle_of, 
 pytestmark = pytest.mark.gpu
 
 
-def check_all(A, kernels=(0, 1, 2, 3, 4)):
+def check_all(A, kernels=(0, 1, 2, 3, 4, 5)):
     import torch
     x = G.dense_vector(A.cols, 4242)
     y_ref, bound = oracle_of(A, x)

@@ -10,7 +10,7 @@ from workloads import csr_gen as G
 from gpu_util import (announce, assert_features_equal, assert_parity, oracle_of, run_spmv, upload)
 
 pytestmark = pytest.mark.gpu
-KERNELS = [0, 1, 2, 3, 4]
+KERNELS = [0, 1, 2, 3, 4, 5]
 
 
 def edge_cases():
@@ -27,6 +27,8 @@ def edge_cases():
     c.append(G.explicit_lengths([14] * (256 * 5 + 3), 500, 11, "len14: 15 merge items per row"))
     c.append(G.explicit_lengths([1791] + [0] + [1792] * 3 + [5, 0, 0, 3839, 3840, 1], 4000, 12, "tile-sized rows"))
     c.append(G.explicit_lengths([2048, 2047, 2049, 1, 4096, 0, 33, 32, 31], 5000, 13, "chunk-sized rows"))
+    c.append(G.explicit_lengths([0, 0, 0, 4097, 0, 2048, 2048, 1, 0, 6143, 2, 2046, 0, 0], 3000, 14, "blocks inside rows"))
+    c.append(G.explicit_lengths([2048] * 7 + [1024] * 6 + [4096] * 3 + [0] * 1500, 2500, 15, "rows on block boundaries"))
     return c
 
 

@@ -47,12 +47,13 @@ def test_fit_recovers_planted_rule(tmp_path):
         for m in range(300):
             f = np.exp(rng.normal(2, 2, S.NUM_FEATURES)).astype(np.float32)
             fast = 2 if f[6] <= 40 else 3
-            t = [100.0, 90.0, 80.0, 70.0, 75.0]
+            t = [100.0, 90.0, 80.0, 70.0, 75.0, 8.0]   # kernel 5 is a little faster per product ...
             t[fast] = 10.0
             row = {"m": m, "family": "x", "rows": int(f[0]) + 1, "cols": 1, "nnz": 1, "t_features_us": 5.0,
                    "max_disagreement": 0.0}
             row.update({f"f_{n}": repr(float(v)) for n, v in zip(S.FEATURE_NAMES, f)})
             row.update({f"t_k{k}_us": t[k] for k in range(S.NUM_KERNELS)})
+            row["t_prep_k5_us"], row["t_single_k5_us"] = 30.0, 38.0   # ... but needs 30 us of preprocessing
             row["t_auto_mp_us"] = t[3] + 4.0          # gathering on the device costs 4 us
             w.writerow(row)
     out = tmp_path / "model.json"
@@ -73,6 +74,22 @@ def test_fit_recovers_planted_rule(tmp_path):
         f.f[6] = v
         assert S.seer_select(f, m.gathered) == want
     assert all(f in (-1, 0, 1, 2, 3, 8) for f in model["known"]["feature"] + model["selector"]["feature"])
+    assert max(model["gathered"]["klass"]) < S.NUM_DIRECT_KERNELS     # single products: no preprocessing
+    # several products with one matrix: 30 + 8 n < 10 n from n = 16 on, so the preprocessing
+    # kernel is the label for the grid's n >= 19 and never below
+    it = model["iterative"]
+    for n, r in it["report"]["test"].items():
+        assert r["amortisation_accuracy"] == 1.0, n
+        assert r["preprocessing_best_fraction"] == (1.0 if int(n) >= 16 else 0.0)
+        assert r["accuracy"]["gathered"] == 1.0
+    assert it["report"]["test"]["100"]["accuracy"]["known"] == 1.0     # the iteration count is known
+    assert all(f in (-1, 0, 1, 2, 3, 8, 12) for f in it["known"]["feature"] + it["selector"]["feature"])
+    mi, _ = T.load_model(str(out), iterative=True)
+    f = B.seer_features_t()
+    f.f[6], f.f[12] = 10.0, 3.0
+    assert S.seer_select(f, mi.gathered) == 2
+    f.f[12] = 50.0
+    assert S.seer_select(f, mi.gathered) == 5 and S.seer_select(f, mi.known) == 5
 
 
 def test_exported_header_is_equivalent_to_the_node_arrays(tmp_path):
