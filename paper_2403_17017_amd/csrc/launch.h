@@ -85,8 +85,10 @@ struct AutoShape {                          // launch shapes, all from rows and 
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
 constexpr size_t kAutoCarryOffset = 32768 + 256;
 size_t auto_workspace_bytes(int rows, int nnz);
-void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, void *workspace,
-                 hipStream_t st);
+constexpr int kAutoFusedRows = 8192;        // up to here every workgroup gathers and selects for itself
+constexpr int kAutoFusedGrid = 512;         // ... if the product's grid has at most this many workgroups
+void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, int fused_rows,
+                 int fused_grid, void *workspace, hipStream_t st);
 
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);
 void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st);

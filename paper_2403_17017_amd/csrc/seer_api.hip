@@ -22,6 +22,8 @@ std::atomic<int> g_tune_wm_lanes{-1};
 std::atomic<int> g_tune_bm_rows{-1};
 std::atomic<int> g_tune_bm_chunk{-1};
 std::atomic<int> g_tune_mp_ipt{-1};
+std::atomic<int> g_tune_fused_rows{-1};
+std::atomic<int> g_tune_fused_grid{-1};
 std::atomic<int> g_tune_remap{-1};
 std::atomic<int> g_tune_nt{-1};
 std::atomic<int> g_tune_vec{-1};
@@ -98,6 +100,12 @@ int mp_ipt(int rows, int nnz)
     // measured crossover: below ~6 M merge items the smaller tile (more workgroups) wins
     const uint64_t total = (uint64_t)rows + (uint64_t)nnz;
     return total < 6000000u ? kMpIptSmall : kMpIptLarge;
+}
+
+int auto_fused_rows()
+{
+    const int t = g_tune_fused_rows.load();
+    return t < 0 ? kAutoFusedRows : t;
 }
 
 int use_remap()
@@ -242,6 +250,8 @@ int seer_set_tuning(const char *name, int value)
     else if (!std::strcmp(name, "bm_rows")) g_tune_bm_rows.store(value);
     else if (!std::strcmp(name, "bm_chunk")) g_tune_bm_chunk.store(value);
     else if (!std::strcmp(name, "mp_ipt")) g_tune_mp_ipt.store(value);
+    else if (!std::strcmp(name, "auto_fused_rows")) g_tune_fused_rows.store(value);
+    else if (!std::strcmp(name, "auto_fused_grid")) g_tune_fused_grid.store(value);
     else if (!std::strcmp(name, "xcd_remap")) g_tune_remap.store(value);
     else if (!std::strcmp(name, "nt")) g_tune_nt.store(value);
     else if (!std::strcmp(name, "vec")) g_tune_vec.store(value);
@@ -407,7 +417,9 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     sh.tiles[SEER_CSR_WO] = wo_num_tiles(A->rows, A->nnz);
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), 1};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
-    launch_auto(a, dt, sh, vec, workspace, static_cast<hipStream_t>(stream));
+    const int fg = g_tune_fused_grid.load();
+    launch_auto(a, dt, sh, vec, auto_fused_rows(), fg < 0 ? kAutoFusedGrid : fg, workspace,
+                static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);
 }

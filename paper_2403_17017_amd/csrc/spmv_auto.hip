@@ -68,6 +68,38 @@ __device__ __forceinline__ void derive_features_device(
     }
 }
 
+// One lane's work once the workgroup holds the matrix's statistics in *s: derive the
+// feature vector (into LDS, so that the tree can index it without forcing it into
+// private scratch memory), walk the tree where it lies in the kernel arguments, and, if
+// `sel` is given, leave the record that seer_spmv_auto_result reads.  Returns the kernel
+// id.  (Sharing the derivation between the waves and staging the tree in LDS first was
+// measured: it is slower by more than a microsecond, the bulk read of the 3 KB argument
+// block costs more than the few nodes a walk touches.)
+__device__ __forceinline__ int select_on_device(
+    int rows, int cols, const int *__restrict__ rp, const FeatLds *s, float *s_f, const AutoTree &tree,
+    AutoSel *__restrict__ sel)
+{
+    const int64_t nnz = (int64_t)rp[rows] - (int64_t)rp[0];
+    derive_features_device(rows, cols, nnz, s->mx, s->mn, (int64_t)s->em, s->sq, s_f);
+    int n = 0, k = SEER_CSR_MP;            // a malformed tree cannot get here (host checks); MP is the safe answer
+    for (int steps = 0; steps <= tree.n_nodes; ++steps) {
+        const int feature = tree.nodes[n].feature;
+        if (feature < 0) { k = tree.nodes[n].klass; break; }
+        n = ((double)s_f[feature] <= tree.nodes[n].threshold) ? tree.nodes[n].left : tree.nodes[n].right;
+    }
+    k = (k >= 0 && k < SEER_NUM_DIRECT_KERNELS) ? k : SEER_CSR_MP;
+    if (sel) {
+        sel->kernel_id = k;
+        sel->valid = 1;
+        sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
+        sel->max_len = s->mx; sel->min_len = s->mn;
+        sel->sum_sq = s->sq; sel->empty = s->em;
+#pragma unroll
+        for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
+    }
+    return k;
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
     int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
@@ -76,25 +108,7 @@ __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
     __shared__ FeatLds s;
     __shared__ float s_f[SEER_NUM_FEATURES];
     features_total<VEC>(rows, rp, part, n_part, &s);
-    if (threadIdx.x == 0) {
-        // the feature vector lives in LDS so that the tree can index it without
-        // forcing it into private (scratch) memory
-        const int64_t nnz = (int64_t)rp[rows] - (int64_t)rp[0];
-        derive_features_device(rows, cols, nnz, s.mx, s.mn, (int64_t)s.em, s.sq, s_f);
-        int n = 0, k = SEER_CSR_MP;            // a malformed tree cannot get here (host checks); MP is the safe answer
-        for (int steps = 0; steps <= tree.n_nodes; ++steps) {
-            const int feature = tree.nodes[n].feature;
-            if (feature < 0) { k = tree.nodes[n].klass; break; }
-            n = ((double)s_f[feature] <= tree.nodes[n].threshold) ? tree.nodes[n].left : tree.nodes[n].right;
-        }
-        sel->kernel_id = (k >= 0 && k < SEER_NUM_DIRECT_KERNELS) ? k : SEER_CSR_MP;
-        sel->valid = 1;
-        sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
-        sel->max_len = s.mx; sel->min_len = s.mn;
-        sel->sum_sq = s.sq; sel->empty = s.em;
-#pragma unroll
-        for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
-    }
+    if (threadIdx.x == 0) select_on_device(rows, cols, rp, &s, s_f, tree, sel);
 }
 
 static_assert(kFeatMaxParts * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(AutoSel) <= kAutoCarryOffset - kAutoSelOffset,
@@ -104,16 +118,14 @@ constexpr int kAutoLds = mp_lds_words<kMpIptLarge>() > bm_lds_words<kBmChunk>() 
                                                                                  : bm_lds_words<kBmChunk>();
 static_assert(bm_lds_words<kWoChunk>() + 2 <= kAutoLds, "CSR,WO's products and its two bounds share the overlay");
 
+// This workgroup's share of schedule k (the same k in every workgroup of the grid).
 template <int IPT, bool VEC>
-__global__ __launch_bounds__(kWG) void spmv_auto_kernel(
-    int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
+__device__ __forceinline__ void auto_dispatch(
+    int k, int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
-    int *__restrict__ carry_row, float *__restrict__ carry_val, const AutoSel *__restrict__ sel,
-    const AutoShape shape, int remap)
+    int *__restrict__ carry_row, float *__restrict__ carry_val, const AutoShape &shape, int remap, int *smem)
 {
     static_assert(mp_lds_words<IPT>() <= kAutoLds, "LDS overlay too small");
-    __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
-    const int k = sel->kernel_id;                           // same for the whole grid
     const uint32_t n_tiles = shape.tiles[k];
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
@@ -140,6 +152,47 @@ __global__ __launch_bounds__(kWG) void spmv_auto_kernel(
     }
 }
 
+template <int IPT, bool VEC>
+__global__ __launch_bounds__(kWG) void spmv_auto_kernel(
+    int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
+    const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
+    int *__restrict__ carry_row, float *__restrict__ carry_val, const AutoSel *__restrict__ sel,
+    const AutoShape shape, int remap)
+{
+    __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
+    auto_dispatch<IPT, VEC>(sel->kernel_id, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
+}
+
+// Small matrices: gathering, selection and the product in ONE launch.  Every workgroup
+// reduces the whole row_ptr for itself (at most kAutoFusedRows offsets, out of L2 after
+// the first workgroup touched them), derives the same feature vector, walks the same
+// tree and then runs its share of the chosen schedule.  The redundant reduction costs
+// each workgroup one to two microseconds; a separate selection launch ahead of the
+// product costs the whole path several, which on a matrix this small is more than the
+// product.  (Measured on larger matrices, where the grid has thousands of workgroups,
+// the redundant work costs more than the launch it saves, also when a first pass leaves
+// partials to fold: there the selection stays a launch of its own.)
+// Workgroup 0 leaves the record for seer_spmv_auto_result and the fix-up kernel.
+template <int IPT, bool VEC, bool RPVEC>
+__global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
+    int rows, int cols, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
+    const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
+    int *__restrict__ carry_row, float *__restrict__ carry_val, AutoSel *__restrict__ sel,
+    const AutoTree tree, const AutoShape shape, int remap)
+{
+    __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
+    __shared__ FeatLds s;
+    __shared__ float s_f[SEER_NUM_FEATURES];
+    __shared__ int s_k;
+    int32_t mx, mn;
+    uint64_t sq, em;
+    features_accumulate_strided<RPVEC>(rows, rp, threadIdx.x, kWG, mx, mn, sq, em);
+    features_block_fold(mx, mn, sq, em, &s);
+    if (threadIdx.x == 0) s_k = select_on_device(rows, cols, rp, &s, s_f, tree, blockIdx.x == 0 ? sel : nullptr);
+    __syncthreads();
+    auto_dispatch<IPT, VEC>(s_k, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
+}
+
 __global__ __launch_bounds__(kWG) void spmv_auto_fixup_kernel(
     int rows, uint32_t n_mp, uint32_t n_wo, const int *__restrict__ carry_row,
     const float *__restrict__ carry_val, float *__restrict__ y, const AutoSel *__restrict__ sel)
@@ -156,8 +209,8 @@ size_t auto_workspace_bytes(int rows, int nnz)
     return kAutoCarryOffset + (mp > wo ? mp : wo);
 }
 
-void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, void *workspace,
-                 hipStream_t st)
+void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, int fused_rows,
+                 int fused_grid, void *workspace, hipStream_t st)
 {
     char *ws = static_cast<char *>(workspace);
     FeatPartial *part = reinterpret_cast<FeatPartial *>(ws);
@@ -168,8 +221,31 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
     int *carry_row = reinterpret_cast<int *>(ws + kAutoCarryOffset);
     float *carry_val = reinterpret_cast<float *>(ws + kAutoCarryOffset + one);
 
+    uint32_t grid = 0;
+    for (int k = 0; k < SEER_NUM_DIRECT_KERNELS; ++k) {
+        const uint32_t g = a.remap ? tiles_per_xcd(shape.tiles[k]) * kXCD : shape.tiles[k];
+        grid = g > grid ? g : grid;
+    }
+    const bool rp_vec = (reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0;
+    if (a.rows <= fused_rows && grid <= (uint32_t)fused_grid) {
+#define SEER_FUSED_LAUNCH(I, V, R)                                                                          \
+    hipLaunchKernelGGL((spmv_auto_fused_kernel<I, V, R>), dim3(grid), dim3(kWG), 0, st, a.rows, a.cols, a.nnz, \
+                       a.rp, a.ci, a.va, a.x, a.y, carry_row, carry_val, sel, tree, shape, a.remap)
+        if (shape.mp_ipt == kMpIptSmall) {
+            if (vec) { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptSmall, true, true); else SEER_FUSED_LAUNCH(kMpIptSmall, true, false); }
+            else     { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptSmall, false, true); else SEER_FUSED_LAUNCH(kMpIptSmall, false, false); }
+        } else {
+            if (vec) { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptLarge, true, true); else SEER_FUSED_LAUNCH(kMpIptLarge, true, false); }
+            else     { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptLarge, false, true); else SEER_FUSED_LAUNCH(kMpIptLarge, false, false); }
+        }
+#undef SEER_FUSED_LAUNCH
+        hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_carry + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
+                           n_wo, carry_row, carry_val, a.y, sel);
+        return;
+    }
+
     const uint32_t n_part = features_num_parts(a.rows);
-    if ((reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0) {
+    if (rp_vec) {
         if (n_part)
             hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
         hipLaunchKernelGGL(features_select_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
@@ -181,11 +257,6 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
                            n_part, sel, tree);
     }
 
-    uint32_t grid = 0;
-    for (int k = 0; k < SEER_NUM_DIRECT_KERNELS; ++k) {
-        const uint32_t g = a.remap ? tiles_per_xcd(shape.tiles[k]) * kXCD : shape.tiles[k];
-        grid = g > grid ? g : grid;
-    }
 #define SEER_AUTO_LAUNCH(I, V)                                                                             \
     hipLaunchKernelGGL((spmv_auto_kernel<I, V>), dim3(grid), dim3(kWG), 0, st, a.rows, a.nnz, a.rp, a.ci, \
                        a.va, a.x, a.y, carry_row, carry_val, sel, shape, a.remap)
