@@ -86,7 +86,8 @@ constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials o
 constexpr size_t kAutoCarryOffset = 32768 + 256;
 size_t auto_workspace_bytes(int rows, int nnz);
 constexpr int kAutoFusedRows = 8192;        // up to here every workgroup gathers and selects for itself
-constexpr int kAutoFusedGrid = 512;         // ... if the product's grid has at most this many workgroups
+constexpr int kAutoFusedGrid = 1024;        // the product's launch selects for itself up to this many workgroups
+constexpr uint32_t kAutoFusedParts = 64;    // partials the first pass leaves for it (each workgroup reads them all)
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, int fused_rows,
                  int fused_grid, void *workspace, hipStream_t st);
 

@@ -163,22 +163,23 @@ __global__ __launch_bounds__(kWG) void spmv_auto_kernel(
     auto_dispatch<IPT, VEC>(sel->kernel_id, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
 }
 
-// Small matrices: gathering, selection and the product in ONE launch.  Every workgroup
-// reduces the whole row_ptr for itself (at most kAutoFusedRows offsets, out of L2 after
-// the first workgroup touched them), derives the same feature vector, walks the same
-// tree and then runs its share of the chosen schedule.  The redundant reduction costs
-// each workgroup one to two microseconds; a separate selection launch ahead of the
-// product costs the whole path several, which on a matrix this small is more than the
-// product.  (Measured on larger matrices, where the grid has thousands of workgroups,
-// the redundant work costs more than the launch it saves, also when a first pass leaves
-// partials to fold: there the selection stays a launch of its own.)
+// Selection inside the product's launch, for grids of a few hundred workgroups.  Every
+// workgroup finishes the feature reduction for itself -- for a small matrix it reduces
+// the whole row_ptr (n_part == 0; at most kAutoFusedRows offsets, out of L2 after the
+// first workgroup touched them), for a larger one it folds the few partials a first
+// pass left -- derives the same feature vector, walks the same tree and then runs its
+// share of the chosen schedule.  The redundant work costs each workgroup two to three
+// microseconds; a separate selection launch costs the whole path four to five.
+// (With thousands of workgroups the redundant work adds up to more than the launch it
+// saves -- measured on a 1M-row matrix: 37 us per step against 27.6 -- so larger grids
+// keep the selection as a launch of its own.)
 // Workgroup 0 leaves the record for seer_spmv_auto_result and the fix-up kernel.
 template <int IPT, bool VEC, bool RPVEC>
 __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
     int rows, int cols, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
-    int *__restrict__ carry_row, float *__restrict__ carry_val, AutoSel *__restrict__ sel,
-    const AutoTree tree, const AutoShape shape, int remap)
+    int *__restrict__ carry_row, float *__restrict__ carry_val, const FeatPartial *__restrict__ part,
+    uint32_t n_part, AutoSel *__restrict__ sel, const AutoTree tree, const AutoShape shape, int remap)
 {
     __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
     __shared__ FeatLds s;
@@ -186,7 +187,18 @@ __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
     __shared__ int s_k;
     int32_t mx, mn;
     uint64_t sq, em;
-    features_accumulate_strided<RPVEC>(rows, rp, threadIdx.x, kWG, mx, mn, sq, em);
+    if (n_part == 0) {
+        features_accumulate_strided<RPVEC>(rows, rp, threadIdx.x, kWG, mx, mn, sq, em);
+    } else {
+        mx = INT32_MIN; mn = INT32_MAX; sq = 0; em = 0;
+        for (uint32_t b = threadIdx.x; b < n_part; b += kWG) {
+            const FeatPartial p = part[b];
+            mx = max(mx, p.max_len);
+            mn = min(mn, p.min_len);
+            sq += p.sum_sq;
+            em += p.empty;
+        }
+    }
     features_block_fold(mx, mn, sq, em, &s);
     if (threadIdx.x == 0) s_k = select_on_device(rows, cols, rp, &s, s_f, tree, blockIdx.x == 0 ? sel : nullptr);
     __syncthreads();
@@ -227,10 +239,20 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
         grid = g > grid ? g : grid;
     }
     const bool rp_vec = (reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0;
-    if (a.rows <= fused_rows && grid <= (uint32_t)fused_grid) {
+    if (grid <= (uint32_t)fused_grid) {
+        // one launch for a small matrix; else a first pass that leaves a few partials
+        uint32_t n_part = 0;
+        if (a.rows > fused_rows) {
+            n_part = features_num_parts(a.rows);
+            n_part = n_part > kAutoFusedParts ? kAutoFusedParts : (n_part ? n_part : 1u);
+            if (rp_vec)
+                hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+            else
+                hipLaunchKernelGGL(features_partial_kernel<false>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+        }
 #define SEER_FUSED_LAUNCH(I, V, R)                                                                          \
     hipLaunchKernelGGL((spmv_auto_fused_kernel<I, V, R>), dim3(grid), dim3(kWG), 0, st, a.rows, a.cols, a.nnz, \
-                       a.rp, a.ci, a.va, a.x, a.y, carry_row, carry_val, sel, tree, shape, a.remap)
+                       a.rp, a.ci, a.va, a.x, a.y, carry_row, carry_val, part, n_part, sel, tree, shape, a.remap)
         if (shape.mp_ipt == kMpIptSmall) {
             if (vec) { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptSmall, true, true); else SEER_FUSED_LAUNCH(kMpIptSmall, true, false); }
             else     { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptSmall, false, true); else SEER_FUSED_LAUNCH(kMpIptSmall, false, false); }

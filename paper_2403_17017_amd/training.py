@@ -188,15 +188,17 @@ def load_prep(rows):
 
 def gather_overhead_us(rows_csv, T):
     """Device-side cost of gathering + selecting per matrix, from the sweep: the excess
-    of the asynchronous path (constant merge-path tree) over the bare merge-path
-    kernel, smoothed by a least-squares line in the number of rows (single timings of
-    millisecond kernels are noisier than the few microseconds being estimated)."""
+    of the asynchronous path (constant merge-path tree) over the bare merge-path kernel.
+    Where the kernel is short the difference is taken as measured (the path has three
+    launch shapes, by size, and their costs differ); where it runs for hundreds of
+    microseconds single timings are noisier than the few microseconds being estimated,
+    and a least-squares line in the number of rows through the short ones stands in."""
     r = np.array([float(x["rows"]) for x in rows_csv])
     d = np.array([float(x["t_auto_mp_us"]) for x in rows_csv]) - T[:, S.CSR_MP]
     keep = T[:, S.CSR_MP] < 200.0            # short kernels give clean differences
     A = np.stack([np.ones(keep.sum()), r[keep]], axis=1)
     (a, b), *_ = np.linalg.lstsq(A, d[keep], rcond=None)
-    return np.maximum(a + b * r, 1.0), (float(a), float(b))
+    return np.maximum(np.where(keep, d, a + b * r), 1.0), (float(a), float(b))
 
 
 def tree_to_arrays(clf):
@@ -242,14 +244,65 @@ def selector_report(T, tf, pred, t_select_us=0.2):
     }
 
 
-def _fit(X, y, cols=None, weight=None):
+SLOWDOWN_CAP = 50.0     # a choice that is more than this many times slower than the best counts as this
+TIME_EXPONENT = 0.5     # a matrix counts by (its best time)^0.5: between "every matrix alike" and "by run time"
+
+
+def choice_costs(T):
+    """What choosing kernel k on matrix m costs, in the unit the trees are trained on: the
+    log of the slowdown against the best kernel for m (capped), and the importance of the
+    matrix.  The paper scores its models both by aggregate run time and per matrix
+    (Sec. IV-C, IV-D); the exponent sits between the two."""
+    tmin = T.min(axis=1)
+    return np.minimum(np.log(T / tmin[:, None]), np.log(SLOWDOWN_CAP)), tmin ** TIME_EXPONENT
+
+
+def _cart(Xs, cost, importance):
+    """CART on a cost matrix instead of hard labels: sample m is entered once per class k
+    with weight importance[m] * (worst cost of m - cost[m, k]), so that the class a leaf
+    votes for is the one with the least total cost over the leaf's matrices (the standard
+    reduction of cost-sensitive classification to weighted classification).  With 0/1
+    costs this is the plain fastest-kernel label."""
     from sklearn.tree import DecisionTreeClassifier
+    n, K = cost.shape
+    w = ((cost.max(axis=1, keepdims=True) - cost) * importance[:, None]).reshape(-1)
+    Xe, ye = np.repeat(Xs, K, axis=0), np.tile(np.arange(K), n)
+    keep = w > 0
+    if not np.any(keep):                      # every choice costs the same everywhere
+        keep, w = ye == 0, np.ones_like(w)
+    return DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0).fit(
+        Xe[keep], ye[keep], sample_weight=w[keep])
+
+
+def _fit(X, cost, importance, cols=None):
     Xs = X if cols is None else X[:, cols]
-    clf = DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0).fit(Xs, y, sample_weight=weight)
+    clf = _cart(Xs, cost, importance)
     tree = tree_to_arrays(clf)
     if cols is not None:   # the stored tree indexes the full feature vector
         tree["feature"] = [cols[f] if f >= 0 else -1 for f in tree["feature"]]
     assert np.array_equal(predict_with_arrays(tree, X), clf.predict(Xs))
+    return tree
+
+
+def _out_of_fold(Xs, cost, importance, groups=None, folds=5):
+    """Predictions for every sample by a tree that was fitted without it (and without
+    any sample of the same group)."""
+    from sklearn.model_selection import GroupKFold, KFold
+    out = np.zeros(len(Xs), dtype=int)
+    split = (GroupKFold(n_splits=folds).split(Xs, groups=groups) if groups is not None
+             else KFold(folds, shuffle=True, random_state=0).split(Xs))
+    for a, b in split:
+        out[b] = _cart(Xs[a], cost[a], importance[a]).predict(Xs[b])
+    return out
+
+
+def _fit_selector(Xk, cols, t_known, t_gather):
+    """The classifier-selection tree: class 0 = the known model is good enough, 1 = gather;
+    costs are the log slowdowns of either way against the better of the two."""
+    best = np.minimum(t_known, t_gather)
+    cost = np.stack([np.log(t_known / best), np.log(t_gather / best)], axis=1)
+    tree = _fit(Xk, cost, best ** TIME_EXPONENT, cols)
+    tree["klass"] = [int(k) if k >= 0 else -1 for k in tree["klass"]]
     return tree
 
 
@@ -295,34 +348,25 @@ def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
     ovh, ovh_fit = gather_overhead_us(rows, T)
     Xk = np.zeros_like(X)
     Xk[:, KNOWN_IDX] = X[:, KNOWN_IDX]          # what the known-features vector looks like at run time
-    gathered = _fit(X[tr], y[tr])
-    # The known model sees too little to tell a skewed matrix from a regular one; there a
-    # wrong guess costs orders of magnitude, so each training matrix counts by the mean
-    # time lost over the wrong choices (the paper scores models by runtime lost, Sec. IV-C).
-    regret = T.mean(axis=1) - T.min(axis=1) + 1e-3
-    known = _fit(Xk[tr], y[tr], KNOWN_IDX, weight=regret[tr])
+    cost, imp = choice_costs(T)
+    gathered = _fit(X[tr], cost[tr], imp[tr])
+    # The known model sees too little to tell a skewed matrix from a regular one; trained
+    # on costs it learns the kernel that is safe where it cannot tell.
+    known = _fit(Xk[tr], cost[tr], imp[tr], KNOWN_IDX)
     pk, pg = predict_with_arrays(known, Xk), predict_with_arrays(gathered, X)
     # Classifier selection: gather exactly where it pays.  The two models are judged on
     # training matrices they were not fitted on (5-fold out-of-fold predictions);
     # judged on their own training data they look better than they are and the selector
     # would learn never to gather.
-    from sklearn.model_selection import cross_val_predict
-    from sklearn.tree import DecisionTreeClassifier
-    mk = lambda: DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0)
-    oof_k = cross_val_predict(mk(), Xk[tr][:, KNOWN_IDX], y[tr], cv=5, params={"sample_weight": regret[tr]})
-    oof_g = cross_val_predict(mk(), X[tr], y[tr], cv=5)
-    want_gather = np.zeros(len(rows), dtype=int)
-    t_if_gather, t_if_known = T[tr, oof_g] + ovh[tr], T[tr, oof_k]
-    want_gather[tr] = (t_if_gather < t_if_known).astype(int)
-    # each training matrix counts by the time that is at stake on it: a wrong "do not
-    # gather" on a skewed matrix costs milliseconds, a wrong "gather" a few microseconds
-    selector = _fit(Xk[tr], want_gather[tr], KNOWN_IDX, weight=np.abs(t_if_gather - t_if_known) + 1e-3)
-    if len(set(want_gather[tr])) == 1:          # a one-class fit stores that class as index 0
-        selector["klass"] = [int(want_gather[tr][0]) if k >= 0 else -1 for k in selector["klass"]]
+    oof_k = _out_of_fold(Xk[tr][:, KNOWN_IDX], cost[tr], imp[tr])
+    oof_g = _out_of_fold(X[tr], cost[tr], imp[tr])
+    it = np.arange(len(tr))
+    selector = _fit_selector(Xk[tr], KNOWN_IDX, T[tr][it, oof_k], T[tr][it, oof_g] + ovh[tr])
     ug = predict_with_arrays(selector, Xk)
     model = {
         "gathered": gathered, "known": known, "selector": selector,
-        "note": f"CART gini max_depth={MAX_DEPTH}, {len(tr)} training matrices",
+        "note": f"CART gini max_depth={MAX_DEPTH} on log-slowdown costs (cap {SLOWDOWN_CAP:g}, importance "
+                f"t_best^{TIME_EXPONENT:g}), {len(tr)} training matrices",
         "feature_names": list(S.FEATURE_NAMES), "known_features": KNOWN_IDX,
         "gather_overhead_us": {"intercept": ovh_fit[0], "per_row": ovh_fit[1]},
         "label_counts": np.bincount(y, minlength=ND).tolist(),
@@ -357,6 +401,7 @@ def iterative_report(C, tf, pred_known, pred_gath, use_gath):
                      "classifier_selection": float(np.mean(chosen == truth))},
         # did the model call the amortisation right: preprocessing chosen iff it pays
         "amortisation_accuracy": float(np.mean(prep == np.isin(truth, PREP_KERNELS))),
+        "amortisation_accuracy_gathered": float(np.mean(np.isin(pred_gath, PREP_KERNELS) == np.isin(truth, PREP_KERNELS))),
         "preprocessing_chosen_fraction": float(np.mean(prep)),
         "preprocessing_best_fraction": float(np.mean(np.isin(truth, PREP_KERNELS))),
         "gathered_fraction": float(np.mean(use_gath)),
@@ -388,21 +433,13 @@ def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
     ytr = Ctr.argmin(axis=1)
     Xk = np.zeros_like(Xtr)
     Xk[:, KNOWN_ITER_IDX] = Xtr[:, KNOWN_ITER_IDX]
-    regret = Ctr.mean(axis=1) - Ctr.min(axis=1) + 1e-3
-    # every (matrix, n) sample counts by the time at stake on it, for both models: with
-    # n in the label a wrong choice at n = 100 costs a hundred times the one at n = 1
-    gathered = _fit(Xtr, ytr, weight=regret)
-    known = _fit(Xk, ytr, KNOWN_ITER_IDX, weight=regret)
-    mk = lambda: DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0)
-    cv = GroupKFold(n_splits=5)
-    oof_k = cross_val_predict(mk(), Xk[:, KNOWN_ITER_IDX], ytr, cv=cv, groups=gtr, params={"sample_weight": regret})
-    oof_g = cross_val_predict(mk(), Xtr, ytr, cv=cv, groups=gtr, params={"sample_weight": regret})
+    cost, imp = choice_costs(Ctr)
+    gathered = _fit(Xtr, cost, imp)
+    known = _fit(Xk, cost, imp, KNOWN_ITER_IDX)
+    oof_k = _out_of_fold(Xk[:, KNOWN_ITER_IDX], cost, imp, groups=gtr)
+    oof_g = _out_of_fold(Xtr, cost, imp, groups=gtr)
     idx = np.arange(len(Ctr))
-    t_if_gather, t_if_known = Ctr[idx, oof_g] + tftr, Ctr[idx, oof_k]
-    want = (t_if_gather < t_if_known).astype(int)
-    selector = _fit(Xk, want, KNOWN_ITER_IDX, weight=np.abs(t_if_gather - t_if_known) + 1e-3)
-    if len(set(want)) == 1:
-        selector["klass"] = [int(want[0]) if k >= 0 else -1 for k in selector["klass"]]
+    selector = _fit_selector(Xk, KNOWN_ITER_IDX, Ctr[idx, oof_k], Ctr[idx, oof_g] + tftr)
 
     def report(sel):
         out = {}
@@ -490,6 +527,80 @@ def summarize_evaluation(eval_csv):
     }
 
 
+def write_report_md(csv_path, model_json, eval_csv, out_md):
+    """Human-readable summary of a sweep, the fit and the held-out evaluation."""
+    rows, X, T, tf = load_csv(csv_path)
+    P = load_prep(rows)
+    with open(model_json) as fh:
+        m = json.load(fh)
+    names = [S.kernel_name(k) for k in range(S.NUM_KERNELS)]
+    L = ["# Selector: sweep, training and held-out evaluation (MI355X)", "",
+         "Commands (GPU box, repository root):", "",
+         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 1000 --out gpurun_out/sweep.csv",
+         "    python -m paper_2403_17017_amd.training fit --csv gpurun_out/sweep.csv --out gpurun_out/selector_model.json",
+         "    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv "
+         "--model gpurun_out/selector_model.json --out gpurun_out/eval.csv",
+         "    python -m paper_2403_17017_amd.training report-md --csv gpurun_out/sweep.csv "
+         "--model gpurun_out/selector_model.json --eval gpurun_out/eval.csv --out profiles/selector_evaluation.md", "",
+         f"Population: {len(rows)} seeded synthetic matrices (workloads/sweep_gen.py), timing 10 warm-up + 10 timed "
+         "runs per kernel, HIP-graph replay, same buffers (warm).  CSR,A is timed with a prepared plan; its "
+         "preprocessing call is timed apart (host wall clock, it waits for the device).", "",
+         f"## Sweep (all {len(rows)} matrices), sum of kernel times in us", "",
+         "| family | matrices | " + " | ".join(names) + " | best per matrix (direct kernels) | fastest direct kernel counts |",
+         "|---|---|" + "---|" * (len(names) + 2)]
+    fam = np.array([r["family"] for r in rows])
+    for f in list(dict.fromkeys(fam)) + ["all"]:
+        sel = np.ones(len(rows), bool) if f == "all" else fam == f
+        counts = np.bincount(T[sel][:, :ND].argmin(axis=1), minlength=ND)
+        L.append(f"| {f} | {int(sel.sum())} | " + " | ".join(f"{v:.0f}" for v in T[sel].sum(axis=0)) +
+                 f" | {T[sel][:, :ND].min(axis=1).sum():.0f} | " + "/".join(str(int(c)) for c in counts) + " |")
+    L += ["", f"Preprocessing call of CSR,A: median {np.median(P[:, S.CSR_A]):.1f} us, "
+          f"90th percentile {np.percentile(P[:, S.CSR_A], 90):.1f} us.  Feature collection call (seer_features, "
+          f"with its wait): median {np.median(tf):.1f} us.", "",
+          "## Single-product models (" + m["note"] + "), held-out matrices, predicted from sweep timings", ""]
+    t = m["report"]["test"]
+    L.append(f"accuracy (fastest kernel exactly): known {t['accuracy']['known']:.3f}, gathered "
+             f"{t['accuracy']['gathered']:.3f}, classifier selection {t['accuracy']['classifier_selection']:.3f}; "
+             f"gathered on {100 * t['gathered_fraction']:.0f} % of matrices; aggregate speed-up over the best fixed "
+             f"kernel ({names[t['best_fixed_kernel']]}) {t['aggregate_speedup_vs_best_fixed']['classifier_selection']:.3f}, "
+             f"per-matrix geomean {t['per_matrix_geomean_vs_best_fixed']['classifier_selection']:.3f}")
+    if eval_csv and os.path.exists(eval_csv):
+        e = summarize_evaluation(eval_csv)
+        best = names[e["best_fixed_kernel"]]
+        L += ["", f"## Held-out evaluation, every path re-measured end to end on the GPU timeline ({e['matrices']} matrices)", "",
+              f"| path | total us | vs best fixed kernel ({best}) | per-matrix geomean vs {best} | vs oracle (best kernel per matrix) |",
+              "|---|---|---|---|---|"]
+        tb = e["t_fixed_us"][e["best_fixed_kernel"]]
+        for k in range(ND):
+            L.append(f"| fixed {names[k]} | {e['t_fixed_us'][k]:.0f} | {tb / e['t_fixed_us'][k]:.3f} | | "
+                     f"{e['t_fixed_us'][k] / e['t_oracle_us']:.3f} |")
+        for key, label in (("always_gather", "always gather (seer_spmv_auto)"),
+                           ("classifier_selection", "classifier selection (seer_spmv_model)")):
+            tot = e["t_always_gather_us"] if key == "always_gather" else e["t_classifier_selection_us"]
+            L.append(f"| {label} | {tot:.0f} | {e['aggregate_speedup_vs_best_fixed'][key]:.3f} | "
+                     f"{e['per_matrix_geomean_vs_best_fixed'][key]:.3f} | {e['time_lost_vs_oracle'][key]:.3f} |")
+        L.append(f"| oracle | {e['t_oracle_us']:.0f} | {tb / e['t_oracle_us']:.3f} | | 1.000 |")
+        L += ["", f"Geomean over the fixed kernels of (kernel total / classifier-selection total): "
+              f"{e['geomean_over_fixed_kernels_of_aggregate_speedup']:.2f}x.  Features gathered on "
+              f"{100 * e['gathered_fraction']:.0f} % of the held-out matrices."]
+    if "iterative" in m:
+        it = m["iterative"]["report"]["test"]
+        L += ["", "## Models for n products with one matrix (Sec. V), held-out matrices, from sweep timings", "",
+              "Cost of kernel k for n products: preprocessing(k) + n * run(k); the gathered path adds one "
+              "feature-collection call.", "",
+              "| n | best fixed kernel | classifier selection vs best fixed (aggregate) | per-matrix geomean | vs oracle | "
+              "gathered on | preprocessing kernel chosen / truly best | amortisation called right |",
+              "|---|---|---|---|---|---|---|---|"]
+        for n, r in it.items():
+            L.append(f"| {n} | {names[r['best_fixed_kernel']]} | {r['aggregate_speedup_vs_best_fixed']:.3f} | "
+                     f"{r['per_matrix_geomean_vs_best_fixed']:.3f} | {r['time_lost_vs_oracle']:.3f} | "
+                     f"{100 * r['gathered_fraction']:.0f} % | {100 * r['preprocessing_chosen_fraction']:.0f} % / "
+                     f"{100 * r['preprocessing_best_fraction']:.0f} % | {100 * r['amortisation_accuracy']:.0f} % |")
+    with open(out_md, "w") as fh:
+        fh.write("\n".join(L) + "\n")
+    return out_md
+
+
 def _emit_node(tree, n, depth, lines):
     pad = "    " * depth
     if tree["feature"][n] < 0:
@@ -574,7 +685,15 @@ def main(argv=None):
     d = sub.add_parser("export-header")
     d.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     d.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model_generated.h"))
+    e = sub.add_parser("report-md")
+    e.add_argument("--csv", required=True)
+    e.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
+    e.add_argument("--eval", default=None)
+    e.add_argument("--out", required=True)
     args = ap.parse_args(argv)
+    if args.cmd == "report-md":
+        print(write_report_md(args.csv, args.model, args.eval, args.out))
+        return
     if args.cmd == "export-header":
         print(export_header(args.model, args.out))
         return
