@@ -177,6 +177,11 @@ def stream_copy_ceiling(nbytes=1 << 31, reps=10):
     return 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def T_graph(enqueue):
+    from paper_2403_17017_amd.training import time_graph_us
+    return time_graph_us(enqueue, warmup=10, reps=20)
+
+
 def selector_eval(model, meta, count):
     """Selected-vs-best-single-kernel on held-out matrices of the sweep population,
     every path timed on the GPU timeline (HIP graph replay, warm buffers)."""
@@ -356,6 +361,31 @@ def main():
         extras["classifier_selection_on_this_matrix"] = {
             "path": "gathered" if path == 1 else "known",
             "kernel": S.kernel_name(S.seer_spmv_auto_result(ws)[1] if path == 1 else k_known)}
+        # several products with one matrix (warm: a solver keeps using the same buffers):
+        # selection with the iteration count + preprocessing of the chosen kernel + n products,
+        # wall clock, against n products with the best kernel that needs no preprocessing
+        if "iterative" in model_meta:
+            from paper_2403_17017_amd.training import load_model as _load
+            it_model, _ = _load(MODEL_PATH, iterative=True)
+            d, xd, y, ws = warm[0]
+            best_direct = min(extras["per_kernel_warm_us"][S.kernel_name(k)] for k in range(S.NUM_DIRECT_KERNELS))
+            extras["iterative"] = {}
+            for n_it in (1, 19, 100):
+                S.seer_spmv_plan(d, it_model, n_it)                 # warm the path once
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                plan, path = S.seer_spmv_plan(d, it_model, n_it)
+                pws = S.alloc_workspace(S.spmv_prepared_workspace_bytes(plan))
+                for _ in range(n_it):
+                    S.seer_spmv_prepared(plan, d, xd, y, pws)
+                torch.cuda.synchronize()
+                total = (time.perf_counter() - t0) * 1e6
+                g = T_graph(lambda: S.seer_spmv_prepared(plan, d, xd, y, pws))
+                extras["iterative"][str(n_it)] = {
+                    "kernel": S.kernel_name(plan.kernel_id), "path": "gathered" if path == 1 else "known",
+                    "wall_us_select_prepare_and_n_products": round(total, 1),
+                    "product_us_on_gpu_timeline": round(g, 2),
+                    "n_products_best_direct_kernel_us": round(n_it * best_direct, 1)}
         del warm
         extras["stream_copy_ceiling_gbps"] = round(stream_copy_ceiling(), 1)
         if model_meta.get("test_matrices") and args.selector_matrices > 0:
