@@ -23,6 +23,11 @@ What it defines
                    (Sec. III-B).  The number of SpMV iterations the caller is
                    about to run is one more known feature (Sec. V, multiple
                    iteration evaluation); it is 1 unless stated.
+  * ell_from_csr -- the preprocessing result of the ELL,TM kernel (Table II: thread
+                   mapped over "one row or fixed width" in the ELL format): every row
+                   padded to the longest row's length, stored column-major.  The
+                   layout (padding marker, row padding) is this build's; ell_spmv_python
+                   multiplies from it literally.
   * adaptive_plan -- the preprocessing result of the Adaptive-CSR schedule
                    (Sec. IV: rows are grouped by size ahead of the first
                    product): row blocks of about `chunk` nonzeros, long rows
@@ -255,4 +260,36 @@ def plan_spmv_python(rows, row_ptr, col_idx, values, x, row, start):
         for i in range(lo, hi):
             a, b = max(int(row_ptr[i]), s), min(int(row_ptr[i + 1]), e)
             y[i] += sum(values[j] * x[col_idx[j]] for j in range(a, b))
+    return y
+
+
+ELL_ROW_MULTIPLE = 64      # rows are padded to a multiple of this (one wave of lanes)
+
+
+def ell_from_csr(rows: int, row_ptr, col_idx, values):
+    """ELL form of a CSR matrix: width = the longest row; cols[j, i] / vals[j, i] hold the
+    j-th entry of row i in CSR order, cols = -1 and vals = 0 where row i has fewer than
+    j + 1 entries; the row dimension is padded to a multiple of ELL_ROW_MULTIPLE (padding
+    rows are all -1 / 0).  Returns (cols int32 [width, rows_pad], vals fp32 [width, rows_pad])."""
+    rp = np.asarray(row_ptr[: rows + 1], dtype=np.int64)
+    width = int((rp[1:] - rp[:-1]).max()) if rows > 0 else 0
+    rows_pad = -(-rows // ELL_ROW_MULTIPLE) * ELL_ROW_MULTIPLE
+    cols = np.full((width, rows_pad), -1, dtype=np.int32)
+    vals = np.zeros((width, rows_pad), dtype=np.float32)
+    for i in range(rows):
+        a, b = int(rp[i]), int(rp[i + 1])
+        cols[: b - a, i] = col_idx[a:b]
+        vals[: b - a, i] = values[a:b]
+    return cols, vals
+
+
+def ell_spmv_python(rows, cols, vals, x):
+    """y = A x from the ELL arrays, entry by entry, padding skipped (not multiplied: a
+    padded slot must not turn an infinite x into NaN)."""
+    y = [0] * rows
+    for i in range(rows):
+        for j in range(cols.shape[0]):
+            c = int(cols[j, i])
+            if c >= 0:
+                y[i] += vals[j, i].item() * x[c]
     return y
