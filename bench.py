@@ -334,12 +334,35 @@ def main():
     if not args.no_extras:
         extras = {"per_kernel_cold_us": {}, "per_kernel_warm_us": {}}
         warm = Rotation(A, x, 1)
-        for k in range(S.NUM_KERNELS):
+        for k in S.ONE_CALL_KERNELS:
             c = time_spmv_graph(k, rot, max(n_sets, 20))
             w = time_spmv_graph(k, warm, max(n_sets, 20))
             extras["per_kernel_cold_us"][S.kernel_name(k)] = round(c, 2)
             extras["per_kernel_warm_us"][S.kernel_name(k)] = round(w, 2)
         best = min(extras["per_kernel_cold_us"].values())
+        # the kernels with preprocessing, from a prepared plan (one plan per rotating copy)
+        extras["prepared_cold_us"], extras["prepared_warm_us"], extras["prepare_call_us"] = {}, {}, {}
+        for k in (S.CSR_A, S.ELL_TM):
+            for R, key in ((rot, "prepared_cold_us"), (warm, "prepared_warm_us")):
+                plans = [S.seer_spmv_prepare(k, R[i][0]) for i in range(R.n)]
+                reps = max(n_sets, 20)
+
+                def enqueue_all():
+                    for i in range(reps):
+                        d, xd, y, ws = R[i]
+                        S.seer_spmv_prepared(plans[i % R.n], d, xd, y, ws)
+                from paper_2403_17017_amd.training import time_graph_us
+                extras[key][S.kernel_name(k)] = round(time_graph_us(enqueue_all, warmup=1, reps=1) / reps, 2)
+                del plans
+            d = warm[0][0]
+            pm = S.alloc_workspace(max(S.plan_bytes(k, A.rows, A.nnz), S.features_workspace_bytes(A.rows),
+                                       S.ell_plan_bytes(A.rows, int(S.seer_features(d).max_len)) if k == S.ELL_TM else 0))
+            S.seer_spmv_prepare(k, d, pm)
+            t0 = time.perf_counter()
+            for _ in range(10):
+                S.seer_spmv_prepare(k, d, pm)
+            extras["prepare_call_us"][S.kernel_name(k)] = round((time.perf_counter() - t0) / 10 * 1e6, 1)
+            del pm
         extras["best_fixed_kernel_cold_gbps"] = round(mb / (best * 1e-6) / 1e9, 1)
         # the same step with the host in the loop: three calls, one wait
         for i in range(10):

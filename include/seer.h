@@ -56,7 +56,11 @@ enum {
                         preprocessing pass over row_ptr, long rows split between
                         blocks (Table II's Adaptive-CSR (A); Sec. IV on its
                         preprocessing and when it is amortised)                        */
-    SEER_NUM_KERNELS = 6
+    SEER_ELL_TM = 6, /* thread mapped over the ELL format: every row padded to the
+                        longest row's length, stored column-major, so that a wave's
+                        loads are contiguous (Table II, "TM ... CSR, ELL").  The
+                        conversion is its preprocessing; it has no one-call form.      */
+    SEER_NUM_KERNELS = 7
 };
 
 /* CSR matrix, fp32 values, int32 indices.  All pointers DEVICE, caller-owned.
@@ -151,7 +155,9 @@ int seer_select(const seer_features_t *f, const seer_tree *tree, int *kernel_id)
  * workspace: at least seer_spmv_workspace_bytes(kernel_id, rows, nnz) bytes (0 for
  * ids 0-2, then workspace may be NULL).
  * SEER_CSR_A in this single call runs its preprocessing pass first, every time (what
- * one product with it costs); seer_spmv_prepare / seer_spmv_prepared split the two. */
+ * one product with it costs); seer_spmv_prepare / seer_spmv_prepared split the two.
+ * SEER_ELL_TM has no one-call form (SEER_EKERNEL): the size of its plan is only known
+ * after a look at the matrix. */
 int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y,
               void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
@@ -213,13 +219,19 @@ typedef struct {
     int32_t n_blocks;     /* SEER_CSR_A: row blocks in the plan                         */
     int32_t split_rows;   /* SEER_CSR_A: 1 if some row is shared between blocks (the
                              product then needs the carry workspace and a second launch) */
-    int32_t reserved;
+    int32_t ell_width;    /* SEER_ELL_TM: slots per row = the longest row               */
     void *device;         /* DEVICE, inside plan_mem; NULL for kernels without a plan   */
     size_t device_bytes;
 } seer_plan;
 
-/* Device bytes seer_spmv_prepare needs for `kernel_id` (0 for ids that need none). */
+/* Device bytes seer_spmv_prepare needs for `kernel_id` (0 for ids that need none, and for
+ * SEER_ELL_TM, whose need depends on the longest row: see seer_ell_plan_bytes). */
 size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz);
+
+/* Device bytes of the ELL form of a matrix with `rows` rows whose longest row has max_len
+ * entries: 2 arrays of roundup(rows, 64) * max_len 4-byte words (each padded to 256 bytes).
+ * 0 if that is 2^31 words or more: the format is then not applicable. */
+size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
 
 /* Runs the preprocessing of `kernel_id` for A on `stream` and fills *plan.  For
  * SEER_CSR_A: one pass over A->row_ptr that writes, for block k = 0 .. n-1 of
@@ -228,9 +240,17 @@ size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz);
  *   after nonzero 2048 k, at that row's first nonzero, or at nonzero 2048 k if the row
  *   also began block k - 1 (such a block holds nothing but part of that row);
  *   entry n is {rows, nnz}.
+ * For SEER_ELL_TM: finds the longest row (the feature reduction, with plan_mem as its
+ * workspace, so plan_mem must hold at least seer_features_workspace_bytes(rows)), then
+ * writes cols[j * R + i] / vals[j * R + i] = the j-th entry of row i in CSR order, or
+ * -1 / 0 where the row is shorter, R = roundup(rows, 64), cols first, vals at half of
+ * seer_ell_plan_bytes(rows, longest row).  If plan_mem is too small the call returns
+ * SEER_EWORKSPACE with plan->device_bytes = the bytes needed; SEER_EINVAL if the format
+ * is not applicable.
  * HOST-SYNCHRONOUS: returns after the pass has finished (it reads back whether any row
- * is split).  plan_mem: DEVICE, 16-byte aligned, >= seer_plan_bytes(); may be NULL for
- * kernels that need no plan (the call then only records the id).  Not capturable. */
+ * is split, or the longest row).  plan_mem: DEVICE, 16-byte aligned, >= seer_plan_bytes();
+ * may be NULL for kernels that need no plan (the call then only records the id).  Not
+ * capturable. */
 int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes,
                       void *stream, seer_plan *plan);
 
@@ -248,7 +268,9 @@ size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan);
  * (preprocessing + iterations * run time) can tell when preprocessing is amortised; then
  * seer_spmv_prepare for the chosen kernel.  The features, when the selector asks for
  * them, are gathered with seer_features.  HOST-SYNCHRONOUS.  Any kernel id may be
- * chosen.  *path (may be NULL): 0 known model, 1 gathered model.
+ * chosen; if it is SEER_ELL_TM and plan_mem cannot hold the ELL arrays (or the format is
+ * not applicable) the call prepares SEER_CSR_A instead, the schedule that is safe on
+ * every matrix.  *path (may be NULL): 0 known model, 1 gathered model.
  * workspace: >= seer_features_workspace_bytes(rows); plan_mem: >= seer_plan_bytes(
  * SEER_CSR_A, rows, nnz) unless the model cannot answer SEER_CSR_A. */
 int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iterations,

@@ -17,9 +17,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libseer.so")
 
 NUM_FEATURES = 13
-NUM_KERNELS = 6
+NUM_KERNELS = 7
 NUM_DIRECT_KERNELS = 5          # ids below this need no preprocessing
-CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A = range(6)
+CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, ELL_TM = range(7)
+ONE_CALL_KERNELS = (CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A)   # what seer_spmv accepts
 FEATURE_NAMES = (
     "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
     "mean_density", "max_density", "min_density", "var_density", "iterations",
@@ -69,7 +70,7 @@ class seer_tree(C.Structure):
 
 class seer_plan(C.Structure):
     _fields_ = [("kernel_id", C.c_int32), ("rows", C.c_int32), ("nnz", C.c_int32), ("n_blocks", C.c_int32),
-                ("split_rows", C.c_int32), ("reserved", C.c_int32), ("device", C.c_void_p),
+                ("split_rows", C.c_int32), ("ell_width", C.c_int32), ("device", C.c_void_p),
                 ("device_bytes", C.c_size_t)]
 
 
@@ -114,6 +115,8 @@ def lib():
         L.seer_spmv_model.restype = C.c_int
         L.seer_plan_bytes.argtypes = [C.c_int, i32, i32]
         L.seer_plan_bytes.restype = sz
+        L.seer_ell_plan_bytes.argtypes = [i32, i32]
+        L.seer_ell_plan_bytes.restype = sz
         L.seer_spmv_prepare.argtypes = [C.c_int, C.POINTER(seer_csr), vp, sz, vp, C.POINTER(seer_plan)]
         L.seer_spmv_prepare.restype = C.c_int
         L.seer_spmv_prepared.argtypes = [C.POINTER(seer_plan), C.POINTER(seer_csr), vp, vp, vp, sz, vp]
@@ -353,7 +356,18 @@ class Plan:
 
     kernel_id = property(lambda self: int(self.c.kernel_id))
     n_blocks = property(lambda self: int(self.c.n_blocks))
+    ell_width = property(lambda self: int(self.c.ell_width))
     split_rows = property(lambda self: bool(self.c.split_rows))
+
+    def ell_arrays(self):
+        """(cols int32 [width, rows_pad], vals fp32 [width, rows_pad]) as host arrays."""
+        import torch
+        rows_pad = -(-int(self.c.rows) // 64) * 64
+        n = rows_pad * self.ell_width
+        half = int(self.c.device_bytes) // 2
+        cols = self.plan_mem[: n * 4].view(torch.int32).cpu().numpy().reshape(self.ell_width, rows_pad)
+        vals = self.plan_mem[half: half + n * 4].view(torch.float32).cpu().numpy().reshape(self.ell_width, rows_pad)
+        return cols, vals
 
     def entries(self) -> np.ndarray:
         """The (first row, first nonzero) pairs as an int32 [n_blocks + 1, 2] host array."""
@@ -366,9 +380,18 @@ def plan_bytes(kernel_id: int, rows: int, nnz: int) -> int:
     return int(lib().seer_plan_bytes(kernel_id, rows, nnz))
 
 
-def seer_spmv_prepare(kernel_id: int, A: DeviceCSR, plan_mem=None, stream=None) -> Plan:
-    """Runs the preprocessing of kernel_id for A (waits for it) and returns the plan."""
+def ell_plan_bytes(rows: int, max_len: int) -> int:
+    return int(lib().seer_ell_plan_bytes(rows, max_len))
+
+
+def seer_spmv_prepare(kernel_id: int, A: DeviceCSR, plan_mem=None, stream=None, max_len: int = None) -> Plan:
+    """Runs the preprocessing of kernel_id for A (waits for it) and returns the plan.
+    For ELL_TM the plan memory is sized from max_len (the longest row) when none is given."""
     need = plan_bytes(kernel_id, A.rows, A.nnz)
+    if kernel_id == ELL_TM and plan_mem is None:
+        if max_len is None:
+            max_len = int(seer_features(A, stream=stream).max_len)
+        need = max(ell_plan_bytes(A.rows, max_len), features_workspace_bytes(A.rows))
     if plan_mem is None and need:
         plan_mem = alloc_workspace(need, A.row_ptr.device)
     cs = A.c_struct()

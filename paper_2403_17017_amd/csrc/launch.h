@@ -46,6 +46,13 @@ int *adaptive_split_flag(void *plan_mem, int rows, int nnz);
 void launch_adaptive_plan(int rows, int nnz, const int *rp, void *plan_mem, bool want_flag, hipStream_t st);
 void launch_adaptive(const SpmvArgs &a, bool vec, const void *plan_mem, void *carry_ws, hipStream_t st);
 
+// ELL,TM: plan_mem holds the ELL columns, then the ELL values (ell_plan_bytes())
+uint32_t ell_rows_pad(int rows);
+size_t ell_plan_bytes(int rows, int width);
+void launch_ell_convert(int rows, int width, const int *rp, const int *ci, const float *va, void *plan_mem,
+                        hipStream_t st);
+void launch_ell(const SpmvArgs &a, int width, const void *plan_mem, hipStream_t st);
+
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory
     int32_t max_len, min_len;

@@ -218,7 +218,7 @@ bool tree_is_acyclic(const seer_tree *t)
     return true;
 }
 
-const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A"};
+const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM"};
 
 } // namespace
 
@@ -504,7 +504,7 @@ int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream)
 int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *workspace,
               size_t workspace_bytes, void *stream)
 {
-    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS) return SEER_EKERNEL;
+    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS || kernel_id == SEER_ELL_TM) return SEER_EKERNEL;
     const int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     if (A->rows == 0) return SEER_OK;
@@ -550,6 +550,34 @@ size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz)
     return adaptive_plan_bytes(rows, nnz);
 }
 
+size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len) { return ell_plan_bytes(rows, max_len); }
+
+// The ELL conversion.  max_len < 0: not known yet, find it with the feature reduction.
+static int prepare_ell(const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream, seer_plan *plan,
+                       int64_t max_len)
+{
+    if (!plan_mem || !aligned16(plan_mem)) return SEER_EWORKSPACE;
+    if (max_len < 0) {
+        seer_features_t f;
+        const int rc = seer_features(A, &f, plan_mem, plan_bytes, stream);
+        if (rc != SEER_OK) return rc;
+        max_len = f.max_len;
+    }
+    const size_t need = ell_plan_bytes(A->rows, (int)max_len);
+    if (need == 0) return SEER_EINVAL;                 // 2^31 words or more: not applicable
+    plan->device_bytes = need;
+    if (plan_bytes < need) return SEER_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    launch_ell_convert(A->rows, (int)max_len, A->row_ptr, A->col_idx, A->values, plan_mem, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    plan->ell_width = (int32_t)max_len;
+    plan->device = plan_mem;
+    return SEER_OK;
+}
+
 int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream,
                       seer_plan *plan)
 {
@@ -561,6 +589,7 @@ int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t p
     plan->kernel_id = kernel_id;
     plan->rows = A->rows;
     plan->nnz = A->nnz;
+    if (kernel_id == SEER_ELL_TM && A->rows > 0) return prepare_ell(A, plan_mem, plan_bytes, stream, plan, -1);
     if (kernel_id != SEER_CSR_A || A->rows == 0) return SEER_OK;   // nothing to prepare
     const size_t need = adaptive_plan_bytes(A->rows, A->nnz);
     if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
@@ -588,6 +617,7 @@ size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan)
     if (!plan) return 0;
     if (plan->kernel_id == SEER_CSR_A)
         return plan->split_rows ? carry_workspace_bytes((uint32_t)plan->n_blocks) : 0;
+    if (plan->kernel_id == SEER_ELL_TM) return 0;
     return seer_spmv_workspace_bytes(plan->kernel_id, plan->rows, plan->nnz);
 }
 
@@ -595,13 +625,19 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
                        size_t workspace_bytes, void *stream)
 {
     if (!plan) return SEER_EINVAL;
-    if (plan->kernel_id != SEER_CSR_A)
+    if (plan->kernel_id != SEER_CSR_A && plan->kernel_id != SEER_ELL_TM)
         return seer_spmv(plan->kernel_id, A, x, y, workspace, workspace_bytes, stream);
     const int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     if (A->rows != plan->rows || A->nnz != plan->nnz) return SEER_EINVAL;   // a plan belongs to one matrix
     if (A->rows == 0) return SEER_OK;
     if (!y || (!x && A->nnz > 0) || !plan->device) return SEER_EINVAL;
+    if (plan->kernel_id == SEER_ELL_TM) {
+        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt()};
+        launch_ell(a, plan->ell_width, plan->device, static_cast<hipStream_t>(stream));
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SEER_OK : hip_fail(e);
+    }
     void *carry = nullptr;
     if (plan->split_rows) {
         if (!workspace || !aligned16(workspace) ||
@@ -625,6 +661,7 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
     int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     int use_gathered = 1, kid = -1;
+    int64_t max_len = -1;
     if (model->selector) {
         seer_features_t kf;
         rc = seer_known_features(A->rows, A->cols, A->nnz, &kf);
@@ -643,11 +680,21 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
         rc = seer_features(A, &gf, workspace, workspace_bytes, stream);
         if (rc != SEER_OK) return rc;
         gf.f[SEER_F_ITERATIONS] = (float)iterations;
+        max_len = gf.max_len;
         rc = seer_select(&gf, model->gathered, &kid);
         if (rc != SEER_OK) return rc;
     }
     if (kid < 0 || kid >= SEER_NUM_KERNELS) return SEER_ETREE;
     if (path) *path = use_gathered;
+    if (kid == SEER_ELL_TM && A->rows > 0) {
+        std::memset(plan, 0, sizeof *plan);
+        plan->kernel_id = kid;
+        plan->rows = A->rows;
+        plan->nnz = A->nnz;
+        rc = prepare_ell(A, plan_mem, plan_bytes, stream, plan, max_len);
+        if (rc != SEER_EWORKSPACE && rc != SEER_EINVAL) return rc;
+        kid = SEER_CSR_A;            // the ELL arrays do not fit: take the schedule that is safe everywhere
+    }
     return seer_spmv_prepare(kid, A, plan_mem, plan_bytes, stream, plan);
 }
 

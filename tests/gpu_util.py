@@ -32,7 +32,10 @@ def run_spmv(kernel_id, dA, x_dev, rows, poison=True):
     import torch
     y = torch.full((max(rows, 1),), float("nan"), dtype=torch.float32, device="cuda:0") if poison \
         else torch.zeros(max(rows, 1), dtype=torch.float32, device="cuda:0")
-    S.seer_spmv(kernel_id, dA, x_dev, y)
+    if kernel_id in S.ONE_CALL_KERNELS:
+        S.seer_spmv(kernel_id, dA, x_dev, y)
+    else:                                      # preprocessing first (ELL,TM has no one-call form)
+        S.seer_spmv_prepared(S.seer_spmv_prepare(kernel_id, dA), dA, x_dev, y)
     torch.cuda.synchronize()
     return y[:rows].cpu().numpy()
 

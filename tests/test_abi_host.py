@@ -39,9 +39,9 @@ def test_struct_layouts_match_header():
 
 
 def test_names_and_errors():
-    assert S.lib().seer_num_kernels() == 6 == S.NUM_KERNELS
-    assert [S.kernel_name(k) for k in range(6)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A"]
-    assert S.lib().seer_kernel_name(6) is None
+    assert S.lib().seer_num_kernels() == 7 == S.NUM_KERNELS
+    assert [S.kernel_name(k) for k in range(7)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM"]
+    assert S.lib().seer_kernel_name(7) is None
     assert S.strerror(0) == "ok" and "tree" in S.strerror(-3)
     with pytest.raises(S.SeerError):
         S.set_tuning("no_such_knob", 1)
@@ -160,7 +160,7 @@ def test_malformed_trees_are_rejected():
         S.Tree([0, -1, -1], [1.0, 0, 0], [1, -1, -1], [7, -1, -1], [-1, 0, 1]),     # child out of range
         S.Tree([0, 0], [1e30, 1e30], [1, 0], [1, 0], [0, 0]),                       # cycle
         S.Tree([13, -1, -1], [1.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),    # feature index too large
-        S.Tree([-1], [0.0], [-1], [-1], [6]),                                       # class out of range
+        S.Tree([-1], [0.0], [-1], [-1], [7]),                                       # class out of range
         S.Tree([0, -1, -1], [float("nan"), 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),
     ]
     for t in bad:

@@ -12,7 +12,7 @@ from gpu_util import announce, assert_features_equal, assert_parity, oracle_of, 
 pytestmark = pytest.mark.gpu
 
 
-def check_all(A, kernels=(0, 1, 2, 3, 4, 5)):
+def check_all(A, kernels=(0, 1, 2, 3, 4, 5), prepared=(5, 6)):
     import torch
     x = G.dense_vector(A.cols, 4242)
     y_ref, bound = oracle_of(A, x)
@@ -24,6 +24,13 @@ def check_all(A, kernels=(0, 1, 2, 3, 4, 5)):
         announce(f"full size {A.name}: kernel {kid} rows={A.rows} nnz={A.nnz}")
         y = run_spmv(kid, dA, xd, A.rows)
         assert_parity(y, y_ref, bound, f"kernel {kid} on {A.name}")
+    for kid in prepared:
+        announce(f"full size {A.name}: kernel {kid} from a prepared plan")
+        plan = S.seer_spmv_prepare(kid, dA)
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_prepared(plan, dA, xd, y)
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"prepared kernel {kid} on {A.name}")
+        del plan
     return dA, xd
 
 
@@ -49,11 +56,12 @@ def test_config3_zipf_nnz_matched():
     """Zipf exponent 1.85: the variant whose nonzero count (~47 M) matches the stated one."""
     A = G.zipf_rows(s=1.85)
     assert A.rows == 2_000_000 and int(np.diff(A.row_ptr).max()) == 200_000
-    check_all(A)
+    assert S.ell_plan_bytes(A.rows, 200_000) == 0          # ELL,TM does not apply to this matrix
+    check_all(A, prepared=(5,))
 
 
 def test_config3_zipf_literal_parameters():
     """Zipf exponent 1.6 as stated (~4.8e8 nonzeros, 3.8 GB of entries)."""
     A = G.zipf_rows(s=1.6)
     assert A.nnz > 4e8 and int(np.diff(A.row_ptr).max()) == 200_000
-    check_all(A)
+    check_all(A, prepared=(5,))

@@ -163,6 +163,9 @@ def test_rows_zero_and_status_codes():
     B = G.random_lengths(100, 50, 0, 5, 3)
     dB = upload(B)
     with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv(S.ELL_TM, dB, torch.zeros(50, device="cuda:0"), torch.zeros(100, device="cuda:0"))
+    assert ei.value.status == -2          # no one-call form: its plan size depends on the matrix
+    with pytest.raises(S.SeerError) as ei:
         S.seer_spmv(S.NUM_KERNELS, dB, torch.zeros(50, device="cuda:0"), torch.zeros(100, device="cuda:0"))
     assert ei.value.status == -2
     small = torch.empty(16, dtype=torch.uint8, device="cuda:0")

@@ -168,3 +168,112 @@ def test_selection_with_an_iteration_count(cases):
             torch.cuda.synchronize()
             assert_parity(y[:A.rows].cpu().numpy(), y_ref, bound, f"planned kernel {plan.kernel_id} on {A.name}")
     assert {(0, 2), (0, 5), (1, 0), (1, 3), (1, 5)} <= seen
+
+
+# ------------------------------------------------------------------ ELL,TM
+def ell_cases(cases):
+    """Matrices whose ELL form is of reasonable size (longest row * rows <= 16 M slots)."""
+    return [c for c in cases if c[0].rows > 0 and int(np.diff(c[0].row_ptr).max(initial=0)) * c[0].rows <= 16_000_000]
+
+
+def test_ell_arrays_bit_exact(cases):
+    picks = ell_cases(cases)
+    assert len(picks) >= 12
+    for A, *_ in picks:
+        announce(f"ELL conversion {A.name} rows={A.rows} nnz={A.nnz}")
+        plan = S.seer_spmv_prepare(S.ELL_TM, upload(A))
+        want_c, want_v = O.ell_from_csr(A.rows, A.row_ptr, A.col_idx, A.values)
+        assert plan.kernel_id == S.ELL_TM and plan.ell_width == want_c.shape[0]
+        got_c, got_v = plan.ell_arrays()
+        assert np.array_equal(got_c, want_c), f"ELL columns differ on {A.name}"
+        assert got_v.tobytes() == want_v.tobytes(), f"ELL values differ on {A.name}"
+        assert S.spmv_prepared_workspace_bytes(plan) == 0
+
+
+def test_ell_product_parity(cases):
+    import torch
+    for A, x, y_ref, bound in ell_cases(cases):
+        announce(f"ELL,TM product {A.name}")
+        for mis in (False, True):
+            if mis and A.nnz == 0:
+                continue
+            dA = upload(A, misalign=mis)
+            plan = S.seer_spmv_prepare(S.ELL_TM, dA)
+            xd = torch.from_numpy(x).cuda()
+            first = None
+            for rep in range(2):
+                y = torch.full((A.rows,), float("nan"), device="cuda:0")
+                S.seer_spmv_prepared(plan, dA, xd, y)
+                torch.cuda.synchronize()
+                got = y.cpu().numpy()
+                assert_parity(got, y_ref, bound, f"ELL,TM on {A.name}")
+                first = got if first is None else first
+                assert got.tobytes() == first.tobytes()
+
+
+def test_ell_padding_is_inert_and_exact_cases():
+    """An infinite x entry must reach only the rows that hold its column (a padded slot that
+    multiplied 0 * inf would give NaN); integer data gives the exact row sums."""
+    import torch
+    A = G.small_integer_values(G.random_lengths(5000, 300, 0, 9, 41), 42)
+    x = np.round(G.dense_vector(A.cols, 43) * 4).astype(np.float32)
+    dA = upload(A)
+    plan = S.seer_spmv_prepare(S.ELL_TM, dA)
+    y = torch.empty(A.rows, device="cuda:0")
+    S.seer_spmv_prepared(plan, dA, torch.from_numpy(x).cuda(), y)
+    y_ref, _ = oracle_of(A, x)
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), y_ref)
+    x[0] = np.inf
+    S.seer_spmv_prepared(plan, dA, torch.from_numpy(x).cuda(), y)
+    got = y.cpu().numpy()
+    has0 = np.array([0 in A.col_idx[A.row_ptr[i]:A.row_ptr[i + 1]] for i in range(A.rows)])
+    assert not np.any(np.isnan(got[~has0])) and np.all(np.isfinite(got[~has0]))
+    assert np.all(~np.isfinite(got[has0]))
+
+
+def test_ell_in_a_hip_graph_and_status_codes(cases):
+    import torch
+    A, x, y_ref, bound = next(c for c in cases if c[0].name.startswith("laplace5_100"))
+    dA, xd = upload(A), torch.from_numpy(x).cuda()
+    plan = S.seer_spmv_prepare(S.ELL_TM, dA)
+    y = torch.full((A.rows,), float("nan"), device="cuda:0")
+    S.seer_spmv_prepared(plan, dA, xd, y)
+    torch.cuda.synchronize()
+    eager = y.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        S.seer_spmv_prepared(plan, dA, xd, y)
+    for rep in range(3):
+        y.fill_(float("nan"))
+        _ = run_spmv(S.CSR_BM, dA, xd, A.rows)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager)
+    assert_parity(y.cpu().numpy(), y_ref, bound, "ELL,TM graph replay")
+    # plan memory too small: the call says how much it needs
+    small = torch.empty(S.features_workspace_bytes(A.rows), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_prepare(S.ELL_TM, dA, plan_mem=small)
+    assert ei.value.status == -4
+    assert S.ell_plan_bytes(A.rows, 5) == 2 * (-(-A.rows // 64) * 64) * 5 * 4
+    # a row so long that the padded arrays cannot be indexed: not applicable
+    assert S.ell_plan_bytes(2_000_000, 200_000) == 0
+    giant = upload(G.explicit_lengths([0] * 50_000 + [70_000] + [0] * 50_000, 70_000, 7, "giant row"))
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_prepare(S.ELL_TM, giant, plan_mem=torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0"))
+    assert ei.value.status == -1
+
+
+def test_plan_falls_back_to_adaptive_when_ell_does_not_fit(cases):
+    import torch
+    always_ell = S.Tree.constant(S.ELL_TM)
+    model = S.Model(always_ell, always_ell, S.Tree([-1], [0.0], [-1], [-1], [1], n_classes=2))
+    for name, want in (("laplace5_100", S.ELL_TM), ("giant-row-among-empties", S.CSR_A)):
+        A, x, y_ref, bound = next(c for c in cases if c[0].name.startswith(name))
+        dA, xd = upload(A), torch.from_numpy(x).cuda()
+        plan_mem = S.alloc_workspace(max(S.plan_bytes(S.CSR_A, A.rows, A.nnz), 1 << 20))
+        plan, path = S.seer_spmv_plan(dA, model, 50, plan_mem=plan_mem)
+        assert path == 1 and plan.kernel_id == want, name
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_prepared(plan, dA, xd, y)
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"planned {S.kernel_name(plan.kernel_id)} on {name}")
