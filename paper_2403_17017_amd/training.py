@@ -7,7 +7,7 @@ the classifier-selection model that decides, from the known features alone, whet
 gathering is worth its cost.  The trees are stored as the flat node arrays that
 `seer_select` / `seer_spmv_auto` / `seer_spmv_model` walk.
 
-    python -m paper_2403_17017_amd.training sweep --count 1000 --out gpurun_out/sweep.csv
+    python -m paper_2403_17017_amd.training sweep --count 3000 --out gpurun_out/sweep.csv
     python -m paper_2403_17017_amd.training fit --csv gpurun_out/sweep.csv \
            --out paper_2403_17017_amd/selector_model.json
     python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv \
@@ -577,15 +577,17 @@ def write_report_md(csv_path, model_json, eval_csv, out_md):
     names = [S.kernel_name(k) for k in range(S.NUM_KERNELS)]
     L = ["# Selector: sweep, training and held-out evaluation (MI355X)", "",
          "Commands (GPU box, repository root):", "",
-         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 1000 --out gpurun_out/sweep.csv",
+         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 3000 --out gpurun_out/sweep.csv",
          "    python -m paper_2403_17017_amd.training fit --csv gpurun_out/sweep.csv --out gpurun_out/selector_model.json",
          "    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv "
          "--model gpurun_out/selector_model.json --out gpurun_out/eval.csv",
          "    python -m paper_2403_17017_amd.training report-md --csv gpurun_out/sweep.csv "
          "--model gpurun_out/selector_model.json --eval gpurun_out/eval.csv --out profiles/selector_evaluation.md", "",
          f"Population: {len(rows)} seeded synthetic matrices (workloads/sweep_gen.py), timing 10 warm-up + 10 timed "
-         "runs per kernel, HIP-graph replay, same buffers (warm).  CSR,A is timed with a prepared plan; its "
-         "preprocessing call is timed apart (host wall clock, it waits for the device).", "",
+         "runs per kernel, HIP-graph replay, same buffers (warm).  CSR,A and ELL,TM are timed with a prepared plan; "
+         "their preprocessing calls are timed apart (host wall clock, they wait for the device).  Where the ELL "
+         "form is not applicable (beyond 2 GiB here) ELL,TM is charged what CSR,A costs: that is what "
+         "seer_spmv_plan falls back to.", "",
          f"## Sweep (all {len(rows)} matrices), sum of kernel times in us", "",
          "| family | matrices | " + " | ".join(names) + " | best per matrix (direct kernels) | fastest direct kernel counts |",
          "|---|---|" + "---|" * (len(names) + 2)]
@@ -712,7 +714,7 @@ def main(argv=None):
     sub = ap.add_subparsers(dest="cmd", required=True)
     a = sub.add_parser("sweep")
     a.add_argument("--first", type=int, default=0)
-    a.add_argument("--count", type=int, default=1000)
+    a.add_argument("--count", type=int, default=3000)
     a.add_argument("--out", default="gpurun_out/sweep.csv")
     a.add_argument("--nnz-cap", type=int, default=200_000_000)
     a.add_argument("--max-rows-exp", type=float, default=7.0)
