@@ -284,11 +284,18 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
  *   "bm_chunk"  products staged in LDS per pass of CSR,BM: 2048 or 4096
  *   "mp_ipt"    merge items per lane of CSR,MP: 7 or 15
  *   "xcd_remap" 1: consecutive tiles stay on one XCD (default), 0: round-robin
- *   "nt"        1: CSR,BM / CSR,MP load the matrix streams with the non-temporal
- *               hint (default), 0: plain loads
+ *   "nt"        1: the matrix streams are loaded with the non-temporal hint, 0: plain
+ *               loads.  Default: 1 in seer_spmv / seer_spmv_auto; in seer_spmv_prepared
+ *               (repeated products) 1 only if the matrix exceeds 192 MiB, so that a
+ *               smaller one stays in the last-level cache between products
  *   "vec"       0: CSR,BM / CSR,MP / CSR,WO / CSR,A take entries with lane-strided 4-byte
  *               loads instead of 16-byte loads (what matrices whose col_idx / values
  *               are not 16-byte aligned get anyway); default 1
+ *   "auto_fused_rows", "auto_fused_grid"  seer_spmv_auto: a matrix of at most
+ *               auto_fused_rows rows (default 8192) is gathered, selected and multiplied
+ *               in one launch, and the selection runs inside the product's launch
+ *               whenever that launch has at most auto_fused_grid workgroups (default
+ *               1024; 0: always a selection launch of its own)
  *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise
  *               (default) it first watches its pinned result word for up to 2 ms
  * Unknown name: SEER_EINVAL.  A value outside the listed set selects the default. */

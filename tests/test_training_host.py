@@ -55,6 +55,7 @@ def test_fit_recovers_planted_rule(tmp_path):
             row.update({f"t_k{k}_us": t[k] for k in range(S.NUM_KERNELS)})
             row["t_prep_k5_us"], row["t_single_k5_us"] = 60.0, 76.0   # ... but needs 60 us of preprocessing
             row["t_prep_k6_us"], row["t_single_k6_us"] = "inf", "inf"  # the ELL form applies to none of them
+            row.update({f"t_rep_k{k}_us": t[k] for k in range(S.NUM_DIRECT_KERNELS)})
             row["t_auto_mp_us"] = t[3] + 4.0          # gathering on the device costs 4 us
             w.writerow(row)
     out = tmp_path / "model.json"
