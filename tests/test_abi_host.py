@@ -199,3 +199,59 @@ def test_workspace_sizes():
     n_tiles = -(-(10**6 + 10**7) // (256 * 7))
     assert S.spmv_workspace_bytes(3, 10**6, 10**7) >= 8 * n_tiles
     assert S.features_workspace_bytes(10**6) >= 1024 * 32
+
+
+def test_plan_argument_errors_and_sizes_without_gpu():
+    """The preprocessing entry points reject bad arguments before any GPU work, and the
+    size functions give what the header states."""
+    L = S.lib()
+    dummy = (C.c_int32 * 4)()
+    A = B.seer_csr(3, 5, 2, C.cast(dummy, C.c_void_p), C.cast(dummy, C.c_void_p), C.cast(dummy, C.c_void_p))
+    plan = B.seer_plan()
+    assert L.seer_spmv_prepare(S.CSR_A, C.byref(A), None, 0, None, None) == -1            # no plan struct
+    assert L.seer_spmv_prepare(S.NUM_KERNELS, C.byref(A), None, 0, None, C.byref(plan)) == -2
+    assert L.seer_spmv_prepare(-1, C.byref(A), None, 0, None, C.byref(plan)) == -2
+    assert L.seer_spmv_prepare(S.CSR_A, None, None, 0, None, C.byref(plan)) == -1
+    assert L.seer_spmv_prepare(S.CSR_A, C.byref(A), None, 0, None, C.byref(plan)) == -4   # no plan memory
+    assert L.seer_spmv_prepare(S.ELL_TM, C.byref(A), None, 0, None, C.byref(plan)) == -4
+    # kernels without preprocessing: the call only records the id
+    assert L.seer_spmv_prepare(S.CSR_BM, C.byref(A), None, 0, None, C.byref(plan)) == 0
+    assert (plan.kernel_id, plan.rows, plan.nnz, plan.device) == (S.CSR_BM, 3, 2, None)
+    assert L.seer_spmv_prepared_workspace_bytes(C.byref(plan)) == 0
+    plan.kernel_id = S.CSR_MP
+    assert L.seer_spmv_prepared_workspace_bytes(C.byref(plan)) == S.spmv_workspace_bytes(S.CSR_MP, 3, 2)
+    assert L.seer_spmv_prepared_workspace_bytes(None) == 0
+    assert L.seer_spmv_prepared(None, C.byref(A), None, None, None, 0, None) == -1
+    # a CSR,A plan is tied to its matrix
+    plan = B.seer_plan(S.CSR_A, 4, 2, 1, 0, 0, C.cast(dummy, C.c_void_p), 16)
+    assert L.seer_spmv_prepared(C.byref(plan), C.byref(A), None, None, None, 0, None) == -1
+    # selection for several products: argument checks
+    t = S.Tree.constant(S.CSR_BM)
+    model = S.Model(t)
+    assert L.seer_spmv_plan(C.byref(A), C.byref(model.c), 0, None, 0, None, 0, None, C.byref(plan), None) == -1
+    assert L.seer_spmv_plan(C.byref(A), None, 1, None, 0, None, 0, None, C.byref(plan), None) == -1
+    assert L.seer_spmv_plan(C.byref(A), C.byref(model.c), 1, None, 0, None, 0, None, None, None) == -1
+    # sizes
+    assert S.plan_bytes(S.CSR_BM, 10**6, 10**7) == 0 and S.plan_bytes(S.ELL_TM, 10**6, 10**7) == 0
+    n_blocks = -(-10**7 // 2048)
+    assert S.plan_bytes(S.CSR_A, 10**6, 10**7) >= 8 * (n_blocks + 1)
+    assert S.plan_bytes(S.CSR_A, 10**6, 0) >= 16                                          # one block owns every row
+    assert S.spmv_workspace_bytes(S.CSR_A, 10**6, 10**7) >= S.plan_bytes(S.CSR_A, 10**6, 10**7) + 8 * n_blocks
+    assert S.spmv_workspace_bytes(S.CSR_WO, 10**6, 10**7) >= 8 * n_blocks
+    assert S.ell_plan_bytes(1000, 5) == 2 * 1024 * 5 * 4
+    assert S.ell_plan_bytes(1000, 0) > 0 and S.ell_plan_bytes(0, 5) == 0
+    assert S.ell_plan_bytes(2**20, 2**11) == 0 and S.ell_plan_bytes(2**20, 2**11 - 1) > 0   # 2^31 slots: not applicable
+
+
+def test_trees_for_the_single_product_paths_must_name_direct_kernels():
+    """seer_spmv_auto / seer_spmv_model reject, before any GPU work, a tree whose leaf names a
+    kernel that needs preprocessing."""
+    L = S.lib()
+    dummy = (C.c_int32 * 4)()
+    A = B.seer_csr(3, 5, 2, C.cast(dummy, C.c_void_p), C.cast(dummy, C.c_void_p), C.cast(dummy, C.c_void_p))
+    for kid in (S.CSR_A, S.ELL_TM):
+        t = S.Tree.constant(kid)
+        assert L.seer_spmv_auto(C.byref(A), C.byref(t.c), None, None, None, 0, None) == -3
+        never_gather = S.Tree([-1], [0.0], [-1], [-1], [0], n_classes=2)
+        model = S.Model(S.Tree.constant(S.CSR_BM), t, never_gather)
+        assert L.seer_spmv_model(C.byref(A), C.byref(model.c), None, None, None, 0, None, None, None) == -3
