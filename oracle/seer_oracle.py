@@ -28,6 +28,9 @@ What it defines
                    padded to the longest row's length, stored column-major.  The
                    layout (padding marker, row padding) is this build's; ell_spmv_python
                    multiplies from it literally.
+  * coo_rows_from_csr -- the preprocessing result of the COO,WM kernel (Table II: warp
+                   mapped over the COO format): the row index of every nonzero, in CSR
+                   order.  coo_spmv_python multiplies from (row, col, value) triples.
   * adaptive_plan -- the preprocessing result of the Adaptive-CSR schedule
                    (Sec. IV: rows are grouped by size ahead of the first
                    product): row blocks of about `chunk` nonzeros, long rows
@@ -292,4 +295,23 @@ def ell_spmv_python(rows, cols, vals, x):
             c = int(cols[j, i])
             if c >= 0:
                 y[i] += vals[j, i].item() * x[c]
+    return y
+
+
+def coo_rows_from_csr(rows: int, row_ptr) -> np.ndarray:
+    """Row index of every nonzero, in CSR order (int32 [nnz]): the third array of the COO
+    form; columns and values are the CSR arrays themselves."""
+    rp = np.asarray(row_ptr[: rows + 1], dtype=np.int64)
+    out = np.zeros(int(rp[rows]) if rows > 0 else 0, dtype=np.int32)
+    for i in range(rows):
+        out[int(rp[i]): int(rp[i + 1])] = i
+    return out
+
+
+def coo_spmv_python(rows, coo_row, col_idx, values, x):
+    """y = A x from the triples: y starts at zero (a row without a triple stays zero) and
+    every triple adds its product to its row."""
+    y = [0] * rows
+    for r, c, v in zip(coo_row, col_idx, values):
+        y[int(r)] += v * x[int(c)]
     return y

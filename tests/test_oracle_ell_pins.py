@@ -52,3 +52,26 @@ def test_worked_case_and_inert_padding():
     assert vals[:, :3].tolist() == [[1.5, 0.0, 4.0], [-2.0, 0.0, 0.0]]
     y = O.ell_spmv_python(3, cols, vals, [float("inf"), 2.0, 1.0])
     assert y == [float("inf"), 0, 8.0]           # the padded slots never touch x
+
+
+# ---------------------------------------------------------------- COO
+def test_coo_rows_invariants_and_round_trip():
+    for A in (G.random_lengths(203, 50, 0, 9, 1), G.explicit_lengths([0, 3, 0, 1, 7, 0], 9, 2, "t"),
+              G.laplacian_5pt(7), G.explicit_lengths([0, 0, 0], 4, 3, "empty")):
+        r = O.coo_rows_from_csr(A.rows, A.row_ptr)
+        assert r.dtype == np.int32 and r.shape == (A.nnz,)
+        assert np.all(np.diff(r) >= 0)                                     # CSR order
+        assert np.array_equal(np.bincount(r, minlength=A.rows), np.diff(A.row_ptr))   # row_ptr comes back
+        # restated without slices: nonzero k belongs to the row whose range holds k
+        for k in range(0, A.nnz, max(1, A.nnz // 50)):
+            assert A.row_ptr[r[k]] <= k < A.row_ptr[r[k] + 1]
+
+
+def test_product_from_coo_is_the_row_sum():
+    A = G.small_integer_values(G.random_lengths(150, 40, 0, 12, 8), 9)
+    x = np.round(G.dense_vector(A.cols, 10) * 4).astype(np.float32)
+    r = O.coo_rows_from_csr(A.rows, A.row_ptr)
+    y = O.coo_spmv_python(A.rows, r, A.col_idx, [float(v) for v in A.values], [float(v) for v in x])
+    y_ref, _ = O.spmv(A.rows, A.row_ptr, A.col_idx, A.values, x)
+    assert np.array_equal(np.array(y, dtype=np.float64), y_ref)
+    assert O.coo_rows_from_csr(3, [0, 2, 2, 3]).tolist() == [0, 0, 2]
