@@ -342,7 +342,7 @@ def main():
         best = min(extras["per_kernel_cold_us"].values())
         # the kernels with preprocessing, from a prepared plan (one plan per rotating copy)
         extras["prepared_cold_us"], extras["prepared_warm_us"], extras["prepare_call_us"] = {}, {}, {}
-        for k in (S.CSR_A, S.ELL_TM):
+        for k in (S.CSR_A, S.ELL_TM, S.COO_WM):
             for R, key in ((rot, "prepared_cold_us"), (warm, "prepared_warm_us")):
                 plans = [S.seer_spmv_prepare(k, R[i][0]) for i in range(R.n)]
                 reps = max(n_sets, 20)

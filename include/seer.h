@@ -60,7 +60,11 @@ enum {
                         longest row's length, stored column-major, so that a wave's
                         loads are contiguous (Table II, "TM ... CSR, ELL").  The
                         conversion is its preprocessing; it has no one-call form.      */
-    SEER_NUM_KERNELS = 7
+    SEER_COO_WM = 7, /* wavefront mapped over the COO format: a wave takes 512 consecutive
+                        (row, column, value) triples and reduces them by row (Table II,
+                        "WM ... CSR, COO").  Its preprocessing expands row_ptr into one
+                        row index per nonzero; columns and values are the CSR arrays.   */
+    SEER_NUM_KERNELS = 8
 };
 
 /* CSR matrix, fp32 values, int32 indices.  All pointers DEVICE, caller-owned.
@@ -154,8 +158,8 @@ int seer_select(const seer_features_t *f, const seer_tree *tree, int *kernel_id)
  * rows == 0: nothing is written.  Asynchronous on `stream`.
  * workspace: at least seer_spmv_workspace_bytes(kernel_id, rows, nnz) bytes (0 for
  * ids 0-2, then workspace may be NULL).
- * SEER_CSR_A in this single call runs its preprocessing pass first, every time (what
- * one product with it costs); seer_spmv_prepare / seer_spmv_prepared split the two.
+ * SEER_CSR_A and SEER_COO_WM in this single call run their preprocessing pass first, every
+ * time (what one product with them costs); seer_spmv_prepare / seer_spmv_prepared split the two.
  * SEER_ELL_TM has no one-call form (SEER_EKERNEL): the size of its plan is only known
  * after a look at the matrix. */
 int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y,
@@ -247,6 +251,7 @@ size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
  * seer_ell_plan_bytes(rows, longest row).  If plan_mem is too small the call returns
  * SEER_EWORKSPACE with plan->device_bytes = the bytes needed; SEER_EINVAL if the format
  * is not applicable.
+ * For SEER_COO_WM: writes the row index of every nonzero, in CSR order (int32 [nnz]).
  * HOST-SYNCHRONOUS: returns after the pass has finished (it reads back whether any row
  * is split, or the longest row).  plan_mem: DEVICE, 16-byte aligned, >= seer_plan_bytes();
  * may be NULL for kernels that need no plan (the call then only records the id).  Not

@@ -17,10 +17,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libseer.so")
 
 NUM_FEATURES = 13
-NUM_KERNELS = 7
+NUM_KERNELS = 8
 NUM_DIRECT_KERNELS = 5          # ids below this need no preprocessing
-CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, ELL_TM = range(7)
-ONE_CALL_KERNELS = (CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A)   # what seer_spmv accepts
+CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, ELL_TM, COO_WM = range(8)
+ONE_CALL_KERNELS = (CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, COO_WM)   # what seer_spmv accepts
 FEATURE_NAMES = (
     "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
     "mean_density", "max_density", "min_density", "var_density", "iterations",
@@ -368,6 +368,11 @@ class Plan:
         cols = self.plan_mem[: n * 4].view(torch.int32).cpu().numpy().reshape(self.ell_width, rows_pad)
         vals = self.plan_mem[half: half + n * 4].view(torch.float32).cpu().numpy().reshape(self.ell_width, rows_pad)
         return cols, vals
+
+    def coo_rows(self) -> np.ndarray:
+        """Row index of every nonzero (int32 [nnz]) as a host array."""
+        import torch
+        return self.plan_mem[: int(self.c.nnz) * 4].view(torch.int32).cpu().numpy()
 
     def entries(self) -> np.ndarray:
         """The (first row, first nonzero) pairs as an int32 [n_blocks + 1, 2] host array."""

@@ -53,6 +53,12 @@ void launch_ell_convert(int rows, int width, const int *rp, const int *ci, const
                         hipStream_t st);
 void launch_ell(const SpmvArgs &a, int width, const void *plan_mem, hipStream_t st);
 
+// COO,WM: plan_mem holds the row index of every nonzero; carry_ws: carry_workspace_bytes(coo_num_intervals())
+uint32_t coo_num_intervals(int rows, int nnz);
+size_t coo_plan_bytes(int rows, int nnz);
+void launch_coo_convert(int rows, const int *rp, void *plan_mem, hipStream_t st);
+void launch_coo(const SpmvArgs &a, const void *plan_mem, void *carry_ws, hipStream_t st);
+
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory
     int32_t max_len, min_len;

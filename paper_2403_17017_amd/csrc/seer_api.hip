@@ -231,7 +231,7 @@ bool tree_is_acyclic(const seer_tree *t)
     return true;
 }
 
-const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM"};
+const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM", "COO,WM"};
 
 } // namespace
 
@@ -281,6 +281,8 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz)
     if (kernel_id == SEER_CSR_WO) return carry_workspace_bytes(wo_num_tiles(rows, nnz));
     if (kernel_id == SEER_CSR_A)   // the carries, then the plan that the call builds for itself
         return carry_workspace_bytes(adaptive_num_tiles(rows, nnz)) + adaptive_plan_bytes(rows, nnz);
+    if (kernel_id == SEER_COO_WM)
+        return carry_workspace_bytes(coo_num_intervals(rows, nnz)) + coo_plan_bytes(rows, nnz);
     if (kernel_id != SEER_CSR_MP) return 0;
     // the small tile gives the larger count; cover either choice
     return mp_workspace_bytes(rows, nnz, kMpIptSmall);
@@ -548,6 +550,15 @@ static int spmv_dispatch(int kernel_id, const seer_csr *A, const float *x, float
         launch_adaptive(a, vec, plan_mem, workspace, st);
         break;
     }
+    case SEER_COO_WM: {
+        const size_t carry = carry_workspace_bytes(coo_num_intervals(A->rows, A->nnz));
+        if (!workspace || !aligned16(workspace) || workspace_bytes < carry + coo_plan_bytes(A->rows, A->nnz))
+            return SEER_EWORKSPACE;
+        void *plan_mem = static_cast<char *>(workspace) + carry;
+        launch_coo_convert(A->rows, A->row_ptr, plan_mem, st);
+        launch_coo(a, plan_mem, workspace, st);
+        break;
+    }
     case SEER_CSR_WO:
         if (!workspace || !aligned16(workspace) ||
             workspace_bytes < carry_workspace_bytes(wo_num_tiles(A->rows, A->nnz)))
@@ -568,7 +579,9 @@ static int spmv_dispatch(int kernel_id, const seer_csr *A, const float *x, float
 
 size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz)
 {
-    if (kernel_id != SEER_CSR_A || rows <= 0 || nnz < 0) return 0;
+    if (rows <= 0 || nnz < 0) return 0;
+    if (kernel_id == SEER_COO_WM) return coo_plan_bytes(rows, nnz);
+    if (kernel_id != SEER_CSR_A) return 0;
     return adaptive_plan_bytes(rows, nnz);
 }
 
@@ -612,6 +625,19 @@ int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t p
     plan->rows = A->rows;
     plan->nnz = A->nnz;
     if (kernel_id == SEER_ELL_TM && A->rows > 0) return prepare_ell(A, plan_mem, plan_bytes, stream, plan, -1);
+    if (kernel_id == SEER_COO_WM && A->rows > 0) {
+        const size_t need = coo_plan_bytes(A->rows, A->nnz);
+        if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        launch_coo_convert(A->rows, A->row_ptr, plan_mem, st);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+        e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return hip_fail(e);
+        plan->device = plan_mem;
+        plan->device_bytes = need;
+        return SEER_OK;
+    }
     if (kernel_id != SEER_CSR_A || A->rows == 0) return SEER_OK;   // nothing to prepare
     const size_t need = adaptive_plan_bytes(A->rows, A->nnz);
     if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
@@ -640,6 +666,7 @@ size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan)
     if (plan->kernel_id == SEER_CSR_A)
         return plan->split_rows ? carry_workspace_bytes((uint32_t)plan->n_blocks) : 0;
     if (plan->kernel_id == SEER_ELL_TM) return 0;
+    if (plan->kernel_id == SEER_COO_WM) return carry_workspace_bytes(coo_num_intervals(plan->rows, plan->nnz));
     return seer_spmv_workspace_bytes(plan->kernel_id, plan->rows, plan->nnz);
 }
 
@@ -647,7 +674,7 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
                        size_t workspace_bytes, void *stream)
 {
     if (!plan) return SEER_EINVAL;
-    if (plan->kernel_id != SEER_CSR_A && plan->kernel_id != SEER_ELL_TM)
+    if (plan->kernel_id != SEER_CSR_A && plan->kernel_id != SEER_ELL_TM && plan->kernel_id != SEER_COO_WM)
         return spmv_dispatch(plan->kernel_id, A, x, y, workspace, workspace_bytes, stream,
                              A ? use_nt_repeated(A) : use_nt());
     const int rc = check_csr(A, true);
@@ -655,6 +682,15 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
     if (A->rows != plan->rows || A->nnz != plan->nnz) return SEER_EINVAL;   // a plan belongs to one matrix
     if (A->rows == 0) return SEER_OK;
     if (!y || (!x && A->nnz > 0) || !plan->device) return SEER_EINVAL;
+    if (plan->kernel_id == SEER_COO_WM) {
+        if (!workspace || !aligned16(workspace) ||
+            workspace_bytes < carry_workspace_bytes(coo_num_intervals(A->rows, A->nnz)))
+            return SEER_EWORKSPACE;
+        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt_repeated(A)};
+        launch_coo(a, plan->device, workspace, static_cast<hipStream_t>(stream));
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SEER_OK : hip_fail(e);
+    }
     if (plan->kernel_id == SEER_ELL_TM) {
         SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt_repeated(A)};
         launch_ell(a, plan->ell_width, plan->device, static_cast<hipStream_t>(stream));

@@ -44,7 +44,7 @@ MAX_DEPTH = 6   # fixed before looking at any test data (the paper caps depth, v
 # sees it, t_single_k{k}_us the one-call form that prepares and multiplies.  t_rep_k{k}_us
 # is a kernel without preprocessing run through seer_spmv_prepared, the entry point for
 # repeated products (it differs from seer_spmv in how a cache-sized matrix is loaded).
-PREP_KERNELS = [S.CSR_A, S.ELL_TM]
+PREP_KERNELS = [S.CSR_A, S.ELL_TM, S.COO_WM]
 ELL_MAX_BYTES = 2 << 30     # the sweep does not build ELL forms beyond this; the run-time rule is the caller's memory
 CSV_FIELDS = (["m", "family", "rows", "cols", "nnz"] + [f"f_{n}" for n in S.FEATURE_NAMES]
               + ["t_features_us"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)]
@@ -682,7 +682,7 @@ def export_header(model_json, out_h, prefix="seer_model"):
     names = m.get("feature_names", list(S.FEATURE_NAMES))
     lines = ["/* Generated by paper_2403_17017_amd.training export-header; do not edit.",
              f" * {m.get('note', '')}", " * Feature vector f[]: " + ", ".join(f"{i} {n}" for i, n in enumerate(names)),
-             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO  5 CSR,A  6 ELL,TM;",
+             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO  5 CSR,A  6 ELL,TM  7 COO,WM;",
              " * the selector returns 0 = use the known model, 1 = gather features first. */",
              "#ifndef SEER_MODEL_GENERATED_H", "#define SEER_MODEL_GENERATED_H", ""]
     groups = [("", m)] + ([("_iterative", m["iterative"])] if "iterative" in m else [])

@@ -39,9 +39,9 @@ def test_struct_layouts_match_header():
 
 
 def test_names_and_errors():
-    assert S.lib().seer_num_kernels() == 7 == S.NUM_KERNELS
-    assert [S.kernel_name(k) for k in range(7)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM"]
-    assert S.lib().seer_kernel_name(7) is None
+    assert S.lib().seer_num_kernels() == 8 == S.NUM_KERNELS
+    assert [S.kernel_name(k) for k in range(8)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM", "COO,WM"]
+    assert S.lib().seer_kernel_name(8) is None
     assert S.strerror(0) == "ok" and "tree" in S.strerror(-3)
     with pytest.raises(S.SeerError):
         S.set_tuning("no_such_knob", 1)
@@ -160,7 +160,7 @@ def test_malformed_trees_are_rejected():
         S.Tree([0, -1, -1], [1.0, 0, 0], [1, -1, -1], [7, -1, -1], [-1, 0, 1]),     # child out of range
         S.Tree([0, 0], [1e30, 1e30], [1, 0], [1, 0], [0, 0]),                       # cycle
         S.Tree([13, -1, -1], [1.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),    # feature index too large
-        S.Tree([-1], [0.0], [-1], [-1], [7]),                                       # class out of range
+        S.Tree([-1], [0.0], [-1], [-1], [8]),                                       # class out of range
         S.Tree([0, -1, -1], [float("nan"), 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),
     ]
     for t in bad:
@@ -174,7 +174,7 @@ def test_malformed_trees_are_rejected():
 def test_spmv_argument_errors_without_gpu():
     L = S.lib()
     A = B.seer_csr(0, 0, 0, None, None, None)
-    assert L.seer_spmv(9, C.byref(A), None, None, None, 0, None) == -2
+    assert L.seer_spmv(S.NUM_KERNELS, C.byref(A), None, None, None, 0, None) == -2
     assert L.seer_spmv(-1, C.byref(A), None, None, None, 0, None) == -2
     assert L.seer_spmv(0, None, None, None, None, 0, None) == -1
     assert L.seer_spmv(0, C.byref(A), None, None, None, 0, None) == -1          # row_ptr null
@@ -238,6 +238,8 @@ def test_plan_argument_errors_and_sizes_without_gpu():
     assert S.plan_bytes(S.CSR_A, 10**6, 0) >= 16                                          # one block owns every row
     assert S.spmv_workspace_bytes(S.CSR_A, 10**6, 10**7) >= S.plan_bytes(S.CSR_A, 10**6, 10**7) + 8 * n_blocks
     assert S.spmv_workspace_bytes(S.CSR_WO, 10**6, 10**7) >= 8 * n_blocks
+    assert S.plan_bytes(S.COO_WM, 10**6, 10**7) == 4 * 10**7 + (-4 * 10**7) % 256
+    assert S.spmv_workspace_bytes(S.COO_WM, 10**6, 10**7) >= S.plan_bytes(S.COO_WM, 10**6, 10**7) + 8 * -(-10**7 // 512)
     assert S.ell_plan_bytes(1000, 5) == 2 * 1024 * 5 * 4
     assert S.ell_plan_bytes(1000, 0) > 0 and S.ell_plan_bytes(0, 5) == 0
     assert S.ell_plan_bytes(2**20, 2**11) == 0 and S.ell_plan_bytes(2**20, 2**11 - 1) > 0   # 2^31 slots: not applicable
@@ -249,7 +251,7 @@ def test_trees_for_the_single_product_paths_must_name_direct_kernels():
     L = S.lib()
     dummy = (C.c_int32 * 4)()
     A = B.seer_csr(3, 5, 2, C.cast(dummy, C.c_void_p), C.cast(dummy, C.c_void_p), C.cast(dummy, C.c_void_p))
-    for kid in (S.CSR_A, S.ELL_TM):
+    for kid in (S.CSR_A, S.ELL_TM, S.COO_WM):
         t = S.Tree.constant(kid)
         assert L.seer_spmv_auto(C.byref(A), C.byref(t.c), None, None, None, 0, None) == -3
         never_gather = S.Tree([-1], [0.0], [-1], [-1], [0], n_classes=2)

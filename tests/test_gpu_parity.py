@@ -10,7 +10,7 @@ from workloads import csr_gen as G
 from gpu_util import (announce, assert_features_equal, assert_parity, oracle_of, run_spmv, upload)
 
 pytestmark = pytest.mark.gpu
-KERNELS = [0, 1, 2, 3, 4, 5]
+KERNELS = [0, 1, 2, 3, 4, 5, 7]     # every id seer_spmv accepts (ELL,TM has no one-call form)
 
 
 def edge_cases():

@@ -277,3 +277,56 @@ def test_plan_falls_back_to_adaptive_when_ell_does_not_fit(cases):
         y = torch.full((A.rows,), float("nan"), device="cuda:0")
         S.seer_spmv_prepared(plan, dA, xd, y)
         assert_parity(y.cpu().numpy(), y_ref, bound, f"planned {S.kernel_name(plan.kernel_id)} on {name}")
+
+
+# ------------------------------------------------------------------ COO,WM
+def test_coo_rows_bit_exact_and_product_parity(cases):
+    import torch
+    for A, x, y_ref, bound in cases:
+        announce(f"COO,WM conversion and product {A.name} rows={A.rows} nnz={A.nnz}")
+        dA = upload(A)
+        plan = S.seer_spmv_prepare(S.COO_WM, dA)
+        assert plan.kernel_id == S.COO_WM
+        assert np.array_equal(plan.coo_rows(), O.coo_rows_from_csr(A.rows, A.row_ptr)), f"row indices differ on {A.name}"
+        xd = torch.from_numpy(x).cuda()
+        single = run_spmv(S.COO_WM, dA, xd, A.rows)
+        for rep in range(2):
+            y = torch.full((max(A.rows, 1),), float("nan"), device="cuda:0")   # every row must be written, empty ones too
+            S.seer_spmv_prepared(plan, dA, xd, y)
+            torch.cuda.synchronize()
+            got = y[:A.rows].cpu().numpy()
+            assert_parity(got, y_ref, bound, f"COO,WM on {A.name}")
+            assert got.tobytes() == single.tobytes()
+        if A.nnz:
+            dM = upload(A, misalign=True)
+            y = torch.full((A.rows,), float("nan"), device="cuda:0")
+            S.seer_spmv_prepared(S.seer_spmv_prepare(S.COO_WM, dM), dM, xd, y)
+            assert_parity(y.cpu().numpy(), y_ref, bound, f"COO,WM misaligned on {A.name}")
+
+
+def test_coo_in_a_hip_graph_and_status_codes(cases):
+    import torch
+    A, x, y_ref, bound = next(c for c in cases if c[0].name.startswith("zipf1.6_20011"))
+    dA, xd = upload(A), torch.from_numpy(x).cuda()
+    plan = S.seer_spmv_prepare(S.COO_WM, dA)
+    ws = S.alloc_workspace(S.spmv_prepared_workspace_bytes(plan))
+    y = torch.full((A.rows,), float("nan"), device="cuda:0")
+    S.seer_spmv_prepared(plan, dA, xd, y, ws)
+    torch.cuda.synchronize()
+    eager = y.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        S.seer_spmv_prepared(plan, dA, xd, y, ws)
+    for rep in range(3):
+        y.fill_(float("nan"))
+        _ = run_spmv(S.CSR_BM, dA, xd, A.rows)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager)
+    assert_parity(y.cpu().numpy(), y_ref, bound, "COO,WM graph replay")
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_prepare(S.COO_WM, dA, plan_mem=torch.empty(16, dtype=torch.uint8, device="cuda:0"))
+    assert ei.value.status == -4
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_prepared(plan, dA, xd, y, workspace=torch.empty(16, dtype=torch.uint8, device="cuda:0"))
+    assert ei.value.status == -4
