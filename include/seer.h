@@ -4,7 +4,11 @@
  *
  * Runtime flow (Sec. III-B, "Runtime Inference"): gather the dynamically computed
  * features of the matrix, walk a decision tree over them to obtain a kernel index,
- * run that SpMV kernel.  The three calls below are those three steps.
+ * run that SpMV kernel.  seer_features, seer_select and seer_spmv are those three steps;
+ * seer_spmv_auto and seer_spmv_model run them without the host in between; and for
+ * several products with one matrix (Sec. V) seer_spmv_plan selects with the iteration
+ * count, runs the chosen kernel's preprocessing once, and seer_spmv_prepared is each
+ * product.
  *
  * General rules
  *   - Plain C types only.  Every pointer is marked DEVICE (memory the current HIP
@@ -12,10 +16,13 @@
  *   - The library never allocates or frees device memory.  Scratch is a caller
  *     buffer handed in as (workspace, workspace_bytes); its contents on entry do
  *     not matter and are undefined on return.  Required sizes come from the
- *     *_workspace_bytes calls.  A workspace must be 16-byte aligned.
+ *     *_workspace_bytes calls.  A workspace must be 16-byte aligned.  What a
+ *     preprocessing pass produces lives in a second caller buffer (plan_mem), which
+ *     the products then only read.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
- *     device work is enqueued on it.  seer_spmv returns without waiting;
- *     seer_features waits for its own result because it returns host values.
+ *     device work is enqueued on it.  seer_spmv, seer_spmv_auto, seer_spmv_model and
+ *     seer_spmv_prepared return without waiting; seer_features, seer_spmv_prepare and
+ *     seer_spmv_plan wait for their own result because they return host values.
  *   - Every call returns SEER_OK (0) or a negative seer_status; on error no output
  *     is written.  Nothing throws or aborts.  Matrix contents (monotone row_ptr,
  *     column range) are NOT validated: they are the caller's contract.

@@ -5,11 +5,14 @@
 //      its finishing workgroup (features_select_kernel) derives the feature vector
 //      on the device, walks the tree (handed over by value in the kernel arguments)
 //      and leaves the chosen kernel id in device memory;
-//   2. spmv_auto_kernel: one kernel that contains all four schedules; every
-//      workgroup reads the chosen id and runs that schedule's body (the grid is
-//      sized for the schedule that needs the most workgroups, the rest exit);
-//   3. spmv_auto_fixup_kernel: the merge-path carry fix-up; exits at once unless
-//      merge path was chosen.
+//   2. spmv_auto_kernel: one kernel that contains the five CSR schedules that need no
+//      preprocessing; every workgroup reads the chosen id and runs that schedule's
+//      body (the grid is sized for the schedule that needs the most workgroups, the
+//      rest exit);
+//   3. spmv_auto_fixup_kernel: the carry fix-up of merge path and of the nonzero
+//      split; exits at once unless one of them was chosen.
+// When the product's grid is small, steps 1 and 2 share a launch (or, for a small
+// matrix, are one launch): see spmv_auto_fused_kernel.
 //
 // The host only enqueues; feature collection costs the reduction kernel itself
 // instead of a launch, a wait and a second launch.  The sequence has no host-side
