@@ -94,6 +94,7 @@ struct AutoSel {                            // what the selection kernel leaves 
 struct AutoShape {                          // launch shapes, all from rows and nnz alone
     uint32_t tiles[SEER_NUM_DIRECT_KERNELS];
     int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
+    int tm_wide;                            // CSR,TM fetches four entries per load (mean row length <= 8)
 };
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
 constexpr size_t kAutoCarryOffset = 32768 + 256;
