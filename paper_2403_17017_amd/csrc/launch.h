@@ -22,6 +22,7 @@ struct SpmvArgs {
     int nt;     // 1: matrix streams are loaded with the non-temporal hint (keeps x in L2)
 };
 
+bool tm_short_rows(int rows, int nnz);
 void launch_tm(const SpmvArgs &a, hipStream_t st);
 void launch_wm(const SpmvArgs &a, int lanes_per_row, hipStream_t st);
 void launch_bm(const SpmvArgs &a, int rows_per_block, int chunk, bool vec, hipStream_t st);
@@ -94,7 +95,7 @@ struct AutoSel {                            // what the selection kernel leaves 
 struct AutoShape {                          // launch shapes, all from rows and nnz alone
     uint32_t tiles[SEER_NUM_DIRECT_KERNELS];
     int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
-    int tm_wide;                            // CSR,TM fetches four entries per load (mean row length <= 8)
+    int tm_short;                           // CSR,TM fetches the first eight entries of a row at once (mean row length <= 8)
 };
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
 constexpr size_t kAutoCarryOffset = 32768 + 256;

@@ -424,7 +424,7 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     sh.bm_rows = bm_rows(A->rows, A->nnz);
     sh.bm_own_shift = bm_own_shift(sh.bm_rows);
     sh.mp_ipt = mp_ipt(A->rows, A->nnz);
-    sh.tm_wide = (uint64_t)A->nnz <= 8ull * (uint64_t)A->rows;
+    sh.tm_short = tm_short_rows(A->rows, A->nnz);
     const uint32_t rows = (uint32_t)A->rows;
     sh.tiles[SEER_CSR_TM] = (rows + 255u) / 256u;
     sh.tiles[SEER_CSR_WM] = (rows + (256u / sh.wm_lanes) - 1u) / (256u / sh.wm_lanes);

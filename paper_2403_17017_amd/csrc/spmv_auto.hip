@@ -133,8 +133,8 @@ __device__ __forceinline__ void auto_dispatch(
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
     if (k == SEER_CSR_TM) {
-        if (shape.tm_wide) tm_body<true>(rows, rp, ci, va, x, y, tile);
-        else tm_body<false>(rows, rp, ci, va, x, y, tile);
+        if (shape.tm_short) tm_body<true>(rows, nnz, rp, ci, va, x, y, tile);
+        else tm_body<false>(rows, nnz, rp, ci, va, x, y, tile);
     } else if (k == SEER_CSR_WM) {
         switch (shape.wm_lanes) {
         case 2: wm_body<2>(rows, rp, ci, va, x, y, tile); break;

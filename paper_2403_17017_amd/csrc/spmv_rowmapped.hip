@@ -4,15 +4,15 @@
 
 namespace seer {
 
-template <bool WIDE>
+template <bool SHORT>
 __global__ __launch_bounds__(kWG) void spmv_tm_kernel(
-    int rows, const int *__restrict__ rp, const int *__restrict__ ci,
+    int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
     uint32_t n_tiles, int remap)
 {
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
-    tm_body<WIDE>(rows, rp, ci, va, x, y, tile);
+    tm_body<SHORT>(rows, nnz, rp, ci, va, x, y, tile);
 }
 
 template <int G>
@@ -44,15 +44,17 @@ static inline uint32_t grid_for(uint32_t n_tiles, int remap)
     return remap ? tiles_per_xcd(n_tiles) * kXCD : n_tiles;
 }
 
+bool tm_short_rows(int rows, int nnz) { return (uint64_t)nnz <= 8ull * (uint64_t)rows; }
+
 void launch_tm(const SpmvArgs &a, hipStream_t st)
 {
     const uint32_t n_tiles = ((uint32_t)a.rows + kWG - 1) / kWG;
-    if (a.nt && (uint64_t)a.nnz <= 8ull * (uint64_t)a.rows)   // short rows, streaming regime: wide loads
+    if (tm_short_rows(a.rows, a.nnz))
         hipLaunchKernelGGL(spmv_tm_kernel<true>, dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                           a.rows, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap);
+                           a.rows, a.nnz, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap);
     else
         hipLaunchKernelGGL(spmv_tm_kernel<false>, dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                           a.rows, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap);
+                           a.rows, a.nnz, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap);
 }
 
 template <int G>
