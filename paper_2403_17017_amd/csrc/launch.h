@@ -85,6 +85,17 @@ struct AutoTree {                           // passed to the kernel by value
     int32_t n_nodes, pad;
     seer_node nodes[kAutoMaxNodes];
 };
+// A tree of depth <= 6 laid out as a complete binary tree (slot i has children 2i + 1 and
+// 2i + 2): one wave can then load every node at once, evaluate all comparisons in parallel
+// and find the leaf with bit operations, instead of one dependent load per level.
+constexpr int kHeapInternal = 63;           // slots 0..62 can be internal nodes, 63..126 are leaves
+struct AutoHeap {                           // passed to the kernel by value (896 bytes)
+    int32_t feature[64];                    // -1: the slot is a leaf (or not reachable)
+    double threshold[64];
+    int8_t klass[128];                      // kernel id of every slot that is a leaf
+};
+bool flatten_tree(const seer_tree *tree, AutoHeap *heap);   // false: deeper than 6 levels of comparisons
+
 struct AutoSel {                            // what the selection kernel leaves in the workspace
     int32_t kernel_id, valid;
     int64_t rows, cols, nnz;
@@ -103,8 +114,9 @@ size_t auto_workspace_bytes(int rows, int nnz);
 constexpr int kAutoFusedRows = 8192;        // up to here every workgroup gathers and selects for itself
 constexpr int kAutoFusedGrid = 1024;        // the product's launch selects for itself up to this many workgroups
 constexpr uint32_t kAutoFusedParts = 64;    // partials the first pass leaves for it (each workgroup reads them all)
-void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, int fused_rows,
-                 int fused_grid, void *workspace, hipStream_t st);
+// heap: the flattened tree, or null if it is too deep (then the node array is walked)
+void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, const AutoShape &shape, bool vec,
+                 int fused_rows, int fused_grid, void *workspace, hipStream_t st);
 
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);
 void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st);

@@ -179,6 +179,37 @@ void derive(seer_features_t *o)
     }
 }
 
+} // namespace
+
+// Lays a validated, acyclic tree out as a complete binary tree of depth 6; false if some
+// comparison lies deeper than that.
+bool seer::flatten_tree(const seer_tree *t, AutoHeap *h)
+{
+    for (int i = 0; i < 64; ++i) { h->feature[i] = -1; h->threshold[i] = 0.0; }
+    for (int i = 0; i < 128; ++i) h->klass[i] = (int8_t)SEER_CSR_MP;
+    struct Item { int node, slot; };
+    Item stack[256];
+    int top = 0;
+    stack[top++] = Item{0, 0};
+    while (top > 0) {
+        const Item it = stack[--top];
+        const seer_node &nd = t->nodes[it.node];
+        if (nd.feature < 0) {
+            const int k = (nd.klass >= 0 && nd.klass < SEER_NUM_DIRECT_KERNELS) ? nd.klass : SEER_CSR_MP;
+            h->klass[it.slot] = (int8_t)k;
+            continue;                                  // feature[slot] stays -1 for slots below 63
+        }
+        if (it.slot >= kHeapInternal) return false;    // a comparison on the seventh level
+        h->feature[it.slot] = nd.feature;
+        h->threshold[it.slot] = nd.threshold;
+        stack[top++] = Item{nd.left, 2 * it.slot + 1};
+        stack[top++] = Item{nd.right, 2 * it.slot + 2};
+    }
+    return true;
+}
+
+namespace {
+
 // every leaf names a kernel id below `limit`
 bool leaves_below(const seer_tree *t, int limit)
 {
@@ -434,7 +465,9 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), 1};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
     const int fg = g_tune_fused_grid.load();
-    launch_auto(a, dt, sh, vec, auto_fused_rows(), fg < 0 ? kAutoFusedGrid : fg, workspace,
+    AutoHeap heap;
+    const bool flat = flatten_tree(tree, &heap);
+    launch_auto(a, dt, flat ? &heap : nullptr, sh, vec, auto_fused_rows(), fg < 0 ? kAutoFusedGrid : fg, workspace,
                 static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);

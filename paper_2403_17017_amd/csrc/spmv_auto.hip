@@ -103,6 +103,88 @@ __device__ __forceinline__ int select_on_device(
     return k;
 }
 
+// ---- selection from the flattened tree (depth <= 6), by the first wave of a workgroup.
+// Walking the node array costs one dependent load from the kernel-argument memory per
+// level (measured: 2.3 us of a 26 us step for a depth-6 tree).  Here every lane fetches one
+// slot when the kernel starts, long before the statistics are ready; afterwards all
+// comparisons are evaluated at once and the leaf is found with two ballots.
+struct HeapRegs {
+    int feature;
+    double threshold;
+    int klass_inner, klass_leaf;   // of slot lane, and of slot 63 + lane
+};
+
+__device__ __forceinline__ HeapRegs heap_load(const AutoHeap &h)
+{
+    const int l = threadIdx.x % kWave;
+    return HeapRegs{h.feature[l], h.threshold[l], (int)h.klass[l], (int)h.klass[kHeapInternal + l]};
+}
+
+// All 64 lanes of one wave; s_f is the feature vector in LDS (complete and visible).
+__device__ __forceinline__ int heap_walk(const HeapRegs &r, const float *s_f)
+{
+    const bool leaf = r.feature < 0;
+    const bool right = !leaf && !((double)s_f[leaf ? 0 : r.feature] <= r.threshold);
+    const uint64_t leaf_mask = __ballot(leaf), right_mask = __ballot(right);
+    int i = 0;
+#pragma unroll
+    for (int d = 0; d < 6; ++d) {
+        if ((leaf_mask >> i) & 1) break;              // i <= 62 here
+        i = 2 * i + 1 + (int)((right_mask >> i) & 1);
+    }
+    const int k = i < kHeapInternal ? __shfl(r.klass_inner, i) : __shfl(r.klass_leaf, i - kHeapInternal);
+    return (k >= 0 && k < SEER_NUM_DIRECT_KERNELS) ? k : SEER_CSR_MP;
+}
+
+__device__ __forceinline__ void write_selection(
+    AutoSel *__restrict__ sel, int k, int rows, int cols, int64_t nnz, const FeatLds *s, const float *s_f)
+{
+    sel->kernel_id = k;
+    sel->valid = 1;
+    sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
+    sel->max_len = s->mx; sel->min_len = s->mn;
+    sel->sum_sq = s->sq; sel->empty = s->em;
+#pragma unroll
+    for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
+}
+
+// The workgroup's statistics are in *s (after a barrier).  Derives the features (one lane),
+// walks the flattened tree (first wave) and leaves the kernel id in *s_k for everyone; ends
+// with a barrier.
+__device__ __forceinline__ void select_with_heap(
+    int rows, int cols, const int *__restrict__ rp, const FeatLds *s, float *s_f, const HeapRegs &hr,
+    AutoSel *__restrict__ sel, int *s_k)
+{
+    int64_t nnz = 0;
+    if (threadIdx.x == 0) {
+        nnz = (int64_t)rp[rows] - (int64_t)rp[0];
+        derive_features_device(rows, cols, nnz, s->mx, s->mn, (int64_t)s->em, s->sq, s_f);
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {
+        const int k = heap_walk(hr, s_f);
+        if (threadIdx.x == 0) {
+            *s_k = k;
+            if (sel) write_selection(sel, k, rows, cols, nnz, s, s_f);
+        }
+    }
+    __syncthreads();
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kFeatWG) void features_select_heap_kernel(
+    int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
+    AutoSel *__restrict__ sel, const AutoHeap heap)
+{
+    __shared__ FeatLds s;
+    __shared__ float s_f[SEER_NUM_FEATURES];
+    __shared__ int s_k;
+    HeapRegs hr{};
+    if (threadIdx.x < kWave) hr = heap_load(heap);
+    features_total<VEC>(rows, rp, part, n_part, &s);
+    select_with_heap(rows, cols, rp, &s, s_f, hr, sel, &s_k);
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
     int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
@@ -183,12 +265,14 @@ __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
     int rows, int cols, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
     int *__restrict__ carry_row, float *__restrict__ carry_val, const FeatPartial *__restrict__ part,
-    uint32_t n_part, AutoSel *__restrict__ sel, const AutoTree tree, const AutoShape shape, int remap)
+    uint32_t n_part, AutoSel *__restrict__ sel, const AutoHeap heap, const AutoShape shape, int remap)
 {
     __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
     __shared__ FeatLds s;
     __shared__ float s_f[SEER_NUM_FEATURES];
     __shared__ int s_k;
+    HeapRegs hr{};
+    if (threadIdx.x < kWave) hr = heap_load(heap);
     int32_t mx, mn;
     uint64_t sq, em;
     if (n_part == 0) {
@@ -204,8 +288,7 @@ __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
         }
     }
     features_block_fold(mx, mn, sq, em, &s);
-    if (threadIdx.x == 0) s_k = select_on_device(rows, cols, rp, &s, s_f, tree, blockIdx.x == 0 ? sel : nullptr);
-    __syncthreads();
+    select_with_heap(rows, cols, rp, &s, s_f, hr, blockIdx.x == 0 ? sel : nullptr, &s_k);
     auto_dispatch<IPT, VEC>(s_k, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
 }
 
@@ -225,8 +308,8 @@ size_t auto_workspace_bytes(int rows, int nnz)
     return kAutoCarryOffset + (mp > wo ? mp : wo);
 }
 
-void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape, bool vec, int fused_rows,
-                 int fused_grid, void *workspace, hipStream_t st)
+void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, const AutoShape &shape, bool vec,
+                 int fused_rows, int fused_grid, void *workspace, hipStream_t st)
 {
     char *ws = static_cast<char *>(workspace);
     FeatPartial *part = reinterpret_cast<FeatPartial *>(ws);
@@ -243,7 +326,7 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
         grid = g > grid ? g : grid;
     }
     const bool rp_vec = (reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0;
-    if (grid <= (uint32_t)fused_grid) {
+    if (heap && grid <= (uint32_t)fused_grid) {
         // one launch for a small matrix; else a first pass that leaves a few partials
         uint32_t n_part = 0;
         if (a.rows > fused_rows) {
@@ -256,7 +339,7 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
         }
 #define SEER_FUSED_LAUNCH(I, V, R)                                                                          \
     hipLaunchKernelGGL((spmv_auto_fused_kernel<I, V, R>), dim3(grid), dim3(kWG), 0, st, a.rows, a.cols, a.nnz, \
-                       a.rp, a.ci, a.va, a.x, a.y, carry_row, carry_val, part, n_part, sel, tree, shape, a.remap)
+                       a.rp, a.ci, a.va, a.x, a.y, carry_row, carry_val, part, n_part, sel, *heap, shape, a.remap)
         if (shape.mp_ipt == kMpIptSmall) {
             if (vec) { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptSmall, true, true); else SEER_FUSED_LAUNCH(kMpIptSmall, true, false); }
             else     { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptSmall, false, true); else SEER_FUSED_LAUNCH(kMpIptSmall, false, false); }
@@ -274,13 +357,21 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoShape &shape
     if (rp_vec) {
         if (n_part)
             hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
-        hipLaunchKernelGGL(features_select_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
-                           n_part, sel, tree);
+        if (heap)
+            hipLaunchKernelGGL(features_select_heap_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp,
+                               part, n_part, sel, *heap);
+        else
+            hipLaunchKernelGGL(features_select_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
+                               n_part, sel, tree);
     } else {
         if (n_part)
             hipLaunchKernelGGL(features_partial_kernel<false>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
-        hipLaunchKernelGGL(features_select_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
-                           n_part, sel, tree);
+        if (heap)
+            hipLaunchKernelGGL(features_select_heap_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp,
+                               part, n_part, sel, *heap);
+        else
+            hipLaunchKernelGGL(features_select_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
+                               n_part, sel, tree);
     }
 
 #define SEER_AUTO_LAUNCH(I, V)                                                                             \

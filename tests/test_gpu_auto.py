@@ -57,6 +57,46 @@ def test_auto_matches_oracle_and_three_call_path(cases, forced):
         assert f3.vector().tobytes() == f.vector().tobytes() and S.seer_select(f3, tree) == kid
 
 
+def test_auto_with_trees_of_every_depth(cases):
+    """Trees up to six comparisons deep are evaluated from a flattened copy, deeper ones by
+    walking the node array: both must agree with the oracle's walk.  Chains of comparisons on
+    nnz with leaves that cycle through the direct kernels, 1 to 9 levels deep, plus a full
+    depth-6 tree over several features."""
+    import torch
+    rng = np.random.default_rng(17)
+    trees = []
+    for depth in range(1, 10):
+        # node 2j: nnz <= t_j ? leaf (node 2j + 1) : node 2j + 2; the last node is a leaf
+        feat, thr, left, right, kl = [], [], [], [], []
+        for j in range(depth):
+            feat += [2, -1]; thr += [float(10 ** (j * 0.9)), 0.0]
+            left += [2 * j + 1, -1]; right += [2 * j + 2, -1]; kl += [-1, j % S.NUM_DIRECT_KERNELS]
+        feat.append(-1); thr.append(0.0); left.append(-1); right.append(-1); kl.append(depth % S.NUM_DIRECT_KERNELS)
+        trees.append(S.Tree(feat, thr, left, right, kl))
+    # full binary tree, depth 6, heap order, random features and thresholds near typical values
+    n_int, feat, thr, left, right, kl = 63, [], [], [], [], []
+    for i in range(127):
+        if i < n_int:
+            f = int(rng.choice([0, 2, 3, 4, 5, 6, 7, 9, 11]))
+            t = float({0: 3000, 2: 50000, 3: 6, 4: 40, 5: 1, 6: 30, 7: 0.2, 9: 0.01, 11: 1e-6}[f] * rng.uniform(0.3, 3))
+            feat.append(f); thr.append(t); left.append(2 * i + 1); right.append(2 * i + 2); kl.append(-1)
+        else:
+            feat.append(-1); thr.append(0.0); left.append(-1); right.append(-1); kl.append(int(rng.integers(S.NUM_DIRECT_KERNELS)))
+    trees.append(S.Tree(feat, thr, left, right, kl))
+    seen = set()
+    for A, x, y_ref, bound in cases:
+        dA, xd = upload(A), torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        want_f = O.features(A.rows, A.cols, A.row_ptr)["f"]
+        for ti, tree in enumerate(trees):
+            announce(f"auto path, tree #{ti} ({len(tree.arrays[0])} nodes), {A.name}")
+            y, f, kid = run_auto(dA, tree, xd, A.rows, ws)
+            assert kid == O.select(want_f, *tree.arrays), (ti, A.name)
+            assert_parity(y, y_ref, bound, f"auto tree #{ti} (kernel {kid}) on {A.name}")
+            seen.add((ti, kid))
+    assert len({k for _, k in seen}) == S.NUM_DIRECT_KERNELS
+
+
 def test_auto_misaligned_and_repeated(cases):
     import torch
     tree = S.Tree(*REAL_TREE)
