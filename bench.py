@@ -342,7 +342,10 @@ def main():
         best = min(extras["per_kernel_cold_us"].values())
         # the kernels with preprocessing, from a prepared plan (one plan per rotating copy)
         extras["prepared_cold_us"], extras["prepared_warm_us"], extras["prepare_call_us"] = {}, {}, {}
+        max_len = int(S.seer_features(warm[0][0]).max_len)
         for k in (S.CSR_A, S.ELL_TM, S.COO_WM):
+            if k == S.ELL_TM and S.ell_plan_bytes(A.rows, max_len) == 0:
+                continue                                   # padded arrays beyond 2^31 words: not applicable
             for R, key in ((rot, "prepared_cold_us"), (warm, "prepared_warm_us")):
                 plans = [S.seer_spmv_prepare(k, R[i][0]) for i in range(R.n)]
                 reps = max(n_sets, 20)
@@ -356,7 +359,7 @@ def main():
                 del plans
             d = warm[0][0]
             pm = S.alloc_workspace(max(S.plan_bytes(k, A.rows, A.nnz), S.features_workspace_bytes(A.rows),
-                                       S.ell_plan_bytes(A.rows, int(S.seer_features(d).max_len)) if k == S.ELL_TM else 0))
+                                       S.ell_plan_bytes(A.rows, max_len) if k == S.ELL_TM else 0))
             S.seer_spmv_prepare(k, d, pm)
             t0 = time.perf_counter()
             for _ in range(10):
