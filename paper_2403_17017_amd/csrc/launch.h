@@ -114,6 +114,7 @@ size_t auto_workspace_bytes(int rows, int nnz);
 constexpr int kAutoFusedRows = 8192;        // up to here every workgroup gathers and selects for itself
 constexpr int kAutoFusedGrid = 1024;        // the product's launch selects for itself up to this many workgroups
 constexpr uint32_t kAutoFusedParts = 64;    // partials the first pass leaves for it (each workgroup reads them all)
+constexpr uint32_t kAutoWmGrid = 4096;      // combined kernel: CSR,WM loops beyond max(this, the other schedules' grids)
 // heap: the flattened tree, or null if it is too deep (then the node array is walked)
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, const AutoShape &shape, bool vec,
                  int fused_rows, int fused_grid, void *workspace, hipStream_t st);

@@ -212,20 +212,30 @@ __device__ __forceinline__ void auto_dispatch(
 {
     static_assert(mp_lds_words<IPT>() <= kAutoLds, "LDS overlay too small");
     const uint32_t n_tiles = shape.tiles[k];
+    if (k == SEER_CSR_WM) {
+        // The one schedule whose tiles can outnumber the grid (launch_auto caps its share):
+        // a workgroup takes every gridDim-th block position; tile_of_block is one-to-one
+        // on [0, span), so each tile is still visited exactly once.
+        const uint32_t span = remap ? tiles_per_xcd(n_tiles) * kXCD : n_tiles;
+        for (uint32_t vb = blockIdx.x; vb < span; vb += gridDim.x) {
+            const uint32_t t = tile_of_block(vb, n_tiles, remap);
+            if (t >= n_tiles) continue;
+            switch (shape.wm_lanes) {
+            case 2: wm_body<2>(rows, rp, ci, va, x, y, t); break;
+            case 4: wm_body<4>(rows, rp, ci, va, x, y, t); break;
+            case 8: wm_body<8>(rows, rp, ci, va, x, y, t); break;
+            case 16: wm_body<16>(rows, rp, ci, va, x, y, t); break;
+            case 32: wm_body<32>(rows, rp, ci, va, x, y, t); break;
+            default: wm_body<64>(rows, rp, ci, va, x, y, t); break;
+            }
+        }
+        return;
+    }
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
     if (k == SEER_CSR_TM) {
         if (shape.tm_short) tm_body<true>(rows, nnz, rp, ci, va, x, y, tile);
         else tm_body<false>(rows, nnz, rp, ci, va, x, y, tile);
-    } else if (k == SEER_CSR_WM) {
-        switch (shape.wm_lanes) {
-        case 2: wm_body<2>(rows, rp, ci, va, x, y, tile); break;
-        case 4: wm_body<4>(rows, rp, ci, va, x, y, tile); break;
-        case 8: wm_body<8>(rows, rp, ci, va, x, y, tile); break;
-        case 16: wm_body<16>(rows, rp, ci, va, x, y, tile); break;
-        case 32: wm_body<32>(rows, rp, ci, va, x, y, tile); break;
-        default: wm_body<64>(rows, rp, ci, va, x, y, tile); break;
-        }
     } else if (k == SEER_CSR_BM) {
         bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
                                      reinterpret_cast<float *>(smem));
@@ -320,9 +330,19 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, 
     int *carry_row = reinterpret_cast<int *>(ws + kAutoCarryOffset);
     float *carry_val = reinterpret_cast<float *>(ws + kAutoCarryOffset + one);
 
-    uint32_t grid = 0;
+    // One workgroup per tile of the schedule with the most tiles -- except CSR,WM, whose
+    // tiles (64/G rows per wave) can be several times the others': beyond kAutoWmGrid
+    // workgroups its share is capped at the others' maximum and its workgroups loop, so a
+    // grid that runs another schedule does not launch thousands of workgroups to no purpose.
+    uint32_t grid = 0, wm_grid = 0;
     for (int k = 0; k < SEER_NUM_DIRECT_KERNELS; ++k) {
         const uint32_t g = a.remap ? tiles_per_xcd(shape.tiles[k]) * kXCD : shape.tiles[k];
+        if (k == SEER_CSR_WM) wm_grid = g;
+        else grid = g > grid ? g : grid;
+    }
+    {
+        const uint32_t cap = grid > kAutoWmGrid ? grid : kAutoWmGrid;
+        const uint32_t g = wm_grid < cap ? wm_grid : cap;
         grid = g > grid ? g : grid;
     }
     const bool rp_vec = (reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0;

@@ -191,6 +191,26 @@ def test_auto_wide_integer_features():
     assert_features_equal(S.seer_features(dA), want, "wide-integer features (host derivation)")
 
 
+def test_auto_wm_when_its_tiles_outnumber_the_grid():
+    """The combined kernel caps CSR,WM's share of the grid and lets its workgroups take
+    several tiles: every row must still be written exactly once, and the result must be
+    the stand-alone kernel's bit for bit.  Short rows (2 lanes per row, twice the
+    thread-mapped tile count) and medium rows (8 lanes per row)."""
+    import torch
+    for A in (G.laplacian_5pt(1100), G.random_lengths(300_001, 300_001, 30, 50, 77)):
+        x = G.dense_vector(A.cols, 5)
+        y_ref, bound = oracle_of(A, x)
+        dA = upload(A)
+        xd = torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        for forced in (S.CSR_WM, S.CSR_TM, S.CSR_WO):
+            announce(f"auto path, capped CSR,WM share: kernel {forced} on {A.name} rows={A.rows} nnz={A.nnz}")
+            y, f, kid = run_auto(dA, S.Tree.constant(forced), xd, A.rows, ws)
+            assert kid == forced
+            assert_parity(y, y_ref, bound, f"auto kernel {forced} on {A.name}")
+            assert np.array_equal(y, run_spmv(forced, dA, xd, A.rows))
+
+
 def test_classifier_selection_path(cases):
     """seer_spmv_model: the selector runs on the host, the known model launches a kernel
     directly, the gathered model goes through the asynchronous path; path and kernel id
