@@ -39,6 +39,11 @@ What it defines
                    plan_spmv_python executes it literally so that tests can
                    check it assigns every nonzero to its row exactly once.
 
+  * csr_defects -- the input contract of the kernels (Sec. IV-A: they consume the CSR
+                   offsets and entries as given), counted: how many offsets and how
+                   many column indices break it.  Not part of the paper's method; the
+                   definition is the contract itself, written out.
+
 Readings where the paper is silent (all listed again in the design document):
   * variance is the population variance (divide by rows);
   * integer statistics are exact; every derived float is computed in fp64 from
@@ -315,3 +320,22 @@ def coo_spmv_python(rows, coo_row, col_idx, values, x):
     for r, c, v in zip(coo_row, col_idx, values):
         y[int(r)] += v * x[int(c)]
     return y
+
+
+def csr_defects(rows: int, cols: int, nnz: int, row_ptr, col_idx):
+    """(bad offsets, bad column indices) of a CSR matrix given as rows, cols, nnz and its
+    two integer arrays.  An offset defect is: row_ptr[0] != 0 (one), row_ptr[rows] != nnz
+    (one), and every i in [0, rows) with row_ptr[i + 1] < row_ptr[i] (one each).  A column
+    defect is every k in [0, nnz) with col_idx[k] < 0 or col_idx[k] >= cols.  A matrix with
+    (0, 0) is one every schedule may be run on: all offsets lie in [0, nnz], rows are
+    contiguous ranges, and every gather stays inside x."""
+    bad_rp = int(int(row_ptr[0]) != 0) + int(int(row_ptr[rows]) != nnz)
+    for i in range(rows):
+        if int(row_ptr[i + 1]) < int(row_ptr[i]):
+            bad_rp += 1
+    bad_ci = 0
+    for k in range(nnz):
+        c = int(col_idx[k])
+        if c < 0 or c >= cols:
+            bad_ci += 1
+    return bad_rp, bad_ci
