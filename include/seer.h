@@ -289,6 +289,21 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
                    void *plan_mem, size_t plan_bytes, void *workspace, size_t workspace_bytes,
                    void *stream, seer_plan *plan, int *path);
 
+/* Input check (the kernels consume the CSR offsets and entries as given, Sec. IV-A, and
+ * read or write out of bounds on a matrix that is not well formed; no other entry point
+ * looks at the contents).  Counts on the device
+ *   *bad_row_ptr = [row_ptr[0] != 0] + [row_ptr[rows] != nnz]
+ *                  + #{ i in [0, rows) : row_ptr[i+1] < row_ptr[i] }
+ *   *bad_col_idx = #{ k in [0, nnz) : col_idx[k] < 0 or col_idx[k] >= cols }
+ * Both zero means every schedule may run on A: offsets lie in [0, nnz], rows are
+ * contiguous ranges, gathers stay inside x.  Reads row_ptr[0..rows] and col_idx[0..nnz-1]
+ * only (A->values may be NULL; with A->col_idx NULL the column count is 0), so the arrays
+ * must have those sizes, whatever they hold.  workspace: DEVICE, 16-byte aligned, at least
+ * 16 bytes.  Host-synchronous (waits for `stream`; not capturable).  Returns SEER_OK
+ * when the check ran, whatever it found; the counts are the verdict. */
+int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* Launch-shape overrides for experiments; the defaults (value < 0) derive every
  * launch shape from rows and nnz alone (the trivially known sizes of Sec. III-A).
  *   "wm_lanes"  lanes per row of CSR,WM: 2, 4, 8, 16, 32 or 64

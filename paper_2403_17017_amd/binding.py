@@ -126,6 +126,8 @@ def lib():
         L.seer_spmv_plan.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_model), i32, vp, sz, vp, sz, vp,
                                      C.POINTER(seer_plan), C.POINTER(C.c_int)]
         L.seer_spmv_plan.restype = C.c_int
+        L.seer_csr_check.argtypes = [C.POINTER(seer_csr), C.POINTER(C.c_int64), C.POINTER(C.c_int64), vp, sz, vp]
+        L.seer_csr_check.restype = C.c_int
         L.seer_set_tuning.argtypes = [C.c_char_p, C.c_int]
         L.seer_set_tuning.restype = C.c_int
         L.seer_stream_copy.argtypes = [vp, vp, sz, vp]
@@ -241,6 +243,20 @@ def seer_features(A: DeviceCSR, workspace=None, stream=None) -> seer_features_t:
     if rc:
         raise SeerError(rc, "seer_features")
     return out
+
+
+def seer_csr_check(A: DeviceCSR, workspace=None, stream=None):
+    """(bad offsets, bad column indices) of A, counted on the device; (0, 0) means every
+    schedule may run on it.  Waits for the stream."""
+    if workspace is None:
+        workspace = alloc_workspace(16, A.row_ptr.device)
+    bad_rp, bad_ci = C.c_int64(-1), C.c_int64(-1)
+    cs = A.c_struct()
+    rc = lib().seer_csr_check(C.byref(cs), C.byref(bad_rp), C.byref(bad_ci), workspace.data_ptr(),
+                              workspace.numel(), _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_csr_check")
+    return int(bad_rp.value), int(bad_ci.value)
 
 
 def seer_derive_features(rows, cols, nnz, max_len, min_len, empty_rows, sum_sq_len) -> seer_features_t:

@@ -56,6 +56,41 @@ __global__ __launch_bounds__(kWG) void stream_sum_kernel(const uint4 *__restrict
     if (threadIdx.x % kWave == 0) out[(blockIdx.x * (kWG / kWave) + threadIdx.x / kWave) % 64] = acc;
 }
 
+// Counts what breaks the kernels' input contract: descents in row_ptr (plus a wrong first
+// or last offset) into counts[0], column indices outside [0, cols) into counts[1].  Reads
+// row_ptr[0..rows] and col_idx[0..nnz-1], whatever they hold.  A well-formed matrix issues
+// no atomic at all; otherwise one per wave that found something.
+__global__ __launch_bounds__(kWG) void csr_check_kernel(
+    int rows, int cols, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
+    unsigned long long *__restrict__ counts)
+{
+    const size_t stride = (size_t)gridDim.x * kWG;
+    const size_t first = (size_t)blockIdx.x * kWG + threadIdx.x;
+    uint32_t bad_rp = 0, bad_ci = 0;
+    for (size_t i = first; i < (size_t)rows; i += stride) bad_rp += rp[i + 1] < rp[i];
+    if (ci)
+        for (size_t k = first; k < (size_t)nnz; k += stride) bad_ci += (uint32_t)ci[k] >= (uint32_t)cols;
+    if (first == 0) bad_rp += (rp[0] != 0) + (rp[rows] != nnz);
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        bad_rp += __shfl_xor(bad_rp, off);
+        bad_ci += __shfl_xor(bad_ci, off);
+    }
+    if (threadIdx.x % kWave == 0) {
+        if (bad_rp) atomicAdd(&counts[0], (unsigned long long)bad_rp);
+        if (bad_ci) atomicAdd(&counts[1], (unsigned long long)bad_ci);
+    }
+}
+
+void launch_csr_check(int rows, int cols, int nnz, const int *rp, const int *ci, void *counts, hipStream_t st)
+{
+    const size_t n = (size_t)(rows > nnz ? rows : nnz);
+    const size_t want = (n + kWG * 4 - 1) / (kWG * 4);                 // about four items per lane
+    const uint32_t blocks = (uint32_t)(want < 1 ? 1 : (want < 256 * 16 ? want : 256 * 16));
+    hipLaunchKernelGGL(csr_check_kernel, dim3(blocks), dim3(kWG), 0, st, rows, cols, nnz, rp, ci,
+                       static_cast<unsigned long long *>(counts));
+}
+
 void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st)
 {
     const size_t n_vec = n_words / 4;

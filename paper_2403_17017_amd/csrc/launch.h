@@ -119,6 +119,7 @@ constexpr uint32_t kAutoWmGrid = 4096;      // combined kernel: CSR,WM loops bey
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, const AutoShape &shape, bool vec,
                  int fused_rows, int fused_grid, void *workspace, hipStream_t st);
 
+void launch_csr_check(int rows, int cols, int nnz, const int *rp, const int *ci, void *counts, hipStream_t st);
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);
 void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st);
 

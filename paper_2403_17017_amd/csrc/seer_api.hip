@@ -541,6 +541,28 @@ int seer_stream_copy(void *dst, const void *src, size_t n_words, void *stream)
     return e == hipSuccess ? SEER_OK : hip_fail(e);
 }
 
+int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    if (!A || !bad_row_ptr || !bad_col_idx) return SEER_EINVAL;
+    if (A->rows < 0 || A->cols < 0 || A->nnz < 0 || !A->row_ptr) return SEER_EINVAL;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < 16) return SEER_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemsetAsync(workspace, 0, 16, st);
+    if (e != hipSuccess) return hip_fail(e);
+    launch_csr_check(A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, workspace, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    unsigned long long counts[2] = {0, 0};
+    e = hipMemcpyAsync(counts, workspace, sizeof counts, hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    *bad_row_ptr = (int64_t)counts[0];
+    *bad_col_idx = (int64_t)counts[1];
+    return SEER_OK;
+}
+
 int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream)
 {
     if (n_words == 0) return SEER_OK;

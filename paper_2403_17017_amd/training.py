@@ -513,18 +513,20 @@ def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
         C = np.repeat(P[sel], len(grid), axis=0) + n[:, None] * np.repeat(T[sel], len(grid), axis=0)
         return Xe, C, np.repeat(tf[sel], len(grid)), np.repeat(sel, len(grid)), n
 
-    Xtr, Ctr, tftr, gtr, _ = expand(tr)
+    Xtr, Ctr, tftr, gtr, ntr = expand(tr)
     ytr = Ctr.argmin(axis=1)
     Xk = np.zeros_like(Xtr)
     Xk[:, KNOWN_ITER_IDX] = Xtr[:, KNOWN_ITER_IDX]
-    cost, imp = choice_costs(Ctr)
+    # costs per product: with totals, the samples at 100 products would outweigh those at one
+    # product a hundred to one and the trees would be fitted to the long runs alone
+    cost, imp = choice_costs(Ctr / ntr[:, None])
     gathered = _fit(Xtr, cost, imp)
     cost_known = neighbour_costs(Xk, cost, groups=len(grid))
     known = _fit(Xk, cost_known, imp, KNOWN_ITER_IDX)
     oof_k = _out_of_fold(Xk[:, KNOWN_ITER_IDX], cost_known, imp, groups=gtr)
     oof_g = _out_of_fold(Xtr, cost, imp, groups=gtr)
     t_if_known, t_if_gathered = _oof_times(Ctr, oof_k, oof_g)
-    selector = _fit_selector(Xk, KNOWN_ITER_IDX, t_if_known, t_if_gathered + tftr)
+    selector = _fit_selector(Xk, KNOWN_ITER_IDX, t_if_known / ntr, (t_if_gathered + tftr) / ntr)
 
     def report(sel):
         out = {}
