@@ -29,6 +29,10 @@ def edge_cases():
     c.append(G.explicit_lengths([2048, 2047, 2049, 1, 4096, 0, 33, 32, 31], 5000, 13, "chunk-sized rows"))
     c.append(G.explicit_lengths([0, 0, 0, 4097, 0, 2048, 2048, 1, 0, 6143, 2, 2046, 0, 0], 3000, 14, "blocks inside rows"))
     c.append(G.explicit_lengths([2048] * 7 + [1024] * 6 + [4096] * 3 + [0] * 1500, 2500, 15, "rows on block boundaries"))
+    # rows cut into 4 ... 141 chunks / merge tiles: carry runs around the fix-up's boundaries
+    # (partials fetched at once by the run's head; 64 per trip of the head's wave)
+    c.append(G.explicit_lengths([2048 * 4 + 100, 3, 2048 * 5 + 100, 0, 2048 * 6 + 7, 1, 2048 * 68 + 5, 2,
+                                 2048 * 69 + 9, 2048 * 70 + 1, 5, 2048 * 140 + 77, 1], 300_000, 16, "carry runs"))
     return c
 
 
