@@ -177,6 +177,32 @@ def stream_copy_ceiling(nbytes=1 << 31, reps=10):
     return 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def random_gather_ceiling(nnz, cols, reps=10):
+    """Rate of the library's bare gather kernel (streamed indices and values, no rows) with
+    uniformly random indices into a vector of `cols` floats: what a product with random
+    columns and this size of x can reach at most.  Returns gathers per second."""
+    import torch
+
+    import paper_2403_17017_amd as S
+    n = max(4, min(int(nnz), 1 << 27) // 4 * 4)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(99)
+    idx = torch.randint(0, max(int(cols), 1), (n,), generator=gen, device="cuda:0", dtype=torch.int32)
+    val = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    x = torch.ones(max(int(cols), 1), dtype=torch.float32, device="cuda:0")
+    out = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    for _ in range(3):
+        S.seer_gather_sum(idx, val, x, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        S.seer_gather_sum(idx, val, x, out)
+    e1.record()
+    torch.cuda.synchronize()
+    return n * reps / (e0.elapsed_time(e1) * 1e-3)
+
+
 def T_graph(enqueue):
     from paper_2403_17017_amd.training import time_graph_us
     return time_graph_us(enqueue, warmup=10, reps=20)
@@ -414,6 +440,11 @@ def main():
                     "n_products_best_direct_kernel_us": round(n_it * best_direct, 1)}
         del warm
         extras["stream_copy_ceiling_gbps"] = round(stream_copy_ceiling(), 1)
+        # warm, like the ceiling probe (which re-reads one set of buffers)
+        extras["gathers"] = {
+            "x_mb": round(A.cols * 4 / 1e6, 2),
+            "random_gather_ceiling_per_s": round(random_gather_ceiling(A.nnz, A.cols), -6),
+            "selected_kernel_per_s": round(A.nnz / (extras["per_kernel_warm_us"][S.kernel_name(kid)] * 1e-6), -6)}
         if model_meta.get("test_matrices") and args.selector_matrices > 0:
             extras["selector_on_held_out_matrices"] = selector_eval(model, model_meta, args.selector_matrices)
         out["extras"] = extras

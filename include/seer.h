@@ -338,6 +338,13 @@ int seer_stream_copy(void *dst, const void *src, size_t n_words, void *stream);
  * checksum into out64 (DEVICE, 64 uint32 words, caller-zeroed or not): a read-only
  * stream of exactly 4n bytes, the access pattern an SpMV mostly is. */
 int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream);
+/* Measurement aid: sum over k < n (rounded down to a multiple of 4) of val[k] * x[idx[k]],
+ * idx and val (DEVICE, 16-byte aligned) streamed, x (DEVICE) gathered; every idx[k] must
+ * index x.  With uniformly random idx its rate is the ceiling of a product whose columns
+ * are random, for that size of x.  out64: DEVICE, 256 bytes, receives per-wave sums
+ * (meaningless).  Asynchronous. */
+int seer_gather_sum(const int32_t *idx, const float *val, size_t n, const float *x, void *out64,
+                    void *stream);
 
 int seer_num_kernels(void);
 const char *seer_kernel_name(int kernel_id); /* "CSR,TM" ...; NULL if out of range  */

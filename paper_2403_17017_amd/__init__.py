@@ -7,6 +7,6 @@ from .binding import (  # noqa: F401
     NUM_KERNELS, DeviceCSR, Model, Plan, SeerError, Tree,
     alloc_workspace, ell_plan_bytes, features_workspace_bytes, kernel_name, lib, plan_bytes, seer_derive_features, seer_features,
     seer_known_features, seer_select, seer_spmv, seer_spmv_auto, seer_spmv_auto_result, seer_spmv_model,
-    seer_spmv_plan, seer_spmv_prepare, seer_spmv_prepared, seer_csr_check, seer_stream_copy, seer_stream_sum, set_tuning,
+    seer_spmv_plan, seer_spmv_prepare, seer_spmv_prepared, seer_csr_check, seer_gather_sum, seer_stream_copy, seer_stream_sum, set_tuning,
     spmv_auto_workspace_bytes, spmv_prepared_workspace_bytes, spmv_workspace_bytes, strerror,
 )

@@ -134,6 +134,8 @@ def lib():
         L.seer_stream_copy.restype = C.c_int
         L.seer_stream_sum.argtypes = [vp, sz, vp, vp]
         L.seer_stream_sum.restype = C.c_int
+        L.seer_gather_sum.argtypes = [vp, vp, sz, vp, vp, vp]
+        L.seer_gather_sum.restype = C.c_int
         L.seer_num_kernels.restype = C.c_int
         L.seer_kernel_name.argtypes = [C.c_int]
         L.seer_kernel_name.restype = C.c_char_p
@@ -315,6 +317,16 @@ def seer_stream_sum(src, out64, stream=None) -> None:
     rc = lib().seer_stream_sum(src.data_ptr(), src.numel(), out64.data_ptr(), _stream_ptr(stream))
     if rc:
         raise SeerError(rc, "seer_stream_sum")
+
+
+def seer_gather_sum(idx, val, x, out64, stream=None) -> None:
+    """sum val[k] * x[idx[k]] with streamed idx / val (measurement aid: the rate of gathers)."""
+    assert idx.is_contiguous() and val.is_contiguous() and idx.numel() == val.numel()
+    assert idx.element_size() == 4 == val.element_size() and out64.numel() * out64.element_size() >= 256
+    rc = lib().seer_gather_sum(idx.data_ptr(), val.data_ptr(), idx.numel(), x.data_ptr(), out64.data_ptr(),
+                               _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_gather_sum")
 
 
 def spmv_auto_workspace_bytes(rows: int, nnz: int) -> int:

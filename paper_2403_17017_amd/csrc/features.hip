@@ -101,6 +101,44 @@ void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t
                        static_cast<uint32_t *>(out64));
 }
 
+// Gathers with streamed operands (measurement aid): sum of val[k] * x[idx[k]], indices and
+// values fetched as 16-byte vectors with the streaming hint, two vectors in flight per lane
+// -- the inner work of every schedule without any row handling.  With uniformly random
+// indices its rate is the ceiling of a product with random columns for that size of x.
+__global__ __launch_bounds__(kWG) void gather_sum_kernel(
+    const v4i *__restrict__ idx, const v4f *__restrict__ val, size_t n_vec, const float *__restrict__ x,
+    float *__restrict__ out)
+{
+    const size_t stride = (size_t)gridDim.x * kWG;
+    float acc = 0.f;
+    size_t i = (size_t)blockIdx.x * kWG + threadIdx.x;
+    for (; i + stride < n_vec; i += 2 * stride) {
+        const v4i c0 = __builtin_nontemporal_load(idx + i), c1 = __builtin_nontemporal_load(idx + i + stride);
+        const v4f v0 = __builtin_nontemporal_load(val + i), v1 = __builtin_nontemporal_load(val + i + stride);
+        acc += v0.x * x[c0.x] + v0.y * x[c0.y] + v0.z * x[c0.z] + v0.w * x[c0.w];
+        acc += v1.x * x[c1.x] + v1.y * x[c1.y] + v1.z * x[c1.z] + v1.w * x[c1.w];
+    }
+    for (; i < n_vec; i += stride) {
+        const v4i c = idx[i];
+        const v4f v = val[i];
+        acc += v.x * x[c.x] + v.y * x[c.y] + v.z * x[c.z] + v.w * x[c.w];
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    // a plain store keeps the loads alive; which wave's sum survives is irrelevant
+    if (threadIdx.x % kWave == 0) out[(blockIdx.x * (kWG / kWave) + threadIdx.x / kWave) % 64] = acc;
+}
+
+void launch_gather_sum(const int *idx, const float *val, size_t n, const float *x, void *out64, hipStream_t st)
+{
+    const size_t n_vec = n / 4;
+    if (!n_vec) return;
+    const size_t want = (n_vec + kWG * 4 - 1) / (kWG * 4);
+    const uint32_t blocks = (uint32_t)(want < 4096 ? want : 4096);
+    hipLaunchKernelGGL(gather_sum_kernel, dim3(blocks), dim3(kWG), 0, st, reinterpret_cast<const v4i *>(idx),
+                       reinterpret_cast<const v4f *>(val), n_vec, x, static_cast<float *>(out64));
+}
+
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st)
 {
     const size_t n_vec = n_words / 4;

@@ -121,6 +121,7 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, 
 
 void launch_csr_check(int rows, int cols, int nnz, const int *rp, const int *ci, void *counts, hipStream_t st);
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);
+void launch_gather_sum(const int *idx, const float *val, size_t n, const float *x, void *out64, hipStream_t st);
 void launch_stream_sum(const void *src, size_t n_words, void *out64, hipStream_t st);
 
 } // namespace seer

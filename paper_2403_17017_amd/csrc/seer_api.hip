@@ -572,6 +572,15 @@ int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream)
     return e == hipSuccess ? SEER_OK : hip_fail(e);
 }
 
+int seer_gather_sum(const int32_t *idx, const float *val, size_t n, const float *x, void *out64, void *stream)
+{
+    if (n < 4) return SEER_OK;
+    if (!idx || !val || !x || !out64 || !aligned16(idx) || !aligned16(val)) return SEER_EINVAL;
+    launch_gather_sum(idx, val, n, x, out64, static_cast<hipStream_t>(stream));
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
 static int spmv_dispatch(int kernel_id, const seer_csr *A, const float *x, float *y, void *workspace,
                          size_t workspace_bytes, void *stream, int nt);
 
