@@ -71,18 +71,25 @@ int wm_lanes(int rows, int nnz)
 }
 
 // Rows per workgroup for CSR,BM, from measurements over banded / random matrices:
-// short rows want fat blocks (5 K to 8 K nonzeros: fewer blocks, longer streams),
-// rows longer than a wave want about one LDS chunk per block, because those rows are
-// reduced one at a time by their wave.  A small matrix is cut finer (down to about
-// one LDS chunk per block) so that every CU gets at least four blocks.
+// short rows want fat blocks (5 K to 8 K nonzeros: fewer blocks, longer streams).  Rows
+// longer than a wave get 16 per block, the most for which the kernel shares out the lanes
+// among the rows (16 lanes each) -- fewer only where that would put more than 12 K
+// nonzeros into a block (measured best at mean lengths 65 to 500: 16 rows; 1200: 4 to 8;
+// 2000: 8).  A small matrix is cut finer (down to about one LDS chunk per block) so
+// that every CU gets at least four blocks.
 int bm_rows(int rows, int nnz)
 {
     const int t = g_tune_bm_rows.load();
     if (t >= 1 && t <= kBmMaxRows) return t;
     const double mean = rows > 0 ? (double)nnz / (double)rows : 0.0;
-    const double target = mean > 64.0 ? 1536.0 : (mean > 24.0 ? 8192.0 : 5120.0);
     int r = 1;
-    while (r < 1024 && (double)r * mean * 1.41421356 < target) r <<= 1;   // nearest power of two
+    if (mean > 64.0) {
+        r = 16;
+        while (r > 1 && (double)r * mean > 12288.0) r >>= 1;
+    } else {
+        const double target = mean > 24.0 ? 8192.0 : 5120.0;
+        while (r < 1024 && (double)r * mean * 1.41421356 < target) r <<= 1;   // nearest power of two
+    }
     while (r > 1 && rows / r < 1024 && (double)r * mean > 2048.0) r >>= 1;
     return r;
 }

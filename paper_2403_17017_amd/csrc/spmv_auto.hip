@@ -237,8 +237,12 @@ __device__ __forceinline__ void auto_dispatch(
         if (shape.tm_short) tm_body<true>(rows, nnz, rp, ci, va, x, y, tile);
         else tm_body<false>(rows, nnz, rp, ci, va, x, y, tile);
     } else if (k == SEER_CSR_BM) {
-        bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
-                                     reinterpret_cast<float *>(smem));
+        if (shape.bm_rows <= (int)kWoGroupRows)
+            bm_body<kBmChunk, VEC, true, true, false, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift,
+                                                            tile, reinterpret_cast<float *>(smem));
+        else
+            bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
+                                         reinterpret_cast<float *>(smem));
     } else if (k == SEER_CSR_WO) {
         wo_body<kWoChunk, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile,
                                      reinterpret_cast<float *>(smem),
