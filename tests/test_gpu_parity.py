@@ -75,7 +75,7 @@ def test_spmv_parity_default_launch(cases, kid):
 
 @pytest.mark.parametrize("knob,values,kid", [
     ("wm_lanes", [2, 4, 8, 16, 32, 64], 1),
-    ("bm_rows", [1, 3, 64, 100, 1024, 2048], 2),
+    ("bm_rows", [1, 3, 7, 16, 17, 64, 100, 1024, 2048], 2),
     ("bm_chunk", [2048, 4096], 2),
     ("mp_ipt", [7, 15], 3),
 ])
