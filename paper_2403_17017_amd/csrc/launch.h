@@ -23,6 +23,8 @@ struct SpmvArgs {
 };
 
 bool tm_short_rows(int rows, int nnz);
+int tm_rows_per_lane(int rows, int nnz);
+uint32_t tm_num_tiles(int rows, int nnz);
 void launch_tm(const SpmvArgs &a, hipStream_t st);
 void launch_wm(const SpmvArgs &a, int lanes_per_row, hipStream_t st);
 void launch_bm(const SpmvArgs &a, int rows_per_block, int chunk, bool vec, hipStream_t st);
@@ -107,6 +109,7 @@ struct AutoShape {                          // launch shapes, all from rows and 
     uint32_t tiles[SEER_NUM_DIRECT_KERNELS];
     int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
     int tm_short;                           // CSR,TM fetches the first eight entries of a row at once (mean row length <= 8)
+    int tm_pair;                            // ... and takes two rows per lane (tiles of 512 rows)
 };
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
 constexpr size_t kAutoCarryOffset = 32768 + 256;

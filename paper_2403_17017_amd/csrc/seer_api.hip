@@ -463,8 +463,9 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     sh.bm_own_shift = bm_own_shift(sh.bm_rows);
     sh.mp_ipt = mp_ipt(A->rows, A->nnz);
     sh.tm_short = tm_short_rows(A->rows, A->nnz);
+    sh.tm_pair = tm_rows_per_lane(A->rows, A->nnz) == 2;
     const uint32_t rows = (uint32_t)A->rows;
-    sh.tiles[SEER_CSR_TM] = (rows + 255u) / 256u;
+    sh.tiles[SEER_CSR_TM] = tm_num_tiles(A->rows, A->nnz);
     sh.tiles[SEER_CSR_WM] = (rows + (256u / sh.wm_lanes) - 1u) / (256u / sh.wm_lanes);
     sh.tiles[SEER_CSR_BM] = (rows + (uint32_t)sh.bm_rows - 1u) / (uint32_t)sh.bm_rows;
     sh.tiles[SEER_CSR_MP] = mp_num_tiles(A->rows, A->nnz, sh.mp_ipt);

@@ -234,7 +234,8 @@ __device__ __forceinline__ void auto_dispatch(
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
     if (k == SEER_CSR_TM) {
-        if (shape.tm_short) tm_body<true>(rows, nnz, rp, ci, va, x, y, tile);
+        if (shape.tm_pair) tm_body<true, 2>(rows, nnz, rp, ci, va, x, y, tile);
+        else if (shape.tm_short) tm_body<true>(rows, nnz, rp, ci, va, x, y, tile);
         else tm_body<false>(rows, nnz, rp, ci, va, x, y, tile);
     } else if (k == SEER_CSR_BM) {
         if (shape.bm_rows <= (int)kWoGroupRows)

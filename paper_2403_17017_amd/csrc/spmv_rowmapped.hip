@@ -4,7 +4,7 @@
 
 namespace seer {
 
-template <bool SHORT>
+template <bool SHORT, int R = 1>
 __global__ __launch_bounds__(kWG) void spmv_tm_kernel(
     int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
@@ -12,7 +12,7 @@ __global__ __launch_bounds__(kWG) void spmv_tm_kernel(
 {
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
-    tm_body<SHORT>(rows, nnz, rp, ci, va, x, y, tile);
+    tm_body<SHORT, R>(rows, nnz, rp, ci, va, x, y, tile);
 }
 
 template <int G>
@@ -46,15 +46,26 @@ static inline uint32_t grid_for(uint32_t n_tiles, int remap)
 
 bool tm_short_rows(int rows, int nnz) { return (uint64_t)nnz <= 8ull * (uint64_t)rows; }
 
+// Two rows per lane from 2^20 short rows on (4096 tiles of 256 rows: two full generations
+// of workgroups), one otherwise.
+int tm_rows_per_lane(int rows, int nnz) { return tm_short_rows(rows, nnz) && rows >= (1 << 20) ? 2 : 1; }
+
+uint32_t tm_num_tiles(int rows, int nnz)
+{
+    const uint32_t per = kWG * (uint32_t)tm_rows_per_lane(rows, nnz);
+    return ((uint32_t)rows + per - 1) / per;
+}
+
 void launch_tm(const SpmvArgs &a, hipStream_t st)
 {
-    const uint32_t n_tiles = ((uint32_t)a.rows + kWG - 1) / kWG;
-    if (tm_short_rows(a.rows, a.nnz))
-        hipLaunchKernelGGL(spmv_tm_kernel<true>, dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                           a.rows, a.nnz, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap);
-    else
-        hipLaunchKernelGGL(spmv_tm_kernel<false>, dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                           a.rows, a.nnz, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap);
+    const uint32_t n_tiles = tm_num_tiles(a.rows, a.nnz);
+#define SEER_TM_LAUNCH(S, R)                                                                       \
+    hipLaunchKernelGGL((spmv_tm_kernel<S, R>), dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st, \
+                       a.rows, a.nnz, a.rp, a.ci, a.va, a.x, a.y, n_tiles, a.remap)
+    if (!tm_short_rows(a.rows, a.nnz)) SEER_TM_LAUNCH(false, 1);
+    else if (tm_rows_per_lane(a.rows, a.nnz) == 2) SEER_TM_LAUNCH(true, 2);
+    else SEER_TM_LAUNCH(true, 1);
+#undef SEER_TM_LAUNCH
 }
 
 template <int G>
