@@ -65,3 +65,25 @@ def test_config3_zipf_literal_parameters():
     A = G.zipf_rows(s=1.6)
     assert A.nnz > 4e8 and int(np.diff(A.row_ptr).max()) == 200_000
     check_all(A, prepared=(5, 7))
+
+
+@pytest.mark.parametrize("extra", [1, 255, 256, 300, 511])
+def test_thread_mapped_two_rows_per_lane_ragged_tail(extra):
+    """From 2^20 short rows on CSR,TM takes two rows per lane (tiles of 512 rows): a last tile
+    whose second half is partly or wholly beyond the matrix, stand-alone and inside the
+    combined kernel of the asynchronous path."""
+    import torch
+    A = G.random_lengths((1 << 20) + extra, 70_001, 0, 6, seed=600 + extra)
+    x = G.dense_vector(A.cols, 77)
+    y_ref, bound = oracle_of(A, x)
+    dA = upload(A)
+    xd = torch.from_numpy(x).cuda()
+    announce(f"two rows per lane, rows=2^20+{extra}: stand-alone")
+    y = run_spmv(S.CSR_TM, dA, xd, A.rows)
+    assert_parity(y, y_ref, bound, f"CSR,TM on 2^20+{extra} rows")
+    announce(f"two rows per lane, rows=2^20+{extra}: combined kernel")
+    ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+    ya = torch.full((A.rows,), float("nan"), device="cuda:0")
+    S.seer_spmv_auto(dA, S.Tree.constant(S.CSR_TM), xd, ya, ws)
+    assert S.seer_spmv_auto_result(ws)[1] == S.CSR_TM
+    assert np.array_equal(ya.cpu().numpy(), y)
