@@ -407,6 +407,18 @@ def main():
             d, xd, y, ws = rot[i]
             S.seer_features(d, workspace=ws)
         extras["features_call_us"] = round((time.perf_counter() - t0) / 50 * 1e6, 2)
+        # independent steps alternating between two streams (default priority): the short
+        # launches of one step run under the product of the other.  Not the headline: that
+        # one is one stream, one step after the other.
+        lanes = [torch.cuda.Stream(), torch.cuda.Stream()]
+        torch.cuda.synchronize()
+        for rep in range(2):                                  # first round warms the streams
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                d, xd, y, ws = rot[i]
+                S.seer_spmv_auto(d, tree, xd, y, ws, stream=lanes[i & 1])
+            torch.cuda.synchronize()
+            extras["two_streams_us_per_step"] = round((time.perf_counter() - t0) / args.steps * 1e6, 2)
         # the classifier-selection path on this matrix (may skip gathering)
         d, xd, y, ws = rot[0]
         path, k_known = S.seer_spmv_model(d, model, xd, y, ws)
