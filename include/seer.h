@@ -52,7 +52,8 @@ typedef enum {
 
 /* Kernel ids: the CSR rows of Table II ("load balancing schedules"), in its order. */
 enum {
-    SEER_CSR_TM = 0, /* thread mapped: one row per lane                               */
+    SEER_CSR_TM = 0, /* thread mapped: whole rows per lane (one; two from 2^20 short
+                        rows on)                                                      */
     SEER_CSR_WM = 1, /* wavefront mapped: one row per group of 2..64 lanes of a wave  */
     SEER_CSR_BM = 2, /* block mapped: a block of consecutive rows per workgroup,
                         nonzeros staged through LDS                                   */
