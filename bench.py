@@ -284,8 +284,8 @@ def main():
                     help="held-out sweep matrices for the selector figures in extras (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
-                         "described in DESIGN.md but not built")
+        raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); sharding over several GPUs is "
+                         "not built")
 
     import torch
 

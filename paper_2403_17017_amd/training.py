@@ -7,11 +7,11 @@ the classifier-selection model that decides, from the known features alone, whet
 gathering is worth its cost.  The trees are stored as the flat node arrays that
 `seer_select` / `seer_spmv_auto` / `seer_spmv_model` walk.
 
-    python -m paper_2403_17017_amd.training sweep --count 3000 --out gpurun_out/sweep.csv
-    python -m paper_2403_17017_amd.training fit --csv gpurun_out/sweep.csv \
+    python -m paper_2403_17017_amd.training sweep --count 3000 --out sweep.csv
+    python -m paper_2403_17017_amd.training fit --csv sweep.csv \
            --out paper_2403_17017_amd/selector_model.json
-    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv \
-           --model paper_2403_17017_amd/selector_model.json --out gpurun_out/eval.csv
+    python -m paper_2403_17017_amd.training evaluate --csv sweep.csv \
+           --model paper_2403_17017_amd/selector_model.json --out eval.csv
     python -m paper_2403_17017_amd.training export-header      # trees as nested if/else in C
 
 The same sweep also feeds the multiple-iteration models (Sec. V): for every matrix
@@ -761,7 +761,7 @@ def main(argv=None):
     a = sub.add_parser("sweep")
     a.add_argument("--first", type=int, default=0)
     a.add_argument("--count", type=int, default=3000)
-    a.add_argument("--out", default="gpurun_out/sweep.csv")
+    a.add_argument("--out", default="sweep.csv")
     a.add_argument("--nnz-cap", type=int, default=200_000_000)
     a.add_argument("--max-rows-exp", type=float, default=7.0)
     b = sub.add_parser("fit")
@@ -770,7 +770,7 @@ def main(argv=None):
     c = sub.add_parser("evaluate")
     c.add_argument("--csv", required=True)
     c.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
-    c.add_argument("--out", default="gpurun_out/eval.csv")
+    c.add_argument("--out", default="eval.csv")
     d = sub.add_parser("export-header")
     d.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     d.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model_generated.h"))
