@@ -110,6 +110,7 @@ struct AutoShape {                          // launch shapes, all from rows and 
     int wm_lanes, bm_rows, bm_own_shift, mp_ipt;
     int tm_short;                           // CSR,TM fetches the first eight entries of a row at once (mean row length <= 8)
     int tm_pair;                            // ... and takes two rows per lane (tiles of 512 rows)
+    int tm_remap;                           // CSR,TM's tile order: 1 XCD-contiguous, 0 round-robin
 };
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
 constexpr size_t kAutoCarryOffset = 32768 + 256;

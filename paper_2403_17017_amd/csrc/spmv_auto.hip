@@ -231,7 +231,7 @@ __device__ __forceinline__ void auto_dispatch(
         }
         return;
     }
-    const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
+    const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, k == SEER_CSR_TM ? (remap && shape.tm_remap) : remap);
     if (tile >= n_tiles) return;
     if (k == SEER_CSR_TM) {
         if (shape.tm_pair) tm_body<true, 2>(rows, nnz, rp, ci, va, x, y, tile);
