@@ -199,8 +199,10 @@ __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
 static_assert(kFeatMaxParts * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(AutoSel) <= kAutoCarryOffset - kAutoSelOffset,
               "workspace layout");
 
-constexpr int kAutoLds = mp_lds_words<kMpIptLarge>() > bm_lds_words<kBmChunk>() ? mp_lds_words<kMpIptLarge>()
-                                                                                 : bm_lds_words<kBmChunk>();
+constexpr int kAutoLdsMpBm = mp_lds_words<kMpIptLarge>() > bm_lds_words<kBmChunk>() ? mp_lds_words<kMpIptLarge>()
+                                                                                     : bm_lds_words<kBmChunk>();
+constexpr int kAutoLds = kAutoLdsMpBm > bm_lds_words<kWoChunkLarge>() + 2 ? kAutoLdsMpBm
+                                                                           : bm_lds_words<kWoChunkLarge>() + 2;
 static_assert(bm_lds_words<kWoChunk>() + 2 <= kAutoLds, "CSR,WO's products and its two bounds share the overlay");
 
 // This workgroup's share of schedule k (the same k in every workgroup of the grid).
@@ -245,9 +247,14 @@ __device__ __forceinline__ void auto_dispatch(
             bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
                                          reinterpret_cast<float *>(smem));
     } else if (k == SEER_CSR_WO) {
-        wo_body<kWoChunk, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile,
-                                     reinterpret_cast<float *>(smem),
-                                     reinterpret_cast<uint32_t *>(smem) + bm_lds_words<kWoChunk>());
+        if (wo_chunk_of(nnz) == kWoChunkLarge)
+            wo_body<kWoChunkLarge, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile,
+                                              reinterpret_cast<float *>(smem),
+                                              reinterpret_cast<uint32_t *>(smem) + bm_lds_words<kWoChunkLarge>());
+        else
+            wo_body<kWoChunk, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile,
+                                         reinterpret_cast<float *>(smem),
+                                         reinterpret_cast<uint32_t *>(smem) + bm_lds_words<kWoChunk>());
     } else {
         mp_body<IPT, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile, smem);
     }

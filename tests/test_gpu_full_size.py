@@ -87,3 +87,29 @@ def test_thread_mapped_two_rows_per_lane_ragged_tail(extra):
     S.seer_spmv_auto(dA, S.Tree.constant(S.CSR_TM), xd, ya, ws)
     assert S.seer_spmv_auto_result(ws)[1] == S.CSR_TM
     assert np.array_equal(ya.cpu().numpy(), y)
+
+
+def test_work_oriented_large_chunk_ragged():
+    """From 2^23 nonzeros on CSR,WO takes chunks of 4096 nonzeros: a matrix just above that
+    size with a ragged last chunk, empty rows, and rows that run through several chunks,
+    stand-alone and inside the combined kernel."""
+    import torch
+    rng = np.random.default_rng(4096)
+    lens = rng.integers(0, 57, 300_007)
+    lens[rng.choice(lens.size, 40, replace=False)] = rng.integers(3_000, 30_000, 40)
+    lens[1000:1400] = 0
+    A = G.explicit_lengths(lens.tolist(), 90_001, seed=4097, name="just above 2^23 nonzeros")
+    assert A.nnz >= (1 << 23) and A.nnz % 4096 != 0
+    x = G.dense_vector(A.cols, 78)
+    y_ref, bound = oracle_of(A, x)
+    dA = upload(A)
+    xd = torch.from_numpy(x).cuda()
+    announce(f"large chunk, nnz={A.nnz}: stand-alone")
+    y = run_spmv(S.CSR_WO, dA, xd, A.rows)
+    assert_parity(y, y_ref, bound, "CSR,WO with 4096-nonzero chunks")
+    announce(f"large chunk, nnz={A.nnz}: combined kernel")
+    ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+    ya = torch.full((A.rows,), float("nan"), device="cuda:0")
+    S.seer_spmv_auto(dA, S.Tree.constant(S.CSR_WO), xd, ya, ws)
+    assert S.seer_spmv_auto_result(ws)[1] == S.CSR_WO
+    assert np.array_equal(ya.cpu().numpy(), y)
