@@ -237,7 +237,9 @@ def test_plan_argument_errors_and_sizes_without_gpu():
     assert S.plan_bytes(S.CSR_A, 10**6, 10**7) >= 8 * (n_blocks + 1)
     assert S.plan_bytes(S.CSR_A, 10**6, 0) >= 16                                          # one block owns every row
     assert S.spmv_workspace_bytes(S.CSR_A, 10**6, 10**7) >= S.plan_bytes(S.CSR_A, 10**6, 10**7) + 8 * n_blocks
-    assert S.spmv_workspace_bytes(S.CSR_WO, 10**6, 10**7) >= 8 * n_blocks
+    # CSR,WO: one carry pair per chunk; chunks of 2048 nonzeros, of 4096 from 2^23 nonzeros on
+    assert 8 * -(-10**7 // 4096) <= S.spmv_workspace_bytes(S.CSR_WO, 10**6, 10**7) < 8 * n_blocks
+    assert S.spmv_workspace_bytes(S.CSR_WO, 10**6, 2**23 - 1) >= 8 * -(-(2**23 - 1) // 2048)
     assert S.plan_bytes(S.COO_WM, 10**6, 10**7) == 4 * 10**7 + (-4 * 10**7) % 256
     assert S.spmv_workspace_bytes(S.COO_WM, 10**6, 10**7) >= S.plan_bytes(S.COO_WM, 10**6, 10**7) + 8 * -(-10**7 // 512)
     assert S.ell_plan_bytes(1000, 5) == 2 * 1024 * 5 * 4
