@@ -71,3 +71,60 @@ def test_every_kernel_on_random_shapes(block):
         f, kid = S.seer_spmv_auto_result(ws)
         assert kid == O.select(O.features(A.rows, A.cols, A.row_ptr)["f"], *tree.arrays)
         assert_parity(y.cpu().numpy(), y_ref, bound, f"seer_spmv_auto ({S.kernel_name(kid)}) on {A.name}")
+
+
+def large_case(seed):
+    """Sizes at which the launchers switch forms: two rows per lane and the round-robin tile
+    order in CSR,TM (2^20 short rows; 96 MiB), 4096-nonzero chunks in CSR,WO (2^23 nonzeros),
+    the guided first round of its row search (more than 4096 rows)."""
+    rng = np.random.default_rng(9500 + seed)
+    kind = seed % 4
+    if kind == 0:      # short rows, a little over 2^20 of them, ragged last tile
+        rows = (1 << 20) + int(rng.integers(1, 700))
+        lens = rng.integers(0, 7, rows)
+    elif kind == 1:    # short rows, large enough for the round-robin order
+        rows = int(rng.integers(2_600_000, 3_000_000))
+        lens = rng.integers(2, 9, rows)
+    elif kind == 2:    # a little over 2^23 nonzeros, even rows
+        rows = int(rng.integers(250_000, 300_000))
+        lens = rng.integers(25, 40, rows)
+        lens[-1] += max(0, (1 << 23) + int(rng.integers(1, 5000)) - int(lens.sum()))
+    else:              # over 2^23 nonzeros, skewed, with runs of empty rows
+        rows = int(rng.integers(400_000, 500_000))
+        lens = np.minimum(rng.zipf(1.7, rows), 60_000)
+        lens[rng.integers(0, rows, 200)] = rng.integers(2_000, 9_000, 200)
+        lens[5000:9000] = 0
+        lens[-1] += max(0, (1 << 23) + 17 - int(lens.sum()))
+    cols = int(rng.integers(50_000, 400_000))
+    return G.explicit_lengths(np.asarray(lens, dtype=np.int64), cols, 9600 + seed, f"large#{seed}(kind {kind})")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_every_kernel_on_large_random_shapes(seed):
+    import torch
+    A = large_case(seed)
+    x = G.dense_vector(A.cols, 9700 + seed)
+    y_ref, bound = oracle_of(A, x)
+    dA, xd = upload(A), torch.from_numpy(x).cuda()
+    max_len = int(np.diff(A.row_ptr).max())
+    announce(f"{A.name} rows={A.rows} cols={A.cols} nnz={A.nnz} max_len={max_len}")
+    assert_features_equal(S.seer_features(dA), O.features(A.rows, A.cols, A.row_ptr), A.name)
+    assert S.seer_csr_check(dA) == (0, 0)
+    for kid in range(S.NUM_KERNELS):
+        if kid in S.ONE_CALL_KERNELS:
+            y = torch.full((A.rows,), float("nan"), device="cuda:0")
+            S.seer_spmv(kid, dA, xd, y)
+            assert_parity(y.cpu().numpy(), y_ref, bound, f"{S.kernel_name(kid)} on {A.name}")
+        if kid == S.ELL_TM and not 0 < S.ell_plan_bytes(A.rows, max_len) <= (1 << 30):
+            continue
+        plan = S.seer_spmv_prepare(kid, dA)
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_prepared(plan, dA, xd, y)
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"prepared {S.kernel_name(kid)} on {A.name}")
+        del plan
+    ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+    for forced in (S.CSR_TM if seed % 4 < 2 else S.CSR_WM, S.CSR_WO):
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_auto(dA, S.Tree.constant(forced), xd, y, ws)
+        assert S.seer_spmv_auto_result(ws)[1] == forced
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"seer_spmv_auto ({S.kernel_name(forced)}) on {A.name}")
