@@ -107,6 +107,9 @@ def test_work_oriented_large_chunk_ragged():
     announce(f"large chunk, nnz={A.nnz}: stand-alone")
     y = run_spmv(S.CSR_WO, dA, xd, A.rows)
     assert_parity(y, y_ref, bound, "CSR,WO with 4096-nonzero chunks")
+    announce(f"large chunk, nnz={A.nnz}: entry arrays 4 bytes off a 16-byte boundary (lane-strided loads)")
+    y_mis = run_spmv(S.CSR_WO, upload(A, misalign=True), xd, A.rows)
+    assert_parity(y_mis, y_ref, bound, "CSR,WO with 4096-nonzero chunks, misaligned entries")
     announce(f"large chunk, nnz={A.nnz}: combined kernel")
     ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
     ya = torch.full((A.rows,), float("nan"), device="cuda:0")
