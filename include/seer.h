@@ -161,7 +161,7 @@ int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t
 int seer_select(const seer_features_t *f, const seer_tree *tree, int *kernel_id);
 
 /* y = A x with the schedule `kernel_id` (Table II).  x: DEVICE [cols], y: DEVICE
- * [rows], overwritten (no alpha/beta); x and y must not alias.  Every kernel id is
+ * [rows], overwritten (no alpha/beta); x and y must not overlap (SEER_EINVAL).  Every kernel id is
  * valid for every matrix and gives the same y up to fp32 summation order.
  * rows == 0: nothing is written.  Asynchronous on `stream`.
  * workspace: at least seer_spmv_workspace_bytes(kernel_id, rows, nnz) bytes (0 for

@@ -42,6 +42,16 @@ int hip_fail(hipError_t e)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// x [cols] and y [rows] must be disjoint: every schedule reads x while other workgroups
+// already write y.
+bool vectors_overlap(const seer_csr *A, const float *x, const float *y)
+{
+    if (!x || !y) return false;
+    const uintptr_t xb = reinterpret_cast<uintptr_t>(x), xe = xb + 4u * (uintptr_t)A->cols;
+    const uintptr_t yb = reinterpret_cast<uintptr_t>(y), ye = yb + 4u * (uintptr_t)A->rows;
+    return xb < ye && yb < xe;
+}
+
 int check_csr(const seer_csr *A, bool need_entries)
 {
     if (!A) return SEER_EINVAL;
@@ -464,7 +474,7 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     // a cycle is only found by walking; make sure no walk can be longer than the tree
     if (!tree_is_acyclic(tree)) return SEER_ETREE;
     if (A->rows == 0) return SEER_OK;
-    if (!y || (!x && A->nnz > 0)) return SEER_EINVAL;
+    if (!y || (!x && A->nnz > 0) || vectors_overlap(A, x, y)) return SEER_EINVAL;
     if (!workspace || !aligned16(workspace) || workspace_bytes < auto_workspace_bytes(A->rows, A->nnz))
         return SEER_EWORKSPACE;
     AutoTree dt;
@@ -620,7 +630,7 @@ static int spmv_dispatch(int kernel_id, const seer_csr *A, const float *x, float
     const int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     if (A->rows == 0) return SEER_OK;
-    if (!y || (!x && A->nnz > 0)) return SEER_EINVAL;
+    if (!y || (!x && A->nnz > 0) || vectors_overlap(A, x, y)) return SEER_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), nt};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
@@ -774,7 +784,7 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
     if (rc != SEER_OK) return rc;
     if (A->rows != plan->rows || A->nnz != plan->nnz) return SEER_EINVAL;   // a plan belongs to one matrix
     if (A->rows == 0) return SEER_OK;
-    if (!y || (!x && A->nnz > 0) || !plan->device) return SEER_EINVAL;
+    if (!y || (!x && A->nnz > 0) || !plan->device || vectors_overlap(A, x, y)) return SEER_EINVAL;
     if (plan->kernel_id == SEER_COO_WM) {
         if (!workspace || !aligned16(workspace) ||
             workspace_bytes < carry_workspace_bytes(coo_num_intervals(A->rows, A->nnz)))

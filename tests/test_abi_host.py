@@ -193,6 +193,23 @@ def test_spmv_argument_errors_without_gpu():
     assert L.seer_features(C.byref(A0), C.byref(out), None, 0, None) == 0 and out.f[1] == 5.0
 
 
+def test_overlapping_x_and_y_are_rejected_before_any_launch():
+    """x [cols] and y [rows] must be disjoint; the check is pointer arithmetic on the host, so it
+    can be exercised with host buffers standing in for device memory (nothing is launched)."""
+    L = S.lib()
+    ints = (C.c_int32 * 16)()
+    buf = (C.c_float * 64)()
+    base = C.addressof(buf)
+    A = B.seer_csr(8, 8, 4, C.cast(ints, C.c_void_p), C.cast(ints, C.c_void_p), C.cast(buf, C.c_void_p))
+    vp = C.c_void_p
+    for kid in (S.CSR_TM, S.CSR_WM, S.CSR_BM):                      # no workspace needed before the check
+        assert L.seer_spmv(kid, C.byref(A), vp(base), vp(base), None, 0, None) == -1            # the same vector
+        assert L.seer_spmv(kid, C.byref(A), vp(base), vp(base + 4 * 7), None, 0, None) == -1    # y starts on x's last entry
+        assert L.seer_spmv(kid, C.byref(A), vp(base + 4 * 7), vp(base), None, 0, None) == -1    # x starts on y's last entry
+    t = S.Tree.constant(S.CSR_TM)
+    assert L.seer_spmv_auto(C.byref(A), C.byref(t.c), vp(base), vp(base + 16), None, 0, None) == -1
+
+
 def test_workspace_sizes():
     assert S.spmv_workspace_bytes(0, 10**6, 10**7) == 0
     assert S.spmv_workspace_bytes(2, 10**6, 10**7) == 0
