@@ -314,8 +314,9 @@ int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx
  *   "xcd_remap" 1: consecutive tiles stay on one XCD (default), 0: round-robin
  *   "nt"        1: the matrix streams are loaded with the non-temporal hint, 0: plain
  *               loads.  Default: 1 in seer_spmv / seer_spmv_auto; in seer_spmv_prepared
- *               (repeated products) 1 only if the matrix exceeds 192 MiB, so that a
- *               smaller one stays in the last-level cache between products
+ *               (repeated products) 1 only if what the kernel reads and writes exceeds
+ *               288 MiB (last-level cache + L2), so that a smaller matrix stays cached
+ *               between products
  *   "vec"       0: CSR,BM / CSR,MP / CSR,WO / CSR,A take entries with lane-strided 4-byte
  *               loads instead of 16-byte loads (what matrices whose col_idx / values
  *               are not 16-byte aligned get anyway); default 1

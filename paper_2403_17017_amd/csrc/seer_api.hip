@@ -151,17 +151,24 @@ int use_nt()
     return t < 0 ? 1 : (t != 0);
 }
 
-// Products from a prepared plan are repeated with the same matrix.  If the matrix fits the
-// 256 MB last-level cache next to x and y, streaming it with the non-temporal hint gives up
-// the reuse between products (measured on an 8 M-row, 250 MB matrix: 135 us per product with
-// plain loads against 148-158 us); beyond that size the hint keeps x in L2 (a 872 MB matrix:
-// 165 us against 184 us).
-int use_nt_repeated(const seer_csr *A)
+// Products from a prepared plan are repeated with the same matrix.  If what a product reads
+// and writes fits the caches (256 MB last-level cache + 8 x 4 MB L2), streaming it with the
+// non-temporal hint gives up the reuse between products; beyond that size the hint keeps x
+// in L2.  Measured, repeated products, plain against hinted loads: 212-218 MB (stencil, band,
+// random columns) plain faster by 4 to 19 %; an 8 M-row 250 MB matrix 135 against 148-158 us;
+// 325 MB stencil hinted faster by 10 % in the CSR kernels while ELL,TM, whose own arrays
+// there come to 300 MB, is faster plain by 24 %; 424 MB and more hinted faster by 5 to 16 %.
+// `footprint` is the byte count of the arrays the kernel reads and writes.
+int use_nt_repeated(uint64_t footprint)
 {
     const int t = g_tune_nt.load();
     if (t >= 0) return t != 0;
-    const uint64_t bytes = 8ull * (uint64_t)A->nnz + 8ull * (uint64_t)A->rows + 4ull * (uint64_t)A->cols;
-    return bytes > (192ull << 20);
+    return footprint > (288ull << 20);
+}
+
+uint64_t csr_footprint(const seer_csr *A)
+{
+    return 8ull * (uint64_t)A->nnz + 8ull * (uint64_t)A->rows + 4ull * (uint64_t)A->cols;
 }
 
 int ensure_mailbox()
@@ -779,7 +786,7 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
     if (!plan) return SEER_EINVAL;
     if (plan->kernel_id != SEER_CSR_A && plan->kernel_id != SEER_ELL_TM && plan->kernel_id != SEER_COO_WM)
         return spmv_dispatch(plan->kernel_id, A, x, y, workspace, workspace_bytes, stream,
-                             A ? use_nt_repeated(A) : use_nt());
+                             A ? use_nt_repeated(csr_footprint(A)) : use_nt());
     const int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     if (A->rows != plan->rows || A->nnz != plan->nnz) return SEER_EINVAL;   // a plan belongs to one matrix
@@ -789,13 +796,15 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
         if (!workspace || !aligned16(workspace) ||
             workspace_bytes < carry_workspace_bytes(coo_num_intervals(A->rows, A->nnz)))
             return SEER_EWORKSPACE;
-        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt_repeated(A)};
+        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
+                   use_nt_repeated(csr_footprint(A) + 4ull * (uint64_t)A->nnz)};
         launch_coo(a, plan->device, workspace, static_cast<hipStream_t>(stream));
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SEER_OK : hip_fail(e);
     }
     if (plan->kernel_id == SEER_ELL_TM) {
-        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt_repeated(A)};
+        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
+                   use_nt_repeated((uint64_t)plan->device_bytes + 4ull * ((uint64_t)A->rows + (uint64_t)A->cols))};
         launch_ell(a, plan->ell_width, plan->device, static_cast<hipStream_t>(stream));
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SEER_OK : hip_fail(e);
@@ -807,7 +816,8 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
             return SEER_EWORKSPACE;
         carry = workspace;
     }
-    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), use_nt_repeated(A)};
+    SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
+               use_nt_repeated(csr_footprint(A))};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
     launch_adaptive(a, vec, plan->device, carry, static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
