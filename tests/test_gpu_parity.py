@@ -98,6 +98,24 @@ def test_spmv_parity_every_launch_shape(cases, knob, values, kid):
 
 
 @pytest.mark.parametrize("kid", KERNELS)
+def test_spmv_parity_tile_orders_and_load_hints(cases, kid):
+    """Every kernel under the round-robin tile order and with plain instead of streaming
+    loads (the defaults are the XCD-contiguous order and the streaming hint)."""
+    import torch
+    try:
+        for remap, nt in ((0, 0), (0, 1), (1, 0)):
+            S.set_tuning("xcd_remap", remap)
+            S.set_tuning("nt", nt)
+            for A, x, y_ref, bound in cases:
+                announce(f"spmv kernel={kid} remap={remap} nt={nt}, {A.name}")
+                y = run_spmv(kid, upload(A), torch.from_numpy(x).cuda(), A.rows)
+                assert_parity(y, y_ref, bound, f"kernel {kid} remap={remap} nt={nt} on {A.name}")
+    finally:
+        S.set_tuning("xcd_remap", -1)
+        S.set_tuning("nt", -1)
+
+
+@pytest.mark.parametrize("kid", KERNELS)
 def test_spmv_misaligned_entries(cases, kid):
     import torch
     for A, x, y_ref, bound in cases:
