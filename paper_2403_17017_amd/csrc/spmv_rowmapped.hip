@@ -44,7 +44,7 @@ static inline uint32_t grid_for(uint32_t n_tiles, int remap)
     return remap ? tiles_per_xcd(n_tiles) * kXCD : n_tiles;
 }
 
-bool tm_short_rows(int rows, int nnz) { return (uint64_t)nnz <= 8ull * (uint64_t)rows; }
+bool tm_short_rows(int rows, int nnz) { return nnz >= 8 && (uint64_t)nnz <= 8ull * (uint64_t)rows; }
 
 // Two rows per lane from 2^20 short rows on (4096 tiles of 256 rows: two full generations
 // of workgroups), one otherwise.
