@@ -116,3 +116,48 @@ def test_work_oriented_large_chunk_ragged():
     S.seer_spmv_auto(dA, S.Tree.constant(S.CSR_WO), xd, ya, ws)
     assert S.seer_spmv_auto_result(ws)[1] == S.CSR_WO
     assert np.array_equal(ya.cpu().numpy(), y)
+
+
+@pytest.mark.timeout(1500)
+def test_nnz_at_the_int32_limit():
+    """The largest matrix the boundary accepts: nnz = 2^31 - 1 (the last value an int32
+    offset can hold), 2 M rows of about a thousand entries, a tenth of them empty, one row
+    of 5.5 M entries.  Every offset computation in the kernels must survive positions next
+    to 2^31.  Values and x are small integers, so every row whose sum|a||x| stays below 2^24
+    has to come out exactly, whatever order a schedule adds in; the one long row is held to
+    the usual tolerance."""
+    import torch
+    announce("int32 limit: generating 16 GiB of entries on the host")
+    A = G.int32_limit()
+    assert A.nnz == 2**31 - 1
+    x = np.random.default_rng(G.BASE_SEED + 32).integers(-4, 5, A.cols).astype(np.float32)
+    announce("int32 limit: oracle")
+    y_ref, bound = oracle_of(A, x)
+    exact = bound < 2.0**24
+    assert int(exact.sum()) >= A.rows - 1
+    want = O.features(A.rows, A.cols, A.row_ptr)
+    announce("int32 limit: upload")
+    dA = upload(A)
+    xd = torch.from_numpy(x).cuda()
+
+    announce("int32 limit: input check and features")
+    assert S.seer_csr_check(dA) == (0, 0)
+    assert_features_equal(S.seer_features(dA), want, A.name)
+    assert S.ell_plan_bytes(A.rows, int(want["max_len"])) == 0        # the padded form would not fit int32 either
+
+    ys = {}
+    for kid in (S.CSR_TM, S.CSR_WM, S.CSR_BM, S.CSR_MP, S.CSR_WO, S.CSR_A, S.COO_WM):
+        announce(f"int32 limit: kernel {kid} ({S.kernel_name(kid)})")
+        y = run_spmv(kid, dA, xd, A.rows)
+        assert_parity(y, y_ref, bound, f"kernel {kid} at nnz = 2^31 - 1")
+        assert np.array_equal(y[exact], y_ref[exact].astype(np.float32)), f"kernel {kid}: integer rows not exact"
+        ys[kid] = y
+
+    for kid in (S.CSR_MP, S.CSR_WO):
+        announce(f"int32 limit: combined kernel answering {S.kernel_name(kid)}")
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        ya = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_auto(dA, S.Tree.constant(kid), xd, ya, ws)
+        f_dev, kid_dev = S.seer_spmv_auto_result(ws)
+        assert kid_dev == kid and f_dev.vector().tobytes() == want["f"].tobytes()
+        assert np.array_equal(ya.cpu().numpy(), ys[kid])

@@ -214,6 +214,38 @@ def small_integer_values(A: HostCSR, seed: int, lo: int = -4, hi: int = 4) -> Ho
     return HostCSR(A.rows, A.cols, A.row_ptr, A.col_idx, v, A.name + "_intvals")
 
 
+def int32_limit(rows: int = 2_097_155, cols: int = 1 << 20, long_row: int = 5_000_000,
+                seed: int = BASE_SEED + 31) -> HostCSR:
+    """The largest matrix int32 offsets can express: exactly 2^31 - 1 nonzeros (16 GiB of
+    entries).  Row lengths: uniform on 0..2047, every tenth row emptied, one row of
+    ``long_row`` entries in the middle, all scaled down and topped up one by one to hit the
+    total.  One block of ``_BLOCK`` columns (uniform, NOT ascending inside a row, unlike the
+    other generators) and integer values in [-8, 7] is drawn and laid down 64 times, the
+    columns shifted by 9973 per repetition (mod ``cols``) and the values rotated by 977
+    entries per repetition, so that a matrix of this size is made in seconds."""
+    target = (1 << 31) - 1
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(0, 2048, rows).astype(np.int64)
+    lens[::10] = 0
+    lens[rows // 2] = long_row
+    lens = lens * target // int(lens.sum())
+    short = target - int(lens.sum())                  # < rows: lost to the roundings
+    assert 0 <= short < rows
+    lens[np.flatnonzero(lens > 0)[:short]] += 1
+    row_ptr = _row_ptr_from_lengths(lens)
+    assert int(row_ptr[-1]) == target
+    block_c = rng.integers(0, cols, _BLOCK, dtype=np.int32)
+    block_v = rng.integers(-8, 8, _BLOCK).astype(np.float32)
+    col_idx = np.empty(target, dtype=np.int32)
+    values = np.empty(target, dtype=np.float32)
+    for t, lo in enumerate(range(0, target, _BLOCK)):
+        n = min(_BLOCK, target - lo)
+        np.add(block_c[:n], np.int32((t * 9973) % cols), out=col_idx[lo:lo + n])
+        col_idx[lo:lo + n] %= np.int32(cols)
+        values[lo:lo + n] = np.roll(block_v, 977 * t)[:n]
+    return HostCSR(rows, cols, row_ptr, col_idx, values, f"int32_limit_{rows}x{cols}")
+
+
 def model_bytes(rows: int, cols: int, nnz: int) -> int:
     """Bytes an SpMV has to move at least: 8 per nonzero (column + value),
     4 per row_ptr entry, 4 per x entry, 4 per y entry."""
