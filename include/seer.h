@@ -325,6 +325,8 @@ int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx
  *               in one launch, and the selection runs inside the product's launch
  *               whenever that launch has at most auto_fused_grid workgroups (default
  *               1024; 0: always a selection launch of its own)
+ *   "coo_runs"  COO,WM: 1 (default): a lane sums a run of eight consecutive triples,
+ *               0: lane <-> triple in rounds of 64
  *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise
  *               (default) it first watches its pinned result word for up to 2 ms
  * Unknown name: SEER_EINVAL.  A value outside the listed set selects the default. */

@@ -60,7 +60,8 @@ void launch_ell(const SpmvArgs &a, int width, const void *plan_mem, hipStream_t 
 uint32_t coo_num_intervals(int rows, int nnz);
 size_t coo_plan_bytes(int rows, int nnz);
 void launch_coo_convert(int rows, const int *rp, void *plan_mem, hipStream_t st);
-void launch_coo(const SpmvArgs &a, const void *plan_mem, void *carry_ws, hipStream_t st);
+void launch_coo(const SpmvArgs &a, bool runs /* lane-owned runs of triples (the default form) */, const void *plan_mem,
+                void *carry_ws, hipStream_t st);
 
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory

@@ -28,6 +28,7 @@ std::atomic<int> g_tune_remap{-1};
 std::atomic<int> g_tune_nt{-1};
 std::atomic<int> g_tune_vec{-1};
 std::atomic<int> g_tune_poll{-1};
+std::atomic<int> g_tune_coo_runs{-1};
 
 std::mutex g_mailbox_mutex;
 FeatureRaw *g_mailbox_host = nullptr;   // pinned, mapped
@@ -102,6 +103,13 @@ int bm_rows(int rows, int nnz)
     }
     while (r > 1 && rows / r < 1024 && (double)r * mean > 2048.0) r >>= 1;
     return r;
+}
+
+// COO,WM sums an interval by lane-owned runs of triples unless the tuning knob asks for the
+// rounds of 64.
+bool coo_runs()
+{
+    return g_tune_coo_runs.load() != 0;
 }
 
 int bm_chunk()
@@ -338,6 +346,7 @@ int seer_set_tuning(const char *name, int value)
     else if (!std::strcmp(name, "nt")) g_tune_nt.store(value);
     else if (!std::strcmp(name, "vec")) g_tune_vec.store(value);
     else if (!std::strcmp(name, "poll")) g_tune_poll.store(value);
+    else if (!std::strcmp(name, "coo_runs")) g_tune_coo_runs.store(value);
     else return SEER_EINVAL;
     return SEER_OK;
 }
@@ -666,7 +675,7 @@ static int spmv_dispatch(int kernel_id, const seer_csr *A, const float *x, float
             return SEER_EWORKSPACE;
         void *plan_mem = static_cast<char *>(workspace) + carry;
         launch_coo_convert(A->rows, A->row_ptr, plan_mem, st);
-        launch_coo(a, plan_mem, workspace, st);
+        launch_coo(a, coo_runs(), plan_mem, workspace, st);
         break;
     }
     case SEER_CSR_WO:
@@ -798,7 +807,7 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
             return SEER_EWORKSPACE;
         SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
                    use_nt_repeated(csr_footprint(A) + 4ull * (uint64_t)A->nnz)};
-        launch_coo(a, plan->device, workspace, static_cast<hipStream_t>(stream));
+        launch_coo(a, coo_runs(), plan->device, workspace, static_cast<hipStream_t>(stream));
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SEER_OK : hip_fail(e);
     }

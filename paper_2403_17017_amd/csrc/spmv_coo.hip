@@ -9,7 +9,7 @@ __global__ __launch_bounds__(kWG) void coo_convert_kernel(int rows, const int *_
     coo_convert_body(rows, rp, crow);
 }
 
-template <bool NT>
+template <bool NT, bool RUNS>
 __global__ __launch_bounds__(kWG) void spmv_coo_kernel(
     int rows, int nnz, const int *__restrict__ crow, const int *__restrict__ ci, const float *__restrict__ va,
     const float *__restrict__ x, float *__restrict__ y, int *__restrict__ carry_row,
@@ -19,7 +19,8 @@ __global__ __launch_bounds__(kWG) void spmv_coo_kernel(
     if (tile >= n_tiles) return;
     const uint32_t w = tile * (kWG / kWave) + threadIdx.x / kWave;
     if (w >= n_intervals) return;                    // whole waves leave; the body has no barrier
-    coo_body<NT>(rows, nnz, crow, ci, va, x, y, carry_row, carry_val, w);
+    if constexpr (RUNS) coo_runs_body<NT>(rows, nnz, crow, ci, va, x, y, carry_row, carry_val, w);
+    else coo_rounds_body<NT>(rows, nnz, crow, ci, va, x, y, carry_row, carry_val, w);
 }
 
 uint32_t coo_num_intervals(int rows, int nnz)
@@ -43,7 +44,7 @@ void launch_coo_convert(int rows, const int *rp, void *plan_mem, hipStream_t st)
                        static_cast<int *>(plan_mem));
 }
 
-void launch_coo(const SpmvArgs &a, const void *plan_mem, void *carry_ws, hipStream_t st)
+void launch_coo(const SpmvArgs &a, bool runs, const void *plan_mem, void *carry_ws, hipStream_t st)
 {
     const uint32_t n_int = coo_num_intervals(a.rows, a.nnz);
     if (n_int == 0) return;
@@ -53,12 +54,15 @@ void launch_coo(const SpmvArgs &a, const void *plan_mem, void *carry_ws, hipStre
     float *carry_val = reinterpret_cast<float *>(static_cast<char *>(carry_ws) + one);
     const int *crow = static_cast<const int *>(plan_mem);
     const dim3 grid(a.remap ? tiles_per_xcd(n_tiles) * kXCD : n_tiles);
-    if (a.nt)
-        hipLaunchKernelGGL(spmv_coo_kernel<true>, grid, dim3(kWG), 0, st, a.rows, a.nnz, crow, a.ci, a.va, a.x, a.y,
-                           carry_row, carry_val, n_tiles, n_int, a.remap);
-    else
-        hipLaunchKernelGGL(spmv_coo_kernel<false>, grid, dim3(kWG), 0, st, a.rows, a.nnz, crow, a.ci, a.va, a.x, a.y,
-                           carry_row, carry_val, n_tiles, n_int, a.remap);
+#define SEER_COO_LAUNCH(N, R)                                                                              \
+    hipLaunchKernelGGL((spmv_coo_kernel<N, R>), grid, dim3(kWG), 0, st, a.rows, a.nnz, crow, a.ci, a.va, a.x, a.y, \
+                       carry_row, carry_val, n_tiles, n_int, a.remap)
+    if (runs) {
+        if (a.nt) SEER_COO_LAUNCH(true, true); else SEER_COO_LAUNCH(false, true);
+    } else {
+        if (a.nt) SEER_COO_LAUNCH(true, false); else SEER_COO_LAUNCH(false, false);
+    }
+#undef SEER_COO_LAUNCH
     launch_carry_fixup(a.rows, n_int, carry_row, carry_val, a.y, st);
 }
 

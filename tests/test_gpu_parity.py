@@ -115,6 +115,32 @@ def test_spmv_parity_tile_orders_and_load_hints(cases, kid):
         S.set_tuning("nt", -1)
 
 
+@pytest.mark.parametrize("runs", [0, 1])
+def test_coo_both_forms_on_every_case(cases, runs):
+    """COO,WM sums an interval in one of two ways (a tuning switch picks); each
+    forced onto every case, also with entry arrays off a 16-byte boundary, and with integer
+    data, where the two forms and the oracle must agree to the bit."""
+    import torch
+    try:
+        S.set_tuning("coo_runs", runs)
+        for A, x, y_ref, bound in cases:
+            for mis in (False, True):
+                if mis and A.nnz == 0:
+                    continue
+                announce(f"COO,WM runs={runs} misaligned={mis}, {A.name}")
+                y = run_spmv(S.COO_WM, upload(A, misalign=mis), torch.from_numpy(x).cuda(), A.rows)
+                assert_parity(y, y_ref, bound, f"COO,WM runs={runs} misaligned={mis} on {A.name}")
+            Ai = G.small_integer_values(A, seed=91)
+            xi = np.random.default_rng(92).integers(-3, 4, A.cols).astype(np.float32)
+            yi_ref, bi = oracle_of(Ai, xi)
+            if A.nnz and float(bi.max()) >= 2.0**24:
+                continue
+            yi = run_spmv(S.COO_WM, upload(Ai), torch.from_numpy(xi).cuda(), A.rows)
+            assert np.array_equal(yi, yi_ref.astype(np.float32)), f"COO,WM runs={runs}: integer data not exact on {A.name}"
+    finally:
+        S.set_tuning("coo_runs", -1)
+
+
 @pytest.mark.parametrize("kid", KERNELS)
 def test_spmv_misaligned_entries(cases, kid):
     import torch
