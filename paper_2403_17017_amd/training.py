@@ -554,10 +554,10 @@ def fit_tree(csv_path, out_json, test_frac=0.2, seed=0):
     return t
 
 
-def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
-    """Runs the held-out matrices again and times, end to end on the GPU timeline (HIP
-    graph replay): every fixed kernel, the always-gather path (seer_spmv_auto) and the
-    classifier-selection path (seer_spmv_model)."""
+def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr, matrices=None):
+    """Runs the held-out matrices again (or `matrices`, e.g. sweep numbers no fit has seen)
+    and times, end to end on the GPU timeline (HIP graph replay): every fixed kernel, the
+    always-gather path (seer_spmv_auto) and the classifier-selection path (seer_spmv_model)."""
     import torch
 
     from workloads.sweep_gen import build_on_device, sweep_spec
@@ -567,7 +567,7 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr):
     with open(out_csv, "w", newline="") as fh:
         w = csv.DictWriter(fh, fieldnames=fields)
         w.writeheader()
-        for m in meta["test_matrices"]:
+        for m in (meta["test_matrices"] if matrices is None else matrices):
             spec = sweep_spec(m)
             rp, ci, va, x = build_on_device(spec)
             dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
@@ -614,7 +614,7 @@ def summarize_evaluation(eval_csv):
     }
 
 
-def write_report_md(csv_path, model_json, eval_csv, out_md):
+def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None):
     """Human-readable summary of a sweep, the fit and the held-out evaluation."""
     rows, X, T, tf = load_csv(csv_path)
     P = load_prep(rows)
@@ -653,25 +653,37 @@ def write_report_md(csv_path, model_json, eval_csv, out_md):
              f"gathered on {100 * t['gathered_fraction']:.0f} % of matrices; aggregate speed-up over the best fixed "
              f"kernel ({names[t['best_fixed_kernel']]}) {t['aggregate_speedup_vs_best_fixed']['classifier_selection']:.3f}, "
              f"per-matrix geomean {t['per_matrix_geomean_vs_best_fixed']['classifier_selection']:.3f}")
-    if eval_csv and os.path.exists(eval_csv):
-        e = summarize_evaluation(eval_csv)
+    def evaluation_section(path, title, whom):
+        e = summarize_evaluation(path)
         best = names[e["best_fixed_kernel"]]
-        L += ["", f"## Held-out evaluation, every path re-measured end to end on the GPU timeline ({e['matrices']} matrices)", "",
-              f"| path | total us | vs best fixed kernel ({best}) | per-matrix geomean vs {best} | vs oracle (best kernel per matrix) |",
-              "|---|---|---|---|---|"]
+        out = ["", f"## {title} ({e['matrices']} matrices)", "",
+               f"| path | total us | vs best fixed kernel ({best}) | per-matrix geomean vs {best} | vs oracle (best kernel per matrix) |",
+               "|---|---|---|---|---|"]
         tb = e["t_fixed_us"][e["best_fixed_kernel"]]
         for k in range(ND):
-            L.append(f"| fixed {names[k]} | {e['t_fixed_us'][k]:.0f} | {tb / e['t_fixed_us'][k]:.3f} | | "
-                     f"{e['t_fixed_us'][k] / e['t_oracle_us']:.3f} |")
+            out.append(f"| fixed {names[k]} | {e['t_fixed_us'][k]:.0f} | {tb / e['t_fixed_us'][k]:.3f} | | "
+                       f"{e['t_fixed_us'][k] / e['t_oracle_us']:.3f} |")
         for key, label in (("always_gather", "always gather (seer_spmv_auto)"),
                            ("classifier_selection", "classifier selection (seer_spmv_model)")):
             tot = e["t_always_gather_us"] if key == "always_gather" else e["t_classifier_selection_us"]
-            L.append(f"| {label} | {tot:.0f} | {e['aggregate_speedup_vs_best_fixed'][key]:.3f} | "
-                     f"{e['per_matrix_geomean_vs_best_fixed'][key]:.3f} | {e['time_lost_vs_oracle'][key]:.3f} |")
-        L.append(f"| oracle | {e['t_oracle_us']:.0f} | {tb / e['t_oracle_us']:.3f} | | 1.000 |")
-        L += ["", f"Geomean over the fixed kernels of (kernel total / classifier-selection total): "
-              f"{e['geomean_over_fixed_kernels_of_aggregate_speedup']:.2f}x.  Features gathered on "
-              f"{100 * e['gathered_fraction']:.0f} % of the held-out matrices."]
+            out.append(f"| {label} | {tot:.0f} | {e['aggregate_speedup_vs_best_fixed'][key]:.3f} | "
+                       f"{e['per_matrix_geomean_vs_best_fixed'][key]:.3f} | {e['time_lost_vs_oracle'][key]:.3f} |")
+        out.append(f"| oracle | {e['t_oracle_us']:.0f} | {tb / e['t_oracle_us']:.3f} | | 1.000 |")
+        out += ["", f"Geomean over the fixed kernels of (kernel total / classifier-selection total): "
+                f"{e['geomean_over_fixed_kernels_of_aggregate_speedup']:.2f}x.  Features gathered on "
+                f"{100 * e['gathered_fraction']:.0f} % of {whom}."]
+        return out
+
+    if eval_csv and os.path.exists(eval_csv):
+        L += evaluation_section(eval_csv, "Held-out evaluation, every path re-measured end to end on the GPU timeline",
+                                "the held-out matrices")
+    if fresh_csv and os.path.exists(fresh_csv):
+        with open(fresh_csv) as fh:
+            ms = [int(r["m"]) for r in csv.DictReader(fh)]
+        L += evaluation_section(fresh_csv, f"The same models on sweep numbers {min(ms)} to {max(ms)}, which no sweep or fit "
+                                "has seen, re-measured end to end", "these matrices")
+        L += ["", f"    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv --model "
+              f"paper_2403_17017_amd/selector_model.json --first {min(ms)} --count {len(ms)} --out gpurun_out/eval_fresh.csv"]
     if "iterative" in m:
         it = m["iterative"]["report"]["test"]
         L += ["", "## Models for n products with one matrix (Sec. V), held-out matrices, from sweep timings", "",
@@ -771,6 +783,9 @@ def main(argv=None):
     c.add_argument("--csv", required=True)
     c.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     c.add_argument("--out", default="eval.csv")
+    c.add_argument("--first", type=int, default=None, help="with --count: evaluate on these sweep numbers instead "
+                   "of the model's held-out ones (numbers beyond the fitted sweep are matrices no fit has seen)")
+    c.add_argument("--count", type=int, default=0)
     d = sub.add_parser("export-header")
     d.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     d.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model_generated.h"))
@@ -778,10 +793,11 @@ def main(argv=None):
     e.add_argument("--csv", required=True)
     e.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     e.add_argument("--eval", default=None)
+    e.add_argument("--fresh-eval", default=None, help="evaluate --first/--count output on unseen sweep numbers")
     e.add_argument("--out", required=True)
     args = ap.parse_args(argv)
     if args.cmd == "report-md":
-        print(write_report_md(args.csv, args.model, args.eval, args.out))
+        print(write_report_md(args.csv, args.model, args.eval, args.out, args.fresh_eval))
         return
     if args.cmd == "export-header":
         print(export_header(args.model, args.out))
@@ -792,7 +808,8 @@ def main(argv=None):
         m = fit_model(args.csv, args.out)
         print(json.dumps(m["report"], indent=1))
     else:
-        print(json.dumps(evaluate_model(args.csv, args.model, args.out), indent=1))
+        fresh = None if args.first is None else list(range(args.first, args.first + args.count))
+        print(json.dumps(evaluate_model(args.csv, args.model, args.out, matrices=fresh), indent=1))
 
 
 if __name__ == "__main__":
