@@ -9,6 +9,7 @@
 namespace seer {
 
 constexpr int kBmMaxRows = 2048;  // most rows one CSR,BM workgroup owns (8 per lane, bounds in registers)
+constexpr int kAutoBmMaxRows = 1024;   // ... inside the combined kernel (4 per lane: keeps it at eight waves per SIMD)
 constexpr int kBmChunk = 2048;    // products staged in LDS per CSR,BM pass (4096 is the other choice)
 constexpr int kMpIptSmall = 7;    // merge items per thread, small problems (tile = 1792 items)
 constexpr int kMpIptLarge = 15;   // merge items per thread, large problems (tile = 3840 items)

@@ -499,7 +499,7 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     std::memcpy(dt.nodes, tree->nodes, sizeof(seer_node) * (size_t)tree->n_nodes);
     AutoShape sh;
     sh.wm_lanes = wm_lanes(A->rows, A->nnz);
-    sh.bm_rows = bm_rows(A->rows, A->nnz);
+    sh.bm_rows = std::min(bm_rows(A->rows, A->nnz), kAutoBmMaxRows);   // (more only through the tuning knob)
     sh.bm_own_shift = bm_own_shift(sh.bm_rows);
     sh.mp_ipt = mp_ipt(A->rows, A->nnz);
     sh.tm_short = tm_short_rows(A->rows, A->nnz);

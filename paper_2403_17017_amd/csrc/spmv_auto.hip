@@ -241,11 +241,11 @@ __device__ __forceinline__ void auto_dispatch(
         else tm_body<false>(rows, nnz, rp, ci, va, x, y, tile);
     } else if (k == SEER_CSR_BM) {
         if (shape.bm_rows <= (int)kWoGroupRows)
-            bm_body<kBmChunk, VEC, true, true, false, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift,
-                                                            tile, reinterpret_cast<float *>(smem));
-        else
-            bm_body<kBmChunk, VEC, true>(rows, rp, ci, va, x, y, shape.bm_rows, shape.bm_own_shift, tile,
-                                         reinterpret_cast<float *>(smem));
+            bm_body<kBmChunk, VEC, true, true, false, true, 256>(rows, rp, ci, va, x, y, shape.bm_rows,
+                                                                 shape.bm_own_shift, tile, reinterpret_cast<float *>(smem));
+        else   // (the host keeps bm_rows within kAutoBmMaxRows here)
+            bm_body<kBmChunk, VEC, true, true, false, false, kAutoBmMaxRows>(rows, rp, ci, va, x, y, shape.bm_rows,
+                                                                             shape.bm_own_shift, tile, reinterpret_cast<float *>(smem));
     } else if (k == SEER_CSR_WO) {
         if (wo_chunk_of(nnz) == kWoChunkLarge)
             wo_body<kWoChunkLarge, VEC, true>(rows, nnz, rp, ci, va, x, y, carry_row, carry_val, tile,

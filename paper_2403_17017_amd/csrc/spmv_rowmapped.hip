@@ -26,7 +26,7 @@ __global__ __launch_bounds__(kWG) void spmv_wm_kernel(
     wm_body<G>(rows, rp, ci, va, x, y, tile);
 }
 
-template <int CH, bool VEC, bool NT, bool GRP = false, bool PIPE = true, bool PAD = false>
+template <int CH, bool VEC, bool NT, bool GRP = false, int MAXR = kBmMaxRows, bool PIPE = true, bool PAD = false>
 __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     int rows, const int *__restrict__ rp, const int *__restrict__ ci,
     const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kWG) void spmv_bm_kernel(
     __shared__ __attribute__((aligned(16))) float s_prod[bm_lds_words<CH>()];
     const uint32_t tile = tile_of_block(blockIdx.x, n_tiles, remap);
     if (tile >= n_tiles) return;
-    bm_body<CH, VEC, NT, PIPE, PAD, GRP>(rows, rp, ci, va, x, y, rows_per_block, own_shift, tile, s_prod);
+    bm_body<CH, VEC, NT, PIPE, PAD, GRP, MAXR>(rows, rp, ci, va, x, y, rows_per_block, own_shift, tile, s_prod);
 }
 
 // ------------------------------------------------------------------ launchers
@@ -94,12 +94,14 @@ static void launch_bm_v(const SpmvArgs &a, int rows_per_block, hipStream_t st)
 {
     const uint32_t n_tiles = ((uint32_t)a.rows + rows_per_block - 1) / (uint32_t)rows_per_block;
     const int own_shift = bm_own_shift(rows_per_block);
-    if (rows_per_block <= (int)kWoGroupRows)     // long rows: several lanes per row
-        hipLaunchKernelGGL((spmv_bm_kernel<CH, VEC, NT, true>), dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                           a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, own_shift, n_tiles, a.remap);
-    else
-        hipLaunchKernelGGL((spmv_bm_kernel<CH, VEC, NT, false>), dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st,
-                           a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, own_shift, n_tiles, a.remap);
+#define SEER_BM_LAUNCH(G, M)                                                                              \
+    hipLaunchKernelGGL((spmv_bm_kernel<CH, VEC, NT, G, M>), dim3(grid_for(n_tiles, a.remap)), dim3(kWG), 0, st, \
+                       a.rows, a.rp, a.ci, a.va, a.x, a.y, rows_per_block, own_shift, n_tiles, a.remap)
+    if (rows_per_block <= (int)kWoGroupRows) SEER_BM_LAUNCH(true, 256);   // long rows: several lanes per row
+    else if (rows_per_block <= 256) SEER_BM_LAUNCH(false, 256);           // else the smallest instance that fits
+    else if (rows_per_block <= 1024) SEER_BM_LAUNCH(false, 1024);
+    else SEER_BM_LAUNCH(false, kBmMaxRows);
+#undef SEER_BM_LAUNCH
 }
 
 template <int CH>
