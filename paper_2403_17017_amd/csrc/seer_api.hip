@@ -4,6 +4,7 @@
 #include "../../include/seer.h"
 #include "launch.h"
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 #include <cstdlib>
