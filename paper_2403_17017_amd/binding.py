@@ -457,7 +457,11 @@ def seer_spmv_plan(A: DeviceCSR, model: Model, iterations: int, plan_mem=None, w
     """Selection for `iterations` products, then the chosen kernel's preprocessing.
     Returns (plan, path): path 0 = known model, 1 = features were gathered."""
     if plan_mem is None:
-        plan_mem = alloc_workspace(plan_bytes(CSR_A, A.rows, A.nnz), A.row_ptr.device)
+        # room for any kernel's plan: CSR,A's blocks, COO,WM's row indices (4 bytes per nonzero),
+        # and the ELL arrays as long as padding adds at most half to the 8 bytes per nonzero
+        # (beyond that the call prepares CSR,A instead, as the C header says)
+        need = max(plan_bytes(CSR_A, A.rows, A.nnz), plan_bytes(COO_WM, A.rows, A.nnz), 12 * A.nnz + (1 << 20))
+        plan_mem = alloc_workspace(need, A.row_ptr.device)
     if workspace is None:
         workspace = alloc_workspace(features_workspace_bytes(A.rows), A.row_ptr.device)
     cs = A.c_struct()

@@ -323,7 +323,7 @@ def neighbour_costs(X, cost, groups=None, k=KNOWN_NEIGHBOURS):
     return c[ind].mean(axis=1).reshape(cost.shape)
 
 
-def _cart(Xs, cost, importance):
+def _cart(Xs, cost, importance, leaves=None):
     """CART on a cost matrix instead of hard labels: sample m is entered once per class k
     with weight importance[m] * (worst cost of m - cost[m, k]), so that the class a leaf
     votes for is the one with the least total cost over the leaf's matrices (the standard
@@ -336,13 +336,16 @@ def _cart(Xs, cost, importance):
     keep = w > 0
     if not np.any(keep):                      # every choice costs the same everywhere
         keep, w = ye == 0, np.ones_like(w)
-    return DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0).fit(
-        Xe[keep], ye[keep], sample_weight=w[keep])
+    if leaves is None:
+        clf = DecisionTreeClassifier(criterion="gini", max_depth=MAX_DEPTH, random_state=0)
+    else:                                     # a number of leaves instead of a depth: grown best split first
+        clf = DecisionTreeClassifier(criterion="gini", max_leaf_nodes=leaves, random_state=0)
+    return clf.fit(Xe[keep], ye[keep], sample_weight=w[keep])
 
 
-def _fit(X, cost, importance, cols=None):
+def _fit(X, cost, importance, cols=None, leaves=None):
     Xs = X if cols is None else X[:, cols]
-    clf = _cart(Xs, cost, importance)
+    clf = _cart(Xs, cost, importance, leaves)
     tree = tree_to_arrays(clf)
     if cols is not None:   # the stored tree indexes the full feature vector
         tree["feature"] = [cols[f] if f >= 0 else -1 for f in tree["feature"]]
@@ -353,7 +356,7 @@ def _fit(X, cost, importance, cols=None):
 OOF_REPEATS = 3
 
 
-def _out_of_fold(Xs, cost, importance, groups=None, folds=5, repeats=OOF_REPEATS):
+def _out_of_fold(Xs, cost, importance, groups=None, folds=5, repeats=OOF_REPEATS, leaves=None):
     """Predictions for every sample by trees that were fitted without it (and without any
     sample of the same group): [samples, repeats], one column per random 5-fold split."""
     g = np.arange(len(Xs)) if groups is None else np.asarray(groups)
@@ -364,8 +367,32 @@ def _out_of_fold(Xs, cost, importance, groups=None, folds=5, repeats=OOF_REPEATS
         f = np.array([fold_of[v] for v in g.tolist()])
         for k in range(folds):
             a, b = f != k, f == k
-            out[b, r] = _cart(Xs[a], cost[a], importance[a]).predict(Xs[b])
+            out[b, r] = _cart(Xs[a], cost[a], importance[a], leaves).predict(Xs[b])
     return out
+
+
+ITER_LEAVES = (64, 128, 256, 512)   # 64 leaves is what MAX_DEPTH allows; 512 leaves = 1023 nodes, 20 KB
+
+
+def _pick_leaves(Xs, cost, importance, groups, candidates=None):
+    """Size of a tree of the iterative models, by cross-validation inside the training set (5
+    folds split by matrix): the number of leaves, grown best split first, whose out-of-fold
+    choices cost least, in the costs the tree is fitted to.  The test matrices play no part.
+    These trees have the iteration count to split on besides the matrix features and eight
+    kernels to tell apart, and they are walked on the host, so the device-side walk's 127
+    nodes do not bind them.  (On the sweep: 512 leaves for both trees; held-out, against
+    depth 6, 100 products 1.028 -> 1.039 of the best fixed kernel and 1.9 -> 0.8 % above the
+    per-matrix best, a preprocessing kernel chosen on 15 % of the matrices instead of 2 %;
+    one to three products 0.3 to 0.6 % worse.)"""
+    candidates = ITER_LEAVES if candidates is None else candidates
+    best, best_cost, seen = candidates[0], None, {}
+    i = np.arange(len(Xs))
+    for n_leaves in candidates:
+        oof = _out_of_fold(Xs, cost, importance, groups=groups, repeats=1, leaves=n_leaves)[:, 0]
+        seen[n_leaves] = float((cost[i, oof] * importance).sum())
+        if best_cost is None or seen[n_leaves] < best_cost:
+            best, best_cost = n_leaves, seen[n_leaves]
+    return best, seen
 
 
 def _oof_times(T, oof_known, oof_gathered):
@@ -520,11 +547,13 @@ def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
     # costs per product: with totals, the samples at 100 products would outweigh those at one
     # product a hundred to one and the trees would be fitted to the long runs alone
     cost, imp = choice_costs(Ctr / ntr[:, None])
-    gathered = _fit(Xtr, cost, imp)
+    leaves_g, cv_g = _pick_leaves(Xtr, cost, imp, gtr)
+    gathered = _fit(Xtr, cost, imp, leaves=leaves_g)
     cost_known = neighbour_costs(Xk, cost, groups=len(grid))
-    known = _fit(Xk, cost_known, imp, KNOWN_ITER_IDX)
-    oof_k = _out_of_fold(Xk[:, KNOWN_ITER_IDX], cost_known, imp, groups=gtr)
-    oof_g = _out_of_fold(Xtr, cost, imp, groups=gtr)
+    leaves_k, cv_k = _pick_leaves(Xk[:, KNOWN_ITER_IDX], cost_known, imp, gtr)
+    known = _fit(Xk, cost_known, imp, KNOWN_ITER_IDX, leaves=leaves_k)
+    oof_k = _out_of_fold(Xk[:, KNOWN_ITER_IDX], cost_known, imp, groups=gtr, leaves=leaves_k)
+    oof_g = _out_of_fold(Xtr, cost, imp, groups=gtr, leaves=leaves_g)
     t_if_known, t_if_gathered = _oof_times(Ctr, oof_k, oof_g)
     selector = _fit_selector(Xk, KNOWN_ITER_IDX, t_if_known / ntr, (t_if_gathered + tftr) / ntr)
 
@@ -542,6 +571,7 @@ def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
 
     return {"gathered": gathered, "known": known, "selector": selector, "iterations_grid": list(grid),
             "known_features": KNOWN_ITER_IDX,
+            "leaves": {"gathered": leaves_g, "known": leaves_k, "cross_validation_cost": {"gathered": cv_g, "known": cv_k}},
             "label_counts": np.bincount(ytr, minlength=S.NUM_KERNELS).tolist(),
             "report": {"train": report(tr), "test": report(te)}}
 
