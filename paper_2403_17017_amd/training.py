@@ -112,8 +112,9 @@ def time_features_us(dA, ws, warmup=3, reps=10):
     return (time.perf_counter() - t0) / reps * 1e6, f
 
 
-def measure_matrix(spec, device="cuda:0"):
-    """One CSV row for sweep matrix `spec` (see workloads.sweep_gen)."""
+def measure_matrix(spec, device="cuda:0", extra=None):
+    """One CSV row for sweep matrix `spec` (see workloads.sweep_gen).  extra(dA, x, y, ws, row):
+    further measurements on the same buffers, added to the row."""
     import torch
 
     from workloads.sweep_gen import build_on_device
@@ -161,6 +162,8 @@ def measure_matrix(spec, device="cuda:0"):
     scale = float(ys[3].abs().max().item()) + 1e-30
     row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item()
                                         for k in range(S.NUM_KERNELS) if k != 3) / scale)
+    if extra is not None:
+        extra(dA, x, ys[0], ws, row)
     return row
 
 
@@ -620,6 +623,69 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr, matrices=None)
     return summarize_evaluation(out_csv)
 
 
+ITER_EVAL_COUNTS = (1, 5, 19, 50, 100)
+
+
+def evaluate_iterative(model_json, out_csv, counts=ITER_EVAL_COUNTS, matrices=None, log=sys.stderr):
+    """The models for n products with one matrix, end to end on the held-out matrices (or
+    `matrices`): every kernel's preprocessing call and product are timed again as in the sweep,
+    and for each n the call a user makes -- seer_spmv_plan (wall clock: classifier selection,
+    feature collection where asked for, the chosen kernel's preprocessing) -- and the product
+    from the plan it returns (HIP graph replay).  Cost of a path for n products = its call +
+    n * its product."""
+    from workloads.sweep_gen import sweep_spec
+    model, meta = load_model(model_json, iterative=True)
+    fields = CSV_FIELDS + [f"{what}_n{n}" for n in counts for what in ("t_plan_us", "t_product_us", "kernel", "path")]
+
+    def plan_path(dA, x, y, ws, row):
+        plan_mem = S.alloc_workspace(max(S.plan_bytes(S.CSR_A, dA.rows, dA.nnz), S.plan_bytes(S.COO_WM, dA.rows, dA.nnz),
+                                         min(12 * dA.nnz + (1 << 20), ELL_MAX_BYTES)))
+        for n in counts:
+            for _ in range(2):
+                plan, path = S.seer_spmv_plan(dA, model, n, plan_mem, ws)
+            t0 = time.perf_counter()
+            for _ in range(5):
+                plan, path = S.seer_spmv_plan(dA, model, n, plan_mem, ws)
+            row[f"t_plan_us_n{n}"] = round((time.perf_counter() - t0) / 5 * 1e6, 3)
+            row[f"t_product_us_n{n}"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws), warmup=10), 3)
+            row[f"kernel_n{n}"], row[f"path_n{n}"] = plan.kernel_id, path
+
+    with open(out_csv, "w", newline="") as fh:
+        w = csv.DictWriter(fh, fieldnames=fields)
+        w.writeheader()
+        for m in (meta["test_matrices"] if matrices is None else matrices):
+            row = measure_matrix(sweep_spec(m), extra=plan_path)
+            w.writerow(row)
+            fh.flush()
+            print(f"[eval-it] m={m} {row['family']} nnz={row['nnz']} " +
+                  " ".join(f"n{n}:k{row[f'kernel_n{n}']}/p{row[f'path_n{n}']}" for n in counts), file=log, flush=True)
+    return summarize_iterative_evaluation(out_csv, counts)
+
+
+def summarize_iterative_evaluation(eval_csv, counts=ITER_EVAL_COUNTS):
+    rows, X, T, tf = load_csv(eval_csv)
+    P = load_prep(rows)
+    geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
+    out = {"matrices": len(rows)}
+    for n in counts:
+        C = P + n * T
+        tm = np.array([float(r[f"t_plan_us_n{n}"]) + n * float(r[f"t_product_us_n{n}"]) for r in rows])
+        chosen = np.array([int(r[f"kernel_n{n}"]) for r in rows])
+        t_fixed = C.sum(axis=0)
+        best = int(np.argmin(t_fixed))
+        out[str(n)] = {
+            "best_fixed_kernel": best, "t_best_fixed_us": float(t_fixed[best]), "t_oracle_us": float(C.min(axis=1).sum()),
+            "t_classifier_selection_us": float(tm.sum()),
+            "aggregate_speedup_vs_best_fixed": float(t_fixed[best] / tm.sum()),
+            "per_matrix_geomean_vs_best_fixed": geo(C[:, best], tm),
+            "time_lost_vs_oracle": float(tm.sum() / C.min(axis=1).sum()),
+            "gathered_fraction": float(np.mean([int(r[f"path_n{n}"]) for r in rows])),
+            "preprocessing_chosen_fraction": float(np.mean(np.isin(chosen, PREP_KERNELS))),
+            "preprocessing_best_fraction": float(np.mean(np.isin(C.argmin(axis=1), PREP_KERNELS))),
+        }
+    return out
+
+
 def summarize_evaluation(eval_csv):
     with open(eval_csv) as fh:
         rows = list(csv.DictReader(fh))
@@ -644,7 +710,7 @@ def summarize_evaluation(eval_csv):
     }
 
 
-def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None):
+def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter_csv=None):
     """Human-readable summary of a sweep, the fit and the held-out evaluation."""
     rows, X, T, tf = load_csv(csv_path)
     P = load_prep(rows)
@@ -727,6 +793,30 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None):
                      f"{r['per_matrix_geomean_vs_best_fixed']:.3f} | {r['time_lost_vs_oracle']:.3f} | "
                      f"{100 * r['gathered_fraction']:.0f} % | {100 * r['preprocessing_chosen_fraction']:.0f} % / "
                      f"{100 * r['preprocessing_best_fraction']:.0f} % | {100 * r['amortisation_accuracy']:.0f} % |")
+    if iter_csv and os.path.exists(iter_csv):
+        e = summarize_iterative_evaluation(iter_csv)
+        with open(iter_csv) as fh:
+            rr = list(csv.DictReader(fh))
+        tp = lambda n, p: [float(r[f"t_plan_us_n{n}"]) for r in rr if int(r[f"path_n{n}"]) == p]
+        L += ["", f"## The same models measured end to end ({e['matrices']} held-out matrices)", "",
+              "    python -m paper_2403_17017_amd.training evaluate-iterative --model paper_2403_17017_amd/selector_model.json "
+              "--out gpurun_out/eval_iterative.csv", "",
+              "Every kernel's preprocessing call and product timed again as in the sweep; the model's path = the "
+              "seer_spmv_plan call as a user makes it through the Python binding (wall clock: selection, feature "
+              "collection where asked for, preprocessing of the chosen kernel) + n * the product from the plan it "
+              "returns (HIP graph replay).  The fixed kernels and the oracle are charged no call at all for kernels "
+              "without preprocessing, so at n = 1 the path's own call decides the small matrices: it costs "
+              f"{np.median(tp(1, 0)):.1f} us (median) on the known path, interpreter and ctypes included, and "
+              f"{np.median(tp(19, 1)):.1f} us when it gathers.", "",
+              "| n | best fixed kernel | classifier selection vs best fixed (aggregate) | per-matrix geomean | vs oracle | "
+              "gathered on | preprocessing kernel chosen / truly best |",
+              "|---|---|---|---|---|---|---|"]
+        for n in ITER_EVAL_COUNTS:
+            r = e[str(n)]
+            L.append(f"| {n} | {names[r['best_fixed_kernel']]} | {r['aggregate_speedup_vs_best_fixed']:.3f} | "
+                     f"{r['per_matrix_geomean_vs_best_fixed']:.3f} | {r['time_lost_vs_oracle']:.3f} | "
+                     f"{100 * r['gathered_fraction']:.0f} % | {100 * r['preprocessing_chosen_fraction']:.0f} % / "
+                     f"{100 * r['preprocessing_best_fraction']:.0f} % |")
     with open(out_md, "w") as fh:
         fh.write("\n".join(L) + "\n")
     return out_md
@@ -816,6 +906,11 @@ def main(argv=None):
     c.add_argument("--first", type=int, default=None, help="with --count: evaluate on these sweep numbers instead "
                    "of the model's held-out ones (numbers beyond the fitted sweep are matrices no fit has seen)")
     c.add_argument("--count", type=int, default=0)
+    ci = sub.add_parser("evaluate-iterative")
+    ci.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
+    ci.add_argument("--out", default="eval_iterative.csv")
+    ci.add_argument("--first", type=int, default=None)
+    ci.add_argument("--count", type=int, default=0)
     d = sub.add_parser("export-header")
     d.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     d.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model_generated.h"))
@@ -824,10 +919,11 @@ def main(argv=None):
     e.add_argument("--model", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
     e.add_argument("--eval", default=None)
     e.add_argument("--fresh-eval", default=None, help="evaluate --first/--count output on unseen sweep numbers")
+    e.add_argument("--iterative-eval", default=None, help="evaluate-iterative output")
     e.add_argument("--out", required=True)
     args = ap.parse_args(argv)
     if args.cmd == "report-md":
-        print(write_report_md(args.csv, args.model, args.eval, args.out, args.fresh_eval))
+        print(write_report_md(args.csv, args.model, args.eval, args.out, args.fresh_eval, args.iterative_eval))
         return
     if args.cmd == "export-header":
         print(export_header(args.model, args.out))
@@ -837,6 +933,9 @@ def main(argv=None):
     elif args.cmd == "fit":
         m = fit_model(args.csv, args.out)
         print(json.dumps(m["report"], indent=1))
+    elif args.cmd == "evaluate-iterative":
+        fresh = None if args.first is None else list(range(args.first, args.first + args.count))
+        print(json.dumps(evaluate_iterative(args.model, args.out, matrices=fresh), indent=1))
     else:
         fresh = None if args.first is None else list(range(args.first, args.first + args.count))
         print(json.dumps(evaluate_model(args.csv, args.model, args.out, matrices=fresh), indent=1))
