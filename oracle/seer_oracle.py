@@ -8,7 +8,9 @@ What it defines
   * spmv        -- y = A x by the inner-product definition (Sec. IV, Table II:
                    every schedule computes the same SpMV), fp64, via the C row
                    loop in spmv_oracle.c; spmv_python is the same loop in Python
-                   for tiny inputs.
+                   for tiny inputs.  spmv_all_cores is the same row loop with the rows
+                   shared among the host threads (spmv_oracle_omp.c): a timed baseline
+                   only, pinned bit for bit to the single-thread loop.
   * features    -- the statistics gathered from the CSR offsets (Sec. IV and
                    IV-A: max / min / variance / mean of the row density, where a
                    row's density is its nonzero count over the number of columns;
@@ -84,6 +86,36 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
         subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-o", _SO, src, "-lm"])
     return _SO
+
+
+_SO_OMP = os.path.join(_HERE, "liboracle_omp.so")
+_lib_omp = None
+
+
+def build_all_cores(force: bool = False) -> str:
+    """Compile spmv_oracle_omp.c (the same row loop, rows shared among the host threads)."""
+    src = os.path.join(_HERE, "spmv_oracle_omp.c")
+    if force or not os.path.exists(_SO_OMP) or os.path.getmtime(_SO_OMP) < os.path.getmtime(src):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _SO_OMP, src])
+    return _SO_OMP
+
+
+def spmv_all_cores(rows, row_ptr, col_idx, values, x):
+    """The row loop of O1 on all host threads: a timed baseline, never the value checked
+    against.  Returns (y fp64 [rows], threads used)."""
+    global _lib_omp
+    _check_csr(rows, row_ptr, col_idx, values, x)
+    if _lib_omp is None:
+        build_all_cores()
+        lib = ctypes.CDLL(_SO_OMP)
+        p = ctypes.c_void_p
+        lib.oracle_spmv_f64_all_cores.argtypes = [ctypes.c_int64, p, p, p, p, p]
+        lib.oracle_spmv_f64_all_cores.restype = ctypes.c_int
+        _lib_omp = lib
+    y = np.empty(rows, dtype=np.float64)
+    ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    threads = _lib_omp.oracle_spmv_f64_all_cores(rows, ptr(row_ptr), ptr(col_idx), ptr(values), ptr(x), ptr(y))
+    return y, int(threads)
 
 
 def _load():

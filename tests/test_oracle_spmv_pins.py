@@ -188,3 +188,13 @@ def test_nonnegative_inputs_bound_equals_value():
     x = np.abs(G.dense_vector(A.cols, 62))
     y, b = O.spmv(A.rows, A.row_ptr, A.col_idx, A.values, x)
     assert np.array_equal(y, b)
+
+
+def test_all_cores_copy_of_the_row_loop_equals_the_single_thread_loop():
+    """The OpenMP copy of the row loop (timed as a CPU baseline, never checked against) sums
+    every row in the same order as the single-thread loop: bit-identical results."""
+    A = G.zipf_rows(30_011, s=1.5, cap=4000, seed=41)
+    x = G.dense_vector(A.cols, 42)
+    y, _ = O.spmv(A.rows, A.row_ptr, A.col_idx, A.values, x, want_bound=False)
+    y_all, threads = O.spmv_all_cores(A.rows, A.row_ptr, A.col_idx, A.values, x)
+    assert threads >= 1 and y_all.tobytes() == y.tobytes()
