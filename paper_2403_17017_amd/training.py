@@ -533,9 +533,6 @@ def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
     """The three trees for n products with one matrix (Sec. V): every training matrix
     appears once per iteration count of the grid, labelled with the kernel of least
     preprocessing + n * run time among all kernels; folds are split by matrix."""
-    from sklearn.model_selection import GroupKFold, cross_val_predict
-    from sklearn.tree import DecisionTreeClassifier
-
     def expand(sel):
         Xe = np.repeat(X[sel], len(grid), axis=0)
         n = np.tile(np.array(grid, dtype=np.float64), len(sel))

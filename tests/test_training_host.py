@@ -20,7 +20,6 @@ def test_sweep_specs_are_deterministic_and_capped():
 
 
 def test_build_gives_valid_sorted_csr():
-    import torch
     for m in range(12):
         spec = W.sweep_spec(m, nnz_cap=300_000, max_rows_exp=4.5)
         rp, ci, va, x = W.build_on_device(spec, "cpu")
