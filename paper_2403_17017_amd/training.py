@@ -765,6 +765,20 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
         out += ["", f"Geomean over the fixed kernels of (kernel total / classifier-selection total): "
                 f"{e['geomean_over_fixed_kernels_of_aggregate_speedup']:.2f}x.  Features gathered on "
                 f"{100 * e['gathered_fraction']:.0f} % of {whom}."]
+        # by family: where the classifier-selection path gains on the best fixed kernel and where it loses
+        with open(path) as fh:
+            rr = list(csv.DictReader(fh))
+        Tk = np.array([[float(r[f"t_k{k}_us"]) for k in range(ND)] for r in rr])
+        tm = np.array([float(r["t_model_us"]) for r in rr])
+        fam = np.array([r["family"] for r in rr])
+        b = e["best_fixed_kernel"]
+        out += ["", f"| family | matrices | {best} total us | classifier selection total us | oracle total us | "
+                f"per-matrix geomean vs {best} | per-matrix geomean above oracle |", "|---|---|---|---|---|---|---|"]
+        for f in list(dict.fromkeys(fam)):
+            s_ = fam == f
+            out.append(f"| {f} | {int(s_.sum())} | {Tk[s_, b].sum():.0f} | {tm[s_].sum():.0f} | {Tk[s_].min(axis=1).sum():.0f} | "
+                       f"{np.exp(np.mean(np.log(Tk[s_, b] / tm[s_]))):.3f} | "
+                       f"{np.exp(np.mean(np.log(tm[s_] / Tk[s_].min(axis=1)))):.3f} |")
         return out
 
     if eval_csv and os.path.exists(eval_csv):
