@@ -308,7 +308,7 @@ int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx
 /* Launch-shape overrides for experiments; the defaults (value < 0) derive every
  * launch shape from rows and nnz alone (the trivially known sizes of Sec. III-A).
  *   "wm_lanes"  lanes per row of CSR,WM: 2, 4, 8, 16, 32 or 64
- *   "bm_rows"   rows per workgroup of CSR,BM: 1..2048
+ *   "bm_rows"   rows per workgroup of CSR,BM: 1..2048 (seer_spmv_auto takes at most 1024)
  *   "bm_chunk"  products staged in LDS per pass of CSR,BM: 2048 or 4096
  *   "mp_ipt"    merge items per lane of CSR,MP: 7 or 15
  *   "xcd_remap" 1: consecutive tiles stay on one XCD (default), 0: round-robin
