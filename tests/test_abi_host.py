@@ -276,3 +276,71 @@ def test_trees_for_the_single_product_paths_must_name_direct_kernels():
         never_gather = S.Tree([-1], [0.0], [-1], [-1], [0], n_classes=2)
         model = S.Model(S.Tree.constant(S.CSR_BM), t, never_gather)
         assert L.seer_spmv_model(C.byref(A), C.byref(model.c), None, None, None, 0, None, None, None) == -3
+
+
+C_CLIENT = r"""
+#include "seer.h"
+#include <stdio.h>
+#include <string.h>
+
+/* every entry point of the header, by address: the prototypes are plain C */
+typedef void (*any_fn)(void);
+static const any_fn entry_points[] = {
+    (any_fn)seer_features, (any_fn)seer_features_workspace_bytes, (any_fn)seer_derive_features,
+    (any_fn)seer_known_features, (any_fn)seer_select, (any_fn)seer_spmv, (any_fn)seer_spmv_workspace_bytes,
+    (any_fn)seer_spmv_auto, (any_fn)seer_spmv_auto_workspace_bytes, (any_fn)seer_spmv_model,
+    (any_fn)seer_spmv_auto_result, (any_fn)seer_plan_bytes, (any_fn)seer_ell_plan_bytes, (any_fn)seer_spmv_prepare,
+    (any_fn)seer_spmv_prepared, (any_fn)seer_spmv_prepared_workspace_bytes, (any_fn)seer_spmv_plan,
+    (any_fn)seer_csr_check, (any_fn)seer_set_tuning, (any_fn)seer_stream_copy, (any_fn)seer_stream_sum,
+    (any_fn)seer_gather_sum, (any_fn)seer_num_kernels, (any_fn)seer_kernel_name, (any_fn)seer_strerror,
+    (any_fn)seer_last_hip_error};
+
+int main(void)
+{
+    seer_features_t f;
+    seer_node nodes[3] = {{SEER_F_MEAN_LEN, 1, 2, -1, 8.0}, {-1, -1, -1, SEER_CSR_TM, 0.0}, {-1, -1, -1, SEER_CSR_WO, 0.0}};
+    seer_tree tree = {3, SEER_NUM_FEATURES, SEER_NUM_KERNELS, nodes};
+    int kid = -1, rc, i;
+    for (i = 0; i < (int)(sizeof entry_points / sizeof entry_points[0]); ++i)
+        if (!entry_points[i]) return 2;
+    memset(&f, 0, sizeof f);
+    f.rows = 4; f.cols = 20; f.nnz = 20; f.max_len = 5; f.min_len = 5; f.empty_rows = 0; f.sum_sq_len = 100;
+    rc = seer_derive_features(&f);                      /* four rows of 5 nonzeros in 20 columns */
+    printf("derive %d mean %.6f density %.6f var %.6f\n", rc, f.f[SEER_F_MEAN_LEN], f.f[SEER_F_MEAN_DENSITY], f.f[SEER_F_VAR_LEN]);
+    rc = seer_select(&f, &tree, &kid);
+    printf("select %d kernel %d %s\n", rc, kid, seer_kernel_name(kid));
+    f.f[SEER_F_MEAN_LEN] = 9.0f;
+    rc = seer_select(&f, &tree, &kid);
+    printf("select %d kernel %d %s\n", rc, kid, seer_kernel_name(kid));
+    printf("kernels %d workspace %lu error \"%s\"\n", seer_num_kernels(),
+           (unsigned long)seer_spmv_workspace_bytes(SEER_CSR_TM, 1000, 5000), seer_strerror(SEER_ETREE));
+    printf("null matrix %d\n", seer_spmv(SEER_CSR_TM, NULL, NULL, NULL, NULL, 0, NULL));
+    return 0;
+}
+"""
+
+
+def test_plain_c_client_compiles_against_the_header_and_runs(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit that includes only seer.h compiles
+    without warnings, links against the library and gets the host-side answers (no GPU call).
+    The density is the one of the paper's worked example (Sec. IV-A): 5 nonzeros in a row of
+    20 columns -> 0.25."""
+    import subprocess
+    from paper_2403_17017_amd import binding
+    S.lib()                                              # make sure the library is built
+    src = tmp_path / "client.c"
+    src.write_text(C_CLIENT)
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    include = os.path.join(os.path.dirname(libdir), "include")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", include, "-o", str(exe),
+                           str(src), binding.LIB_PATH, f"-Wl,-rpath,{libdir}", "-Wl,-rpath-link,/opt/rocm/lib",
+                           "-Wl,--allow-shlib-undefined"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr
+    lines = out.stdout.strip().splitlines()
+    assert lines[0] == "derive 0 mean 5.000000 density 0.250000 var 0.000000"
+    assert lines[1] == "select 0 kernel 0 CSR,TM"
+    assert lines[2] == "select 0 kernel 4 CSR,WO"
+    assert lines[3] == 'kernels 8 workspace 0 error "%s"' % S.strerror(-3)
+    assert lines[4] == "null matrix -1"
