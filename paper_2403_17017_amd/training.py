@@ -716,12 +716,13 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
     names = [S.kernel_name(k) for k in range(S.NUM_KERNELS)]
     L = ["# Selector: sweep, training and held-out evaluation (MI355X)", "",
          "Commands (GPU box, repository root):", "",
-         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 3000 --out gpurun_out/sweep.csv",
-         "    python -m paper_2403_17017_amd.training fit --csv gpurun_out/sweep.csv --out gpurun_out/selector_model.json",
-         "    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv "
-         "--model gpurun_out/selector_model.json --out gpurun_out/eval.csv",
-         "    python -m paper_2403_17017_amd.training report-md --csv gpurun_out/sweep.csv "
-         "--model gpurun_out/selector_model.json --eval gpurun_out/eval.csv --out profiles/selector_evaluation.md", "",
+         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 3000 --out sweep.csv",
+         "    python -m paper_2403_17017_amd.training fit --csv sweep.csv --out selector_model.json",
+         "    python -m paper_2403_17017_amd.training evaluate --csv sweep.csv "
+         "--model selector_model.json --out eval.csv",
+         "    python -m paper_2403_17017_amd.training report-md --csv sweep.csv "
+         "--model selector_model.json --eval eval.csv" + (" --fresh-eval eval_fresh.csv" if fresh_csv else "") +
+         (" --iterative-eval eval_iterative.csv" if iter_csv else "") + " --out profiles/selector_evaluation.md", "",
          f"Population: {len(rows)} seeded synthetic matrices (workloads/sweep_gen.py), timing 10 warm-up + 10 timed "
          "runs per kernel, HIP-graph replay, same buffers (warm).  CSR,A and ELL,TM are timed with a prepared plan; "
          "their preprocessing calls are timed apart (host wall clock, they wait for the device).  Where the ELL "
@@ -789,8 +790,8 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
             ms = [int(r["m"]) for r in csv.DictReader(fh)]
         L += evaluation_section(fresh_csv, f"The same models on sweep numbers {min(ms)} to {max(ms)}, which no sweep or fit "
                                 "has seen, re-measured end to end", "these matrices")
-        L += ["", f"    python -m paper_2403_17017_amd.training evaluate --csv gpurun_out/sweep.csv --model "
-              f"paper_2403_17017_amd/selector_model.json --first {min(ms)} --count {len(ms)} --out gpurun_out/eval_fresh.csv"]
+        L += ["", f"    python -m paper_2403_17017_amd.training evaluate --csv sweep.csv --model "
+              f"paper_2403_17017_amd/selector_model.json --first {min(ms)} --count {len(ms)} --out eval_fresh.csv"]
     if "iterative" in m:
         it = m["iterative"]["report"]["test"]
         L += ["", "## Models for n products with one matrix (Sec. V), held-out matrices, from sweep timings", "",
@@ -811,7 +812,7 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
         tp = lambda n, p: [float(r[f"t_plan_us_n{n}"]) for r in rr if int(r[f"path_n{n}"]) == p]
         L += ["", f"## The same models measured end to end ({e['matrices']} held-out matrices)", "",
               "    python -m paper_2403_17017_amd.training evaluate-iterative --model paper_2403_17017_amd/selector_model.json "
-              "--out gpurun_out/eval_iterative.csv", "",
+              "--out eval_iterative.csv", "",
               "Every kernel's preprocessing call and product timed again as in the sweep; the model's path = the "
               "seer_spmv_plan call as a user makes it through the Python binding (wall clock: selection, feature "
               "collection where asked for, preprocessing of the chosen kernel) + n * the product from the plan it "
