@@ -47,7 +47,9 @@ typedef enum {
     SEER_EKERNEL = -2,    /* kernel id outside [0, seer_num_kernels())                */
     SEER_ETREE = -3,      /* malformed tree: index out of range, cycle, bad feature   */
     SEER_EWORKSPACE = -4, /* workspace missing, misaligned or too small               */
-    SEER_EHIP = -5        /* a HIP runtime call failed; see seer_last_hip_error()     */
+    SEER_EHIP = -5,       /* a HIP runtime call failed; see seer_last_hip_error()     */
+    SEER_ELIMIT = -6      /* seer_spmv_auto_static: the matrix needs more scratch than
+                             the library's built-in array holds                         */
 } seer_status;
 
 /* Kernel ids: the CSR rows of Table II ("load balancing schedules"), in its order. */
@@ -190,6 +192,26 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
 int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y,
                    void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_auto_workspace_bytes(int32_t rows, int32_t nnz);
+
+/* seer_spmv_auto for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, checks, launches and results as seer_spmv_auto, but the scratch (feature
+ * partials, selection record, tile carry-outs) is an array of SEER_STATIC_SCRATCH_BYTES that
+ * the library itself holds in device memory, one copy per GPU, from the moment the library
+ * is loaded on that GPU until the process ends.  The call allocates and frees nothing, on the
+ * device or the host.
+ *   - Limit: SEER_ELIMIT if seer_spmv_auto_workspace_bytes(rows, nnz) exceeds
+ *     SEER_STATIC_SCRATCH_BYTES (about 4.6e8 rows + nonzeros); nothing is enqueued then.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress, with
+ *     that device current); make that call before capturing a graph.
+ *   - All calls on one GPU share the one array, and it keeps the last call's contents; the
+ *     kernels overwrite every word they later read, so nothing needs clearing.  Two calls
+ *     on the same GPU must not overlap in time: on different streams without an ordering
+ *     between them they race on the array and both results are undefined.
+ *   - There is no way to ask what was selected (seer_spmv_auto_result takes a workspace). */
+#define SEER_STATIC_SCRATCH_BYTES (2u << 20)
+int seer_spmv_auto_static(const seer_csr *A, const seer_tree *tree, const float *x, float *y,
+                          void *stream);
 
 /* The three models of Sec. III-A.  `selector` is the classifier-selection model: it
  * sees only the known features (seer_known_features) and answers 0 = "the known

@@ -106,6 +106,8 @@ def lib():
         L.seer_spmv_workspace_bytes.restype = sz
         L.seer_spmv_auto.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_tree), vp, vp, vp, sz, vp]
         L.seer_spmv_auto.restype = C.c_int
+        L.seer_spmv_auto_static.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_tree), vp, vp, vp]
+        L.seer_spmv_auto_static.restype = C.c_int
         L.seer_spmv_auto_workspace_bytes.argtypes = [i32, i32]
         L.seer_spmv_auto_workspace_bytes.restype = sz
         L.seer_spmv_auto_result.argtypes = [vp, vp, C.POINTER(seer_features_t), C.POINTER(C.c_int)]
@@ -340,6 +342,18 @@ def seer_spmv_auto(A: DeviceCSR, tree: Tree, x, y, workspace, stream=None) -> No
                               workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     if rc:
         raise SeerError(rc, "seer_spmv_auto")
+
+
+STATIC_SCRATCH_BYTES = 2 << 20   # SEER_STATIC_SCRATCH_BYTES
+
+
+def seer_spmv_auto_static(A: DeviceCSR, tree: Tree, x, y, stream=None) -> None:
+    """seer_spmv_auto on the library's own built-in scratch: no workspace argument, nothing
+    allocated.  Raises SeerError(SEER_ELIMIT) for a matrix beyond STATIC_SCRATCH_BYTES."""
+    cs = A.c_struct()
+    rc = lib().seer_spmv_auto_static(C.byref(cs), C.byref(tree.c), x.data_ptr(), y.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise SeerError(rc, "seer_spmv_auto_static")
 
 
 def seer_spmv_auto_result(workspace, stream=None):

@@ -10,11 +10,22 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
-#include <vector>
 
 using namespace seer;
 
+// Scratch of seer_spmv_auto_static, the entry point for callers that cannot allocate: feature
+// partials, the selection record and the tile carry-outs of the asynchronous path.  Every
+// GPU the library runs on holds its own copy of this array until the process ends.  In host
+// code the name below is only a handle for hipGetSymbolAddress; kernels get the address
+// that call returns.
+constexpr size_t kStaticScratchBytes = SEER_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on each device, once looked up
 
 std::atomic<int> g_last_hip_error{0};
 
@@ -283,27 +294,34 @@ int check_tree(const seer_tree *t)
     return SEER_OK;
 }
 
-// True if no path from the root visits a node twice (iterative depth-first walk).
+// True if no path from the root visits a node twice (iterative depth-first walk).  Called
+// with at most kAutoMaxNodes nodes, so its bookkeeping lives on the stack: the asynchronous
+// entry points allocate nothing, on the host or the device.
 bool tree_is_acyclic(const seer_tree *t)
 {
     const int32_t n = t->n_nodes;
-    std::vector<uint8_t> state((size_t)n, 0);   // 0 unseen, 1 on the current path, 2 done
-    std::vector<int32_t> stack;
-    stack.push_back(0);
-    while (!stack.empty()) {
-        const int32_t v = stack.back();
+    if (n > kAutoMaxNodes) return false;
+    uint8_t state[kAutoMaxNodes] = {};          // 0 unseen, 1 on the current path, 2 done
+    int32_t stack[2 * kAutoMaxNodes + 1];       // a node is pushed at most once per parent edge
+    int top = 0;
+    stack[top++] = 0;
+    while (top > 0) {
+        const int32_t v = stack[top - 1];
         if (state[v] == 0) {
             state[v] = 1;
             const seer_node &nd = t->nodes[v];
             if (nd.feature >= 0) {
                 for (int32_t c : {nd.left, nd.right}) {
                     if (state[c] == 1) return false;
-                    if (state[c] == 0) stack.push_back(c);
+                    if (state[c] == 0) {
+                        if (top >= (int)(sizeof stack / sizeof stack[0])) return false;
+                        stack[top++] = c;
+                    }
                 }
             }
         } else {
             if (state[v] == 1) state[v] = 2;
-            stack.pop_back();
+            --top;
         }
     }
     return true;
@@ -328,6 +346,7 @@ const char *seer_strerror(int s)
     case SEER_ETREE: return "malformed decision tree";
     case SEER_EWORKSPACE: return "workspace missing, misaligned or too small";
     case SEER_EHIP: return "HIP runtime error";
+    case SEER_ELIMIT: return "matrix too large for the library's built-in scratch";
     default: return "unknown status";
     }
 }
@@ -478,9 +497,11 @@ size_t seer_spmv_auto_workspace_bytes(int32_t rows, int32_t nnz)
     return auto_workspace_bytes(rows, nnz);
 }
 
-int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y, void *workspace,
-                   size_t workspace_bytes, void *stream)
+// Everything seer_spmv_auto checks before it needs scratch memory.  SEER_OK with *enqueue
+// false: nothing to do (no rows).
+static int auto_check(const seer_csr *A, const seer_tree *tree, const float *x, float *y, bool *enqueue)
 {
+    *enqueue = false;
     const int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     if (!tree) return SEER_EINVAL;
@@ -492,8 +513,15 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
     if (!tree_is_acyclic(tree)) return SEER_ETREE;
     if (A->rows == 0) return SEER_OK;
     if (!y || (!x && A->nnz > 0) || vectors_overlap(A, x, y)) return SEER_EINVAL;
-    if (!workspace || !aligned16(workspace) || workspace_bytes < auto_workspace_bytes(A->rows, A->nnz))
-        return SEER_EWORKSPACE;
+    *enqueue = true;
+    return SEER_OK;
+}
+
+// Launch shapes from rows and nnz, then the launches; `workspace` holds at least
+// auto_workspace_bytes(rows, nnz) bytes.
+static int auto_enqueue(const seer_csr *A, const seer_tree *tree, const float *x, float *y, void *workspace,
+                        void *stream)
+{
     AutoTree dt;
     std::memset(&dt, 0, sizeof dt);
     dt.n_nodes = tree->n_nodes;
@@ -521,6 +549,43 @@ int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, flo
                 static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);
+}
+
+int seer_spmv_auto(const seer_csr *A, const seer_tree *tree, const float *x, float *y, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    bool enqueue = false;
+    const int rc = auto_check(A, tree, x, y, &enqueue);
+    if (rc != SEER_OK || !enqueue) return rc;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < auto_workspace_bytes(A->rows, A->nnz))
+        return SEER_EWORKSPACE;
+    return auto_enqueue(A, tree, x, y, workspace, stream);
+}
+
+int seer_spmv_auto_static(const seer_csr *A, const seer_tree *tree, const float *x, float *y, void *stream)
+{
+    bool enqueue = false;
+    const int rc = auto_check(A, tree, x, y, &enqueue);
+    if (rc != SEER_OK || !enqueue) return rc;
+    if (auto_workspace_bytes(A->rows, A->nnz) > kStaticScratchBytes) return SEER_ELIMIT;
+    // The array's device address, looked up once per device with that device current.
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SEER_EINVAL;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return hip_fail(e);
+            if (!p) return hip_fail(hipErrorInvalidSymbol);
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    return auto_enqueue(A, tree, x, y, ptr, stream);
 }
 
 int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, float *y, void *workspace,
