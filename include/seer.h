@@ -6,7 +6,7 @@
  * features of the matrix, walk a decision tree over them to obtain a kernel index,
  * run that SpMV kernel.  seer_features, seer_select and seer_spmv are those three steps;
  * seer_spmv_auto and seer_spmv_model run them without the host in between; and for
- * several products with one matrix (Sec. V) seer_spmv_plan selects with the iteration
+ * several products with one matrix (Sec. IV-E) seer_spmv_plan selects with the iteration
  * count, runs the chosen kernel's preprocessing once, and seer_spmv_prepared is each
  * product.
  *
@@ -92,7 +92,7 @@ typedef struct {
  * a row = its nonzero count / cols, Sec. IV-A); 3-7 are the same statistics on
  * row lengths (Table III: Most, Least, Avg, Var) plus the fraction of empty rows;
  * 12 is the number of products the caller is about to run with this matrix, known
- * to every model at no cost (Sec. V, multiple iteration evaluation).  Every call here
+ * to every model at no cost (Sec. IV-E, multiple iteration evaluation).  Every call here
  * that fills a vector writes 1 there; seer_spmv_plan writes the caller's count. */
 enum {
     SEER_F_ROWS = 0, SEER_F_COLS, SEER_F_NNZ,
@@ -162,6 +162,19 @@ int seer_known_features(int32_t rows, int32_t cols, int32_t nnz, seer_features_t
  * integer index).  HOST only.  Validates the tree (SEER_ETREE) before walking. */
 int seer_select(const seer_features_t *f, const seer_tree *tree, int *kernel_id);
 
+/* What a tree can still answer once the features that cost nothing are fixed (Sec. III-A:
+ * rows, columns and nonzeros come with the dataset; Sec. III-B: collecting the others is
+ * only justified where it can change the choice).  `known` is what seer_known_features
+ * filled (f[SEER_F_ITERATIONS] may be set by the caller); its other entries are ignored.
+ * *class_mask receives one bit per class of a leaf that a walk as in seer_select can end
+ * in when every entry other than rows, cols, nnz, mean length, mean density and the
+ * iteration count may take any value: at a node that tests a known entry the walk goes
+ * where seer_select would, at any other node both children stay possible (tests of one
+ * entry along a path are not reconciled, so the set may hold a class no matrix reaches;
+ * it never misses one).  One bit set: the answer does not depend on the matrix beyond its
+ * sizes.  HOST only.  SEER_ETREE for a malformed tree or more than 32 classes. */
+int seer_tree_reachable(const seer_tree *tree, const seer_features_t *known, uint32_t *class_mask);
+
 /* y = A x with the schedule `kernel_id` (Table II).  x: DEVICE [cols], y: DEVICE
  * [rows], overwritten (no alpha/beta); x and y must not overlap (SEER_EINVAL).  Every kernel id is
  * valid for every matrix and gives the same y up to fp32 summation order.
@@ -184,6 +197,11 @@ size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
  * collection (Sec. III-C) cut down to the reduction kernel itself.
  * y is the same as seer_spmv would give with the id seer_select would return for
  * the features seer_features would return (all three bit for bit).
+ * Before anything is enqueued the host prunes the tree with what it knows from rows,
+ * cols and nnz (seer_tree_reachable): the launches are sized for the schedules that stay
+ * reachable, the carry fix-up of CSR,MP / CSR,WO is enqueued only if one of them does,
+ * and if a single kernel is left the matrix is not looked at: that kernel is launched and
+ * nothing is gathered (Sec. III-B: collection only where it is justified).
  * tree: HOST, at most 127 nodes, no cycles, every leaf a kernel id below
  * SEER_NUM_DIRECT_KERNELS (SEER_ETREE otherwise; validated before anything is
  * enqueued).  f[SEER_F_ITERATIONS] is 1 on this path.
@@ -238,6 +256,10 @@ int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, 
 
 /* Waits for `stream`, then reports what the last seer_spmv_auto that used `workspace`
  * decided: the features it gathered and the kernel id it ran (either may be NULL).
+ * If the host could decide alone (see seer_spmv_auto) nothing was gathered: *features
+ * then holds what seer_known_features gives, with max_len = min_len = empty_rows = -1
+ * as the mark.  The record is whatever that call left at a fixed place in the workspace;
+ * other calls that are handed the same workspace may overwrite it.
  * SEER_EINVAL if no selection has been written there. */
 int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *features,
                           int *kernel_id);
@@ -297,7 +319,7 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
                        void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan);
 
-/* Selection for `iterations` >= 1 products with the same matrix (Sec. V, multiple
+/* Selection for `iterations` >= 1 products with the same matrix (Sec. IV-E, multiple
  * iteration evaluation): classifier-selection inference as in seer_spmv_model, with
  * f[SEER_F_ITERATIONS] = iterations in the vector every tree sees, so a model trained on
  * (preprocessing + iterations * run time) can tell when preprocessing is amortised; then
@@ -342,11 +364,15 @@ int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx
  *   "vec"       0: CSR,BM / CSR,MP / CSR,WO / CSR,A take entries with lane-strided 4-byte
  *               loads instead of 16-byte loads (what matrices whose col_idx / values
  *               are not 16-byte aligned get anyway); default 1
- *   "auto_fused_rows", "auto_fused_grid"  seer_spmv_auto: a matrix of at most
- *               auto_fused_rows rows (default 8192) is gathered, selected and multiplied
- *               in one launch, and the selection runs inside the product's launch
- *               whenever that launch has at most auto_fused_grid workgroups (default
- *               1024; 0: always a selection launch of its own)
+ *   "auto_fused_rows", "auto_fused_grid", "auto_fused_max_rows"  seer_spmv_auto: a matrix of
+ *               at most auto_fused_rows rows (default 8192) is gathered, selected and
+ *               multiplied in one launch; a larger one gets a first reduction pass and the
+ *               selection runs inside the product's launch if that launch has at most
+ *               auto_fused_grid workgroups (default 1024) or the matrix at most
+ *               auto_fused_max_rows rows (default 2^21); otherwise the selection is a
+ *               launch of its own (both 0: always)
+ *   "auto_prune" 0: seer_spmv_auto does not prune the tree with the known features (every
+ *               schedule counts as reachable, the features are always gathered); default 1
  *   "coo_runs"  COO,WM: 1 (default): a lane sums a run of eight consecutive triples,
  *               0: lane <-> triple in rounds of 64
  *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise

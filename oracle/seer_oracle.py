@@ -23,8 +23,11 @@ What it defines
                    (Sec. III-A) and inference with the classifier-selection
                    model that chooses between the known and the gathered model
                    (Sec. III-B).  The number of SpMV iterations the caller is
-                   about to run is one more known feature (Sec. V, multiple
+                   about to run is one more known feature (Sec. IV-E, multiple
                    iteration evaluation); it is 1 unless stated.
+  * reachable_classes -- which kernels the gathered model can still answer once the
+                   known features are fixed: what decides, before anything is gathered,
+                   whether gathering can change the choice at all (Sec. III-B).
   * ell_from_csr -- the preprocessing result of the ELL,TM kernel (Table II: thread
                    mapped over "one row or fixed width" in the ELL format): every row
                    padded to the longest row's length, stored column-major.  The
@@ -241,6 +244,33 @@ def model_select(rows, cols, nnz, f_gathered, selector, known, gathered, iterati
         if select(kf, *selector) == 0:
             return 0, select(kf, *known)
     return 1, select(f_gathered, *gathered)
+
+
+KNOWN_FEATURES = (0, 1, 2, 3, 8, 12)   # rows, cols, nnz, mean_len, mean_density, iterations
+
+
+def reachable_classes(f_known, feature, threshold, left, right, klass) -> set:
+    """The classes a walk of the tree (as in select) can end in when only the known
+    entries of the feature vector are fixed (Sec. III-A: the features that come with the
+    dataset at no cost) and every gathered entry may take any value: at a node that tests a
+    known entry the walk goes where select would go; at a node that tests a gathered entry
+    both children stay possible.  Comparisons on the same gathered entry along one path are
+    not reconciled with each other, so the set can hold a class no real vector reaches; it
+    never misses one.  A single class means the matrix need not be looked at (Sec. III-B:
+    feature collection is paid for only where it is justified)."""
+    out = set()
+
+    def walk(n):
+        if int(feature[n]) < 0:
+            out.add(int(klass[n]))
+        elif int(feature[n]) in KNOWN_FEATURES:
+            walk(int(left[n]) if float(np.float32(f_known[int(feature[n])])) <= float(threshold[n]) else int(right[n]))
+        else:
+            walk(int(left[n]))
+            walk(int(right[n]))
+
+    walk(0)
+    return out
 
 
 def select(f, feature, threshold, left, right, klass) -> int:

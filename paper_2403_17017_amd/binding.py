@@ -100,6 +100,8 @@ def lib():
         L.seer_known_features.restype = C.c_int
         L.seer_select.argtypes = [C.POINTER(seer_features_t), C.POINTER(seer_tree), C.POINTER(C.c_int)]
         L.seer_select.restype = C.c_int
+        L.seer_tree_reachable.argtypes = [C.POINTER(seer_tree), C.POINTER(seer_features_t), C.POINTER(C.c_uint32)]
+        L.seer_tree_reachable.restype = C.c_int
         L.seer_spmv.argtypes = [C.c_int, C.POINTER(seer_csr), vp, vp, vp, sz, vp]
         L.seer_spmv.restype = C.c_int
         L.seer_spmv_workspace_bytes.argtypes = [C.c_int, i32, i32]
@@ -285,6 +287,15 @@ def seer_select(f: seer_features_t, tree: Tree) -> int:
     if rc:
         raise SeerError(rc, "seer_select")
     return int(k.value)
+
+
+def seer_tree_reachable(tree: Tree, known: seer_features_t) -> set:
+    """Classes the tree can still answer given the known features alone."""
+    mask = C.c_uint32(0)
+    rc = lib().seer_tree_reachable(C.byref(tree.c), C.byref(known), C.byref(mask))
+    if rc:
+        raise SeerError(rc, "seer_tree_reachable")
+    return {k for k in range(32) if (mask.value >> k) & 1}
 
 
 def seer_spmv(kernel_id: int, A: DeviceCSR, x, y, workspace=None, stream=None) -> None:

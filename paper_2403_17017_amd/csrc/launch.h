@@ -100,8 +100,8 @@ struct AutoHeap {                           // passed to the kernel by value (89
 };
 bool flatten_tree(const seer_tree *tree, AutoHeap *heap);   // false: deeper than 6 levels of comparisons
 
-struct AutoSel {                            // what the selection kernel leaves in the workspace
-    int32_t kernel_id, valid;
+struct AutoSel {                            // what the selection leaves in the workspace
+    int32_t kernel_id, valid;               // valid: 1 gathered on the device; 2 decided on the host, no statistics
     int64_t rows, cols, nnz;
     int32_t max_len, min_len;
     uint64_t sum_sq, empty;
@@ -113,17 +113,27 @@ struct AutoShape {                          // launch shapes, all from rows and 
     int tm_short;                           // CSR,TM fetches the first eight entries of a row at once (mean row length <= 8)
     int tm_pair;                            // ... and takes two rows per lane (tiles of 512 rows)
     int tm_remap;                           // CSR,TM's tile order: 1 XCD-contiguous, 0 round-robin
+    uint32_t reachable;                     // bit k: the tree can answer kernel k given rows, cols and nnz (never 0)
 };
 constexpr size_t kAutoSelOffset = 32768;    // after the 1024 feature partials of 32 bytes
 constexpr size_t kAutoCarryOffset = 32768 + 256;
 size_t auto_workspace_bytes(int rows, int nnz);
-constexpr int kAutoFusedRows = 8192;        // up to here every workgroup gathers and selects for itself
-constexpr int kAutoFusedGrid = 1024;        // the product's launch selects for itself up to this many workgroups
-constexpr uint32_t kAutoFusedParts = 64;    // partials the first pass leaves for it (each workgroup reads them all)
+constexpr int kAutoFusedRows = 8192;        // up to here every workgroup gathers and selects for itself, no first pass
+constexpr int kAutoFusedGrid = 1024;        // the product's launch selects for itself up to this many workgroups ...
+constexpr int kAutoFusedMaxRows = 0;        // ... and, whatever its grid, up to this many rows (off: measured slower; the first pass
+                                            // of at most kAutoFusedParts workgroups is the slower way to read row_ptr)
+constexpr uint32_t kAutoFusedParts = 64;    // partials the first pass leaves for it (one per lane of the folding wave)
 constexpr uint32_t kAutoWmGrid = 4096;      // combined kernel: CSR,WM loops beyond max(this, the other schedules' grids)
-// heap: the flattened tree, or null if it is too deep (then the node array is walked)
+struct AutoPolicy {                         // when the selection runs inside the product's launch
+    int fused_rows, fused_grid, fused_max_rows;
+    int select_wave;                        // 1: the selection launch is a single wave (0: a workgroup of 1024 lanes)
+    uint32_t part_rows;                     // rows per workgroup of the first pass (0: the default)
+};
+// heap: the flattened tree, or null if it is too deep (then the node array is walked).
+// decided: null, or the record of a choice the host could make alone (shape.reachable has
+// one bit): nothing is gathered then.
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, const AutoShape &shape, bool vec,
-                 int fused_rows, int fused_grid, void *workspace, hipStream_t st);
+                 const AutoPolicy &policy, const AutoSel *decided, void *workspace, hipStream_t st);
 
 void launch_csr_check(int rows, int cols, int nnz, const int *rp, const int *ci, void *counts, hipStream_t st);
 void launch_stream_copy(void *dst, const void *src, size_t n_words, hipStream_t st);

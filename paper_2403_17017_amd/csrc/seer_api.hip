@@ -36,6 +36,10 @@ std::atomic<int> g_tune_bm_chunk{-1};
 std::atomic<int> g_tune_mp_ipt{-1};
 std::atomic<int> g_tune_fused_rows{-1};
 std::atomic<int> g_tune_fused_grid{-1};
+std::atomic<int> g_tune_fused_max_rows{-1};
+std::atomic<int> g_tune_prune{-1};
+std::atomic<int> g_tune_select_wave{-1};
+std::atomic<int> g_tune_part_rows{-1};
 std::atomic<int> g_tune_remap{-1};
 std::atomic<int> g_tune_nt{-1};
 std::atomic<int> g_tune_vec{-1};
@@ -276,6 +280,47 @@ bool leaves_below(const seer_tree *t, int limit)
     return true;
 }
 
+// Classes of the leaves a walk can end in when only the entries of f[] that follow from
+// rows, cols and nnz (and the iteration count) are known and the others may take any value:
+// one bit per class.  The known comparisons are the ones seer_select and the device make,
+// on the same bits.  Nodes may share children, so each is visited once; `seen` and `stack`
+// hold n_nodes and 2 * n_nodes + 1 entries.  Classes must be below 32.
+uint32_t reachable_classes(const seer_tree *t, const float *f, bool *seen, int32_t *stack)
+{
+    const auto known = [](int feature) {
+        return feature == SEER_F_ROWS || feature == SEER_F_COLS || feature == SEER_F_NNZ ||
+               feature == SEER_F_MEAN_LEN || feature == SEER_F_MEAN_DENSITY || feature == SEER_F_ITERATIONS;
+    };
+    uint32_t mask = 0;
+    for (int32_t i = 0; i < t->n_nodes; ++i) seen[i] = false;
+    int top = 0;
+    stack[top++] = 0;
+    while (top > 0) {
+        const int32_t v = stack[--top];
+        if (seen[v]) continue;
+        seen[v] = true;
+        const seer_node &nd = t->nodes[v];
+        if (nd.feature < 0) {
+            mask |= 1u << nd.klass;
+        } else if (known(nd.feature)) {
+            stack[top++] = ((double)f[nd.feature] <= nd.threshold) ? nd.left : nd.right;
+        } else {
+            stack[top++] = nd.left;
+            stack[top++] = nd.right;
+        }
+    }
+    return mask;
+}
+
+// ... for the asynchronous path, whose trees have at most kAutoMaxNodes nodes and only
+// kernel ids below SEER_NUM_DIRECT_KERNELS in their leaves: nothing is allocated.
+uint32_t reachable_kernels(const seer_tree *t, const float *f)
+{
+    bool seen[kAutoMaxNodes];
+    int32_t stack[2 * kAutoMaxNodes + 1];
+    return reachable_classes(t, f, seen, stack);
+}
+
 int check_tree(const seer_tree *t)
 {
     if (!t->nodes || t->n_nodes < 1 || t->n_classes < 1 || t->n_features < 0 ||
@@ -362,6 +407,10 @@ int seer_set_tuning(const char *name, int value)
     else if (!std::strcmp(name, "mp_ipt")) g_tune_mp_ipt.store(value);
     else if (!std::strcmp(name, "auto_fused_rows")) g_tune_fused_rows.store(value);
     else if (!std::strcmp(name, "auto_fused_grid")) g_tune_fused_grid.store(value);
+    else if (!std::strcmp(name, "auto_fused_max_rows")) g_tune_fused_max_rows.store(value);
+    else if (!std::strcmp(name, "auto_prune")) g_tune_prune.store(value);
+    else if (!std::strcmp(name, "auto_select_wave")) g_tune_select_wave.store(value);
+    else if (!std::strcmp(name, "auto_part_rows")) g_tune_part_rows.store(value);
     else if (!std::strcmp(name, "xcd_remap")) g_tune_remap.store(value);
     else if (!std::strcmp(name, "nt")) g_tune_nt.store(value);
     else if (!std::strcmp(name, "vec")) g_tune_vec.store(value);
@@ -491,6 +540,26 @@ int seer_select(const seer_features_t *f, const seer_tree *t, int *kernel_id)
     return SEER_ETREE;   // walked more nodes than exist: a cycle
 }
 
+int seer_tree_reachable(const seer_tree *tree, const seer_features_t *known, uint32_t *class_mask)
+{
+    if (!tree || !known || !class_mask) return SEER_EINVAL;
+    const int rc = check_tree(tree);
+    if (rc != SEER_OK) return rc;
+    if (tree->n_classes > 32) return SEER_ETREE;
+    const size_t n = (size_t)tree->n_nodes;
+    bool *seen = static_cast<bool *>(std::malloc(n));
+    int32_t *stack = static_cast<int32_t *>(std::malloc((2 * n + 1) * sizeof(int32_t)));
+    if (!seen || !stack) {
+        std::free(seen);
+        std::free(stack);
+        return SEER_EINVAL;
+    }
+    *class_mask = reachable_classes(tree, known->f, seen, stack);
+    std::free(seen);
+    std::free(stack);
+    return SEER_OK;
+}
+
 size_t seer_spmv_auto_workspace_bytes(int32_t rows, int32_t nnz)
 {
     if (rows < 0 || nnz < 0) return 0;
@@ -542,10 +611,30 @@ static int auto_enqueue(const seer_csr *A, const seer_tree *tree, const float *x
     sh.tiles[SEER_CSR_WO] = wo_num_tiles(A->rows, A->nnz);
     SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(), 1};
     const bool vec = aligned16(A->col_idx) && aligned16(A->values) && g_tune_vec.load() != 0;
-    const int fg = g_tune_fused_grid.load();
+    // What the host knows without looking at the matrix prunes the tree: the grid is sized
+    // for the schedules that stay reachable, the carry fix-up is enqueued only if merge path
+    // or the nonzero split is among them, and if a single kernel is left nothing is gathered.
+    seer_features_t kf;
+    (void)seer_known_features(A->rows, A->cols, A->nnz, &kf);
+    sh.reachable = g_tune_prune.load() == 0 ? (1u << SEER_NUM_DIRECT_KERNELS) - 1u : reachable_kernels(tree, kf.f);
+    AutoSel record;
+    const bool decided = (sh.reachable & (sh.reachable - 1u)) == 0;
+    if (decided) {
+        std::memset(&record, 0, sizeof record);
+        record.kernel_id = __builtin_ctz(sh.reachable);
+        record.valid = 2;
+        record.rows = A->rows; record.cols = A->cols; record.nnz = A->nnz;
+        record.max_len = -1; record.min_len = -1;
+        record.empty = ~0ull;
+        for (int i = 0; i < SEER_NUM_FEATURES; ++i) record.f[i] = kf.f[i];
+    }
+    const int fg = g_tune_fused_grid.load(), fm = g_tune_fused_max_rows.load();
+    const int pr = g_tune_part_rows.load();
+    const AutoPolicy policy{auto_fused_rows(), fg < 0 ? kAutoFusedGrid : fg, fm < 0 ? kAutoFusedMaxRows : fm,
+                            g_tune_select_wave.load() != 0, pr >= 256 ? (uint32_t)pr : 0u};
     AutoHeap heap;
     const bool flat = flatten_tree(tree, &heap);
-    launch_auto(a, dt, flat ? &heap : nullptr, sh, vec, auto_fused_rows(), fg < 0 ? kAutoFusedGrid : fg, workspace,
+    launch_auto(a, dt, flat ? &heap : nullptr, sh, vec, policy, decided ? &record : nullptr, workspace,
                 static_cast<hipStream_t>(stream));
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SEER_OK : hip_fail(e);
@@ -631,7 +720,7 @@ int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *
     if (e != hipSuccess) return hip_fail(e);
     e = hipStreamSynchronize(st);
     if (e != hipSuccess) return hip_fail(e);
-    if (sel.valid != 1) return SEER_EINVAL;
+    if (sel.valid != 1 && sel.valid != 2) return SEER_EINVAL;
     if (kernel_id) *kernel_id = sel.kernel_id;
     if (features) {
         std::memset(features, 0, sizeof *features);

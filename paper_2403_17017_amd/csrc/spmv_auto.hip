@@ -80,7 +80,7 @@ __device__ __forceinline__ void derive_features_device(
 // block costs more than the few nodes a walk touches.)
 __device__ __forceinline__ int select_on_device(
     int rows, int cols, const int *__restrict__ rp, const FeatLds *s, float *s_f, const AutoTree &tree,
-    AutoSel *__restrict__ sel)
+    uint32_t reachable, AutoSel *__restrict__ sel)
 {
     const int64_t nnz = (int64_t)rp[rows] - (int64_t)rp[0];
     derive_features_device(rows, cols, nnz, s->mx, s->mn, (int64_t)s->em, s->sq, s_f);
@@ -91,6 +91,7 @@ __device__ __forceinline__ int select_on_device(
         n = ((double)s_f[feature] <= tree.nodes[n].threshold) ? tree.nodes[n].left : tree.nodes[n].right;
     }
     k = (k >= 0 && k < SEER_NUM_DIRECT_KERNELS) ? k : SEER_CSR_MP;
+    if (!((reachable >> k) & 1u)) k = __ffs((int)reachable) - 1;   // (see select_in_wave)
     if (sel) {
         sel->kernel_id = k;
         sel->valid = 1;
@@ -120,11 +121,46 @@ __device__ __forceinline__ HeapRegs heap_load(const AutoHeap &h)
     return HeapRegs{h.feature[l], h.threshold[l], (int)h.klass[l], (int)h.klass[kHeapInternal + l]};
 }
 
-// All 64 lanes of one wave; s_f is the feature vector in LDS (complete and visible).
-__device__ __forceinline__ int heap_walk(const HeapRegs &r, const float *s_f)
+struct FeatTotals {   // the four reduced statistics of the whole matrix
+    int32_t mx, mn;
+    uint64_t sq, em;
+};
+
+// Entry `l` of the feature vector (l < SEER_NUM_FEATURES; other lanes get 1).  The same
+// operations as derive_features_device, arranged so that every lane of a wave runs the same
+// instructions on its own operands: f[l] = fl32((a / b) / c) with b, c = 1 where the entry
+// has fewer divisions (x / 1 is exact), so the thirteen entries cost two fp64 divisions
+// instead of seven one after the other.  rows > 0.
+__device__ __forceinline__ float derive_feature_lane(int rows, int cols, int64_t nnz, const FeatTotals &t, int l)
+{
+    const double R = (double)(int64_t)rows, C = (double)(int64_t)cols, N = (double)nnz;
+    const unsigned __int128 num = (unsigned __int128)(uint64_t)rows * (unsigned __int128)t.sq -
+                                  (unsigned __int128)(uint64_t)nnz * (unsigned __int128)(uint64_t)nnz;
+    const double VN = u128_to_double(num), RR = (double)((uint64_t)rows * (uint64_t)rows);
+    const double MX = (double)(int64_t)t.mx, MN = (double)(int64_t)t.mn, E = (double)(int64_t)t.em;
+    const bool density = l >= SEER_F_MEAN_DENSITY && l <= SEER_F_VAR_DENSITY;
+    double a = 1.0, b = 1.0, c = 1.0;           // SEER_F_ITERATIONS: 1 on this path
+    if (l == SEER_F_ROWS) a = R;
+    if (l == SEER_F_COLS) a = C;
+    if (l == SEER_F_NNZ || l == SEER_F_MEAN_LEN || l == SEER_F_MEAN_DENSITY) a = N;
+    if (l == SEER_F_MAX_LEN || l == SEER_F_MAX_DENSITY) a = MX;
+    if (l == SEER_F_MIN_LEN || l == SEER_F_MIN_DENSITY) a = MN;
+    if (l == SEER_F_VAR_LEN || l == SEER_F_VAR_DENSITY) a = VN;
+    if (l == SEER_F_EMPTY_FRAC) a = E;
+    if (l == SEER_F_MEAN_LEN || l == SEER_F_EMPTY_FRAC || l == SEER_F_MEAN_DENSITY) b = R;
+    if (l == SEER_F_VAR_LEN || l == SEER_F_VAR_DENSITY) b = RR;
+    if (density) c = l == SEER_F_VAR_DENSITY ? C * C : C;
+    if (density && cols <= 0) { a = 0.0; b = 1.0; c = 1.0; }   // no columns: densities are 0
+    return (float)((a / b) / c);
+}
+
+// All 64 lanes of one wave, each holding its slot of the flattened tree in `r` and, for
+// lane < SEER_NUM_FEATURES, its entry of the feature vector in `f`.
+__device__ __forceinline__ int heap_walk_lanes(const HeapRegs &r, float f)
 {
     const bool leaf = r.feature < 0;
-    const bool right = !leaf && !((double)s_f[leaf ? 0 : r.feature] <= r.threshold);
+    const float fv = __shfl(f, leaf ? 0 : r.feature);
+    const bool right = !leaf && !((double)fv <= r.threshold);
     const uint64_t leaf_mask = __ballot(leaf), right_mask = __ballot(right);
     int i = 0;
 #pragma unroll
@@ -136,64 +172,106 @@ __device__ __forceinline__ int heap_walk(const HeapRegs &r, const float *s_f)
     return (k >= 0 && k < SEER_NUM_DIRECT_KERNELS) ? k : SEER_CSR_MP;
 }
 
-__device__ __forceinline__ void write_selection(
-    AutoSel *__restrict__ sel, int k, int rows, int cols, int64_t nnz, const FeatLds *s, const float *s_f)
+// One wave: from the matrix's statistics to the kernel id (the same in every lane), and, if
+// `sel` is given, the record seer_spmv_auto_result reads.  `reachable` has a bit per kernel
+// id the host found reachable from rows, cols and nnz alone and sized the grid for; the
+// device arrives at one of them unless nnz is not what row_ptr says, and then takes the
+// lowest of them rather than a schedule the grid cannot hold.
+__device__ __forceinline__ int select_in_wave(
+    int rows, int cols, int64_t nnz, const FeatTotals &t, const HeapRegs &hr, uint32_t reachable,
+    AutoSel *__restrict__ sel)
 {
-    sel->kernel_id = k;
-    sel->valid = 1;
-    sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
-    sel->max_len = s->mx; sel->min_len = s->mn;
-    sel->sum_sq = s->sq; sel->empty = s->em;
-#pragma unroll
-    for (int i = 0; i < SEER_NUM_FEATURES; ++i) sel->f[i] = s_f[i];
-}
-
-// The workgroup's statistics are in *s (after a barrier).  Derives the features (one lane),
-// walks the flattened tree (first wave) and leaves the kernel id in *s_k for everyone; ends
-// with a barrier.
-__device__ __forceinline__ void select_with_heap(
-    int rows, int cols, const int *__restrict__ rp, const FeatLds *s, float *s_f, const HeapRegs &hr,
-    AutoSel *__restrict__ sel, int *s_k)
-{
-    int64_t nnz = 0;
-    if (threadIdx.x == 0) {
-        nnz = (int64_t)rp[rows] - (int64_t)rp[0];
-        derive_features_device(rows, cols, nnz, s->mx, s->mn, (int64_t)s->em, s->sq, s_f);
-    }
-    __syncthreads();
-    if (threadIdx.x < kWave) {
-        const int k = heap_walk(hr, s_f);
-        if (threadIdx.x == 0) {
-            *s_k = k;
-            if (sel) write_selection(sel, k, rows, cols, nnz, s, s_f);
+    const int l = threadIdx.x % kWave;
+    const float f = derive_feature_lane(rows, cols, nnz, t, l);
+    int k = heap_walk_lanes(hr, f);
+    if (!((reachable >> k) & 1u)) k = __ffs((int)reachable) - 1;
+    if (sel) {
+        if (l < SEER_NUM_FEATURES) sel->f[l] = f;
+        if (l == 0) {
+            sel->kernel_id = k;
+            sel->valid = 1;
+            sel->rows = rows; sel->cols = cols; sel->nnz = nnz;
+            sel->max_len = t.mx; sel->min_len = t.mn;
+            sel->sum_sq = t.sq; sel->empty = t.em;
         }
     }
-    __syncthreads();
+    return k;
 }
 
+// The partials of a first pass folded by one wave (lane l takes partials l, l + 64, ..., all
+// requested before the first is used; then a butterfly): no LDS, no barrier.  Every lane ends
+// up with the totals.
+__device__ __forceinline__ FeatTotals fold_partials_wave(const FeatPartial *__restrict__ part, uint32_t n_part)
+{
+    const uint32_t l = threadIdx.x % kWave;
+    FeatTotals t{INT32_MIN, INT32_MAX, 0, 0};
+    for (uint32_t b = l; b < n_part; b += kWave * 4u) {
+        FeatPartial p[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t i = b + (uint32_t)j * kWave;
+            p[j] = part[i < n_part ? i : b];          // (a repeat of partial b changes no statistic but the sums)
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool in = b + (uint32_t)j * kWave < n_part;
+            t.mx = max(t.mx, p[j].max_len);
+            t.mn = min(t.mn, p[j].min_len);
+            t.sq += in ? p[j].sum_sq : 0u;
+            t.em += in ? p[j].empty : 0u;
+        }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        t.mx = max(t.mx, __shfl_xor(t.mx, off));
+        t.mn = min(t.mn, __shfl_xor(t.mn, off));
+        t.sq += (uint64_t)__shfl_xor((unsigned long long)t.sq, off);
+        t.em += (uint64_t)__shfl_xor((unsigned long long)t.em, off);
+    }
+    return t;
+}
+
+// Finishing launch of the selection after a first pass: ONE wave folds the partials, derives
+// the features, walks the tree and leaves the record -- no LDS, no barrier (as a workgroup of
+// 1024 lanes that met in LDS atomics it took 4.4 us on the timeline).
+__global__ __launch_bounds__(kWave) void features_select_wave_kernel(
+    int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
+    AutoSel *__restrict__ sel, const AutoHeap heap, uint32_t reachable)
+{
+    const HeapRegs hr = heap_load(heap);
+    const int64_t nnz = (int64_t)rp[rows] - (int64_t)rp[0];
+    const FeatTotals t = fold_partials_wave(part, n_part);
+    select_in_wave(rows, cols, nnz, t, hr, reachable, sel);
+}
+
+// Finishing launch of the selection when it is a launch of its own: the workgroup folds the
+// partials of the first pass (or, for a small matrix, reduces row_ptr itself), its first wave
+// derives the features, walks the tree and leaves the record.
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_select_heap_kernel(
     int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
-    AutoSel *__restrict__ sel, const AutoHeap heap)
+    AutoSel *__restrict__ sel, const AutoHeap heap, uint32_t reachable)
 {
     __shared__ FeatLds s;
-    __shared__ float s_f[SEER_NUM_FEATURES];
-    __shared__ int s_k;
     HeapRegs hr{};
-    if (threadIdx.x < kWave) hr = heap_load(heap);
+    int64_t nnz = 0;
+    if (threadIdx.x < kWave) {                       // requested before the reduction, used after it
+        hr = heap_load(heap);
+        nnz = (int64_t)rp[rows] - (int64_t)rp[0];
+    }
     features_total<VEC>(rows, rp, part, n_part, &s);
-    select_with_heap(rows, cols, rp, &s, s_f, hr, sel, &s_k);
+    if (threadIdx.x < kWave) select_in_wave(rows, cols, nnz, FeatTotals{s.mx, s.mn, s.sq, s.em}, hr, reachable, sel);
 }
 
 template <bool VEC>
 __global__ __launch_bounds__(kFeatWG) void features_select_kernel(
     int rows, int cols, const int *__restrict__ rp, const FeatPartial *__restrict__ part, uint32_t n_part,
-    AutoSel *__restrict__ sel, const AutoTree tree)
+    AutoSel *__restrict__ sel, const AutoTree tree, uint32_t reachable)
 {
     __shared__ FeatLds s;
     __shared__ float s_f[SEER_NUM_FEATURES];
     features_total<VEC>(rows, rp, part, n_part, &s);
-    if (threadIdx.x == 0) select_on_device(rows, cols, rp, &s, s_f, tree, sel);
+    if (threadIdx.x == 0) select_on_device(rows, cols, rp, &s, s_f, tree, reachable, sel);
 }
 
 static_assert(kFeatMaxParts * sizeof(FeatPartial) <= kAutoSelOffset && sizeof(AutoSel) <= kAutoCarryOffset - kAutoSelOffset,
@@ -271,17 +349,34 @@ __global__ __launch_bounds__(kWG) void spmv_auto_kernel(
     auto_dispatch<IPT, VEC>(sel->kernel_id, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
 }
 
-// Selection inside the product's launch, for grids of a few hundred workgroups.  Every
-// workgroup finishes the feature reduction for itself -- for a small matrix it reduces
-// the whole row_ptr (n_part == 0; at most kAutoFusedRows offsets, out of L2 after the
-// first workgroup touched them), for a larger one it folds the few partials a first
-// pass left -- derives the same feature vector, walks the same tree and then runs its
-// share of the chosen schedule.  The redundant work costs each workgroup two to three
-// microseconds; a separate selection launch costs the whole path four to five.
-// (With thousands of workgroups the redundant work adds up to more than the launch it
-// saves -- measured on a 1M-row matrix: 37 us per step against 27.6 -- so larger grids
-// keep the selection as a launch of its own.)
-// Workgroup 0 leaves the record for seer_spmv_auto_result and the fix-up kernel.
+// The product when the host could decide alone: every leaf the tree can reach from rows,
+// cols and nnz names the same kernel, so nothing is gathered.  Workgroup 0 leaves the record
+// (valid = 2: no statistics, known features only).
+template <int IPT, bool VEC>
+__global__ __launch_bounds__(kWG) void spmv_auto_decided_kernel(
+    int rows, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
+    const float *__restrict__ va, const float *__restrict__ x, float *__restrict__ y,
+    int *__restrict__ carry_row, float *__restrict__ carry_val, AutoSel *__restrict__ sel,
+    const AutoSel record, const AutoShape shape, int remap)
+{
+    __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *sel = record;
+    auto_dispatch<IPT, VEC>(record.kernel_id, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
+}
+
+// Selection inside the product's launch.  The first wave of every workgroup finishes the
+// feature reduction for itself -- it folds the up to 64 partials a first pass left (lane <->
+// partial, no LDS; for a matrix of at most kAutoFusedRows rows there is no first pass and the
+// whole workgroup reduces row_ptr, out of L2 after the first workgroup touched it) -- derives
+// the same feature vector, walks the same tree, and hands the kernel id to the other waves
+// through LDS; then the workgroup runs its share of the chosen schedule.  The redundant work
+// is a few hundred instructions of one wave behind one load of two kilobytes that hits L2,
+// about what reading the choice of a selection launch costs; that launch itself costs the
+// path four to five microseconds.  Workgroup 0 leaves the record for seer_spmv_auto_result
+// and the fix-up kernel.
+// (An earlier form folded with LDS atomics between barriers and derived on a single lane; it
+// cost each workgroup two to three microseconds and only paid off for grids of up to a
+// thousand workgroups.)
 template <int IPT, bool VEC, bool RPVEC>
 __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
     int rows, int cols, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,
@@ -291,26 +386,27 @@ __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
 {
     __shared__ __attribute__((aligned(16))) int smem[kAutoLds];
     __shared__ FeatLds s;
-    __shared__ float s_f[SEER_NUM_FEATURES];
     __shared__ int s_k;
+    const bool first_wave = threadIdx.x < kWave;
     HeapRegs hr{};
-    if (threadIdx.x < kWave) hr = heap_load(heap);
-    int32_t mx, mn;
-    uint64_t sq, em;
-    if (n_part == 0) {
-        features_accumulate_strided<RPVEC>(rows, rp, threadIdx.x, kWG, mx, mn, sq, em);
-    } else {
-        mx = INT32_MIN; mn = INT32_MAX; sq = 0; em = 0;
-        for (uint32_t b = threadIdx.x; b < n_part; b += kWG) {
-            const FeatPartial p = part[b];
-            mx = max(mx, p.max_len);
-            mn = min(mn, p.min_len);
-            sq += p.sum_sq;
-            em += p.empty;
-        }
+    int64_t nnz_dev = 0;
+    FeatTotals t{INT32_MIN, INT32_MAX, 0, 0};
+    if (first_wave) {
+        hr = heap_load(heap);
+        nnz_dev = (int64_t)rp[rows] - (int64_t)rp[0];
     }
-    features_block_fold(mx, mn, sq, em, &s);
-    select_with_heap(rows, cols, rp, &s, s_f, hr, blockIdx.x == 0 ? sel : nullptr, &s_k);
+    if (n_part == 0) {                                // block-uniform
+        features_accumulate_strided<RPVEC>(rows, rp, threadIdx.x, kWG, t.mx, t.mn, t.sq, t.em);
+        features_block_fold(t.mx, t.mn, t.sq, t.em, &s);
+        t = FeatTotals{s.mx, s.mn, s.sq, s.em};
+    } else if (first_wave) {
+        t = fold_partials_wave(part, n_part);
+    }
+    if (first_wave) {
+        const int k = select_in_wave(rows, cols, nnz_dev, t, hr, shape.reachable, blockIdx.x == 0 ? sel : nullptr);
+        if (threadIdx.x == 0) s_k = k;
+    }
+    __syncthreads();
     auto_dispatch<IPT, VEC>(s_k, rows, nnz, rp, ci, va, x, y, carry_row, carry_val, shape, remap, smem);
 }
 
@@ -330,8 +426,27 @@ size_t auto_workspace_bytes(int rows, int nnz)
     return kAutoCarryOffset + (mp > wo ? mp : wo);
 }
 
+// The first pass ahead of a product that selects for itself: at most kAutoFusedParts
+// partials, sixteen rows (four 16-byte loads in flight) per lane and trip; workgroups of
+// 1024 lanes once 256-lane ones would need more than one trip.
+static uint32_t launch_fused_partials(const SpmvArgs &a, FeatPartial *part, bool rp_vec, hipStream_t st)
+{
+    const uint32_t rows = (uint32_t)a.rows;
+    if (rows <= kAutoFusedParts * kFeatPartWG * 16u) {
+        const uint32_t n = (rows + kFeatPartWG * 16u - 1u) / (kFeatPartWG * 16u);
+        if (rp_vec) hipLaunchKernelGGL((features_partial_kernel<true, kFeatPartWG>), dim3(n), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+        else hipLaunchKernelGGL((features_partial_kernel<false, kFeatPartWG>), dim3(n), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+        return n;
+    }
+    uint32_t n = (rows + kFeatWG * 16u - 1u) / (kFeatWG * 16u);
+    n = n > kAutoFusedParts ? kAutoFusedParts : n;
+    if (rp_vec) hipLaunchKernelGGL((features_partial_kernel<true, kFeatWG>), dim3(n), dim3(kFeatWG), 0, st, a.rows, a.rp, part);
+    else hipLaunchKernelGGL((features_partial_kernel<false, kFeatWG>), dim3(n), dim3(kFeatWG), 0, st, a.rows, a.rp, part);
+    return n;
+}
+
 void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, const AutoShape &shape, bool vec,
-                 int fused_rows, int fused_grid, void *workspace, hipStream_t st)
+                 const AutoPolicy &policy, const AutoSel *decided, void *workspace, hipStream_t st)
 {
     char *ws = static_cast<char *>(workspace);
     FeatPartial *part = reinterpret_cast<FeatPartial *>(ws);
@@ -341,34 +456,47 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, 
     const size_t one = carry_workspace_bytes(n_carry) / 2;
     int *carry_row = reinterpret_cast<int *>(ws + kAutoCarryOffset);
     float *carry_val = reinterpret_cast<float *>(ws + kAutoCarryOffset + one);
+    const auto reachable = [&](int k) { return ((shape.reachable >> k) & 1u) != 0; };
 
-    // One workgroup per tile of the schedule with the most tiles -- except CSR,WM, whose
-    // tiles (64/G rows per wave) can be several times the others': beyond kAutoWmGrid
+    // One workgroup per tile of the reachable schedule with the most tiles -- except CSR,WM,
+    // whose tiles (64/G rows per wave) can be several times the others': beyond kAutoWmGrid
     // workgroups its share is capped at the others' maximum and its workgroups loop, so a
     // grid that runs another schedule does not launch thousands of workgroups to no purpose.
     uint32_t grid = 0, wm_grid = 0;
     for (int k = 0; k < SEER_NUM_DIRECT_KERNELS; ++k) {
+        if (!reachable(k)) continue;
         const uint32_t g = a.remap ? tiles_per_xcd(shape.tiles[k]) * kXCD : shape.tiles[k];
         if (k == SEER_CSR_WM) wm_grid = g;
         else grid = g > grid ? g : grid;
     }
-    {
+    if (reachable(SEER_CSR_WM)) {
         const uint32_t cap = grid > kAutoWmGrid ? grid : kAutoWmGrid;
         const uint32_t g = wm_grid < cap ? wm_grid : cap;
         grid = g > grid ? g : grid;
     }
-    const bool rp_vec = (reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0;
-    if (heap && grid <= (uint32_t)fused_grid) {
-        // one launch for a small matrix; else a first pass that leaves a few partials
-        uint32_t n_part = 0;
-        if (a.rows > fused_rows) {
-            n_part = features_num_parts(a.rows);
-            n_part = n_part > kAutoFusedParts ? kAutoFusedParts : (n_part ? n_part : 1u);
-            if (rp_vec)
-                hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
-            else
-                hipLaunchKernelGGL(features_partial_kernel<false>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
+    // The fix-up launch finds nothing to do unless merge path or the nonzero split ran: it
+    // is only enqueued if the tree can get to one of them from what the host knows.
+    const bool carries = reachable(SEER_CSR_MP) || reachable(SEER_CSR_WO);
+
+    if (decided) {
+#define SEER_DECIDED_LAUNCH(I, V)                                                                          \
+    hipLaunchKernelGGL((spmv_auto_decided_kernel<I, V>), dim3(grid), dim3(kWG), 0, st, a.rows, a.nnz, a.rp, \
+                       a.ci, a.va, a.x, a.y, carry_row, carry_val, sel, *decided, shape, a.remap)
+        if (shape.mp_ipt == kMpIptSmall) {
+            if (vec) SEER_DECIDED_LAUNCH(kMpIptSmall, true); else SEER_DECIDED_LAUNCH(kMpIptSmall, false);
+        } else {
+            if (vec) SEER_DECIDED_LAUNCH(kMpIptLarge, true); else SEER_DECIDED_LAUNCH(kMpIptLarge, false);
         }
+#undef SEER_DECIDED_LAUNCH
+        if (carries)
+            launch_carry_fixup(a.rows, decided->kernel_id == SEER_CSR_MP ? n_mp : n_wo, carry_row, carry_val, a.y, st);
+        return;
+    }
+
+    const bool rp_vec = (reinterpret_cast<uintptr_t>(a.rp) & 15u) == 0;
+    if (heap && (grid <= (uint32_t)policy.fused_grid || a.rows <= policy.fused_max_rows)) {
+        // one launch for a small matrix; else a first pass that leaves a few partials
+        const uint32_t n_part = a.rows > policy.fused_rows ? launch_fused_partials(a, part, rp_vec, st) : 0u;
 #define SEER_FUSED_LAUNCH(I, V, R)                                                                          \
     hipLaunchKernelGGL((spmv_auto_fused_kernel<I, V, R>), dim3(grid), dim3(kWG), 0, st, a.rows, a.cols, a.nnz, \
                        a.rp, a.ci, a.va, a.x, a.y, carry_row, carry_val, part, n_part, sel, *heap, shape, a.remap)
@@ -380,30 +508,37 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, 
             else     { if (rp_vec) SEER_FUSED_LAUNCH(kMpIptLarge, false, true); else SEER_FUSED_LAUNCH(kMpIptLarge, false, false); }
         }
 #undef SEER_FUSED_LAUNCH
-        hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_carry + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
-                           n_wo, carry_row, carry_val, a.y, sel);
+        if (carries)
+            hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_carry + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
+                               n_wo, carry_row, carry_val, a.y, sel);
         return;
     }
 
-    const uint32_t n_part = features_num_parts(a.rows);
+    const uint32_t n_part = features_num_parts(a.rows, policy.part_rows);
     if (rp_vec) {
         if (n_part)
             hipLaunchKernelGGL(features_partial_kernel<true>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
-        if (heap)
+        if (heap && n_part && policy.select_wave)
+            hipLaunchKernelGGL(features_select_wave_kernel, dim3(1), dim3(kWave), 0, st, a.rows, a.cols, a.rp, part,
+                               n_part, sel, *heap, shape.reachable);
+        else if (heap)
             hipLaunchKernelGGL(features_select_heap_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp,
-                               part, n_part, sel, *heap);
+                               part, n_part, sel, *heap, shape.reachable);
         else
             hipLaunchKernelGGL(features_select_kernel<true>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
-                               n_part, sel, tree);
+                               n_part, sel, tree, shape.reachable);
     } else {
         if (n_part)
             hipLaunchKernelGGL(features_partial_kernel<false>, dim3(n_part), dim3(kFeatPartWG), 0, st, a.rows, a.rp, part);
-        if (heap)
+        if (heap && n_part && policy.select_wave)
+            hipLaunchKernelGGL(features_select_wave_kernel, dim3(1), dim3(kWave), 0, st, a.rows, a.cols, a.rp, part,
+                               n_part, sel, *heap, shape.reachable);
+        else if (heap)
             hipLaunchKernelGGL(features_select_heap_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp,
-                               part, n_part, sel, *heap);
+                               part, n_part, sel, *heap, shape.reachable);
         else
             hipLaunchKernelGGL(features_select_kernel<false>, dim3(1), dim3(kFeatWG), 0, st, a.rows, a.cols, a.rp, part,
-                               n_part, sel, tree);
+                               n_part, sel, tree, shape.reachable);
     }
 
 #define SEER_AUTO_LAUNCH(I, V)                                                                             \
@@ -415,8 +550,9 @@ void launch_auto(const SpmvArgs &a, const AutoTree &tree, const AutoHeap *heap, 
         if (vec) SEER_AUTO_LAUNCH(kMpIptLarge, true); else SEER_AUTO_LAUNCH(kMpIptLarge, false);
     }
 #undef SEER_AUTO_LAUNCH
-    hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_carry + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
-                       n_wo, carry_row, carry_val, a.y, sel);
+    if (carries)
+        hipLaunchKernelGGL(spmv_auto_fixup_kernel, dim3((n_carry + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_mp,
+                           n_wo, carry_row, carry_val, a.y, sel);
 }
 
 } // namespace seer

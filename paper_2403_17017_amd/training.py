@@ -14,7 +14,7 @@ gathering is worth its cost.  The trees are stored as the flat node arrays that
            --model paper_2403_17017_amd/selector_model.json --out eval.csv
     python -m paper_2403_17017_amd.training export-header      # trees as nested if/else in C
 
-The same sweep also feeds the multiple-iteration models (Sec. V): for every matrix
+The same sweep also feeds the multiple-iteration models (Sec. IV-E): for every matrix
 and every iteration count n of a fixed grid the label is the kernel with the smallest
 preprocessing + n * run time, the iteration count is one more known feature, and the
 feature collection is paid once.  Those three trees are stored under "iterative" and are
@@ -157,7 +157,11 @@ def measure_matrix(spec, device="cuda:0", extra=None):
     # the asynchronous path with a constant tree: its excess over the bare kernel is the
     # device-side cost of gathering and selecting
     mp_only = S.Tree.constant(S.CSR_MP)
-    row["t_auto_mp_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, mp_only, x, ys[3], ws)), 3)
+    S.set_tuning("auto_prune", 0)            # (a one-leaf tree would otherwise not gather at all)
+    try:
+        row["t_auto_mp_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, mp_only, x, ys[3], ws)), 3)
+    finally:
+        S.set_tuning("auto_prune", -1)
     # the schedules must agree with each other (a sanity check, not the parity test)
     scale = float(ys[3].abs().max().item()) + 1e-30
     row["max_disagreement"] = float(max((ys[k] - ys[3]).abs().max().item()
@@ -530,7 +534,7 @@ def iterative_report(C, tf, pred_known, pred_gath, use_gath):
 
 
 def fit_iterative(X, T, P, tf, tr, te, grid=ITER_GRID):
-    """The three trees for n products with one matrix (Sec. V): every training matrix
+    """The three trees for n products with one matrix (Sec. IV-E): every training matrix
     appears once per iteration count of the grid, labelled with the kernel of least
     preprocessing + n * run time among all kernels; folds are split by matrix."""
     def expand(sel):
@@ -794,7 +798,7 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
               f"paper_2403_17017_amd/selector_model.json --first {min(ms)} --count {len(ms)} --out eval_fresh.csv"]
     if "iterative" in m:
         it = m["iterative"]["report"]["test"]
-        L += ["", "## Models for n products with one matrix (Sec. V), held-out matrices, from sweep timings", "",
+        L += ["", "## Models for n products with one matrix (Sec. IV-E), held-out matrices, from sweep timings", "",
               "Cost of kernel k for n products: preprocessing(k) + n * run(k); the gathered path adds one "
               "feature-collection call.", "",
               "| n | best fixed kernel | classifier selection vs best fixed (aggregate) | per-matrix geomean | vs oracle | "

@@ -120,6 +120,35 @@ def random_tree(rng, n_internal, n_classes=4):
     return feat, thr, left, right, kl
 
 
+def test_tree_reachable_matches_oracle():
+    """seer_tree_reachable against the oracle's definition: random trees (also ones whose nodes
+    share children), random sizes, sizes that sit exactly on a threshold, an iteration count."""
+    rng = np.random.default_rng(404)
+    for trial in range(300):
+        feat, thr, left, right, kl = random_tree(rng, int(rng.integers(0, 60)), n_classes=8)
+        rows, cols, nnz = int(rng.integers(1, 10**7)), int(rng.integers(1, 10**7)), int(rng.integers(0, 10**8))
+        kf = S.seer_known_features(rows, cols, nnz)
+        if trial % 3 == 0:
+            kf.f[12] = float(rng.integers(1, 100))
+        want_f = np.array(list(kf.f), np.float32)
+        internal = [i for i, f in enumerate(feat) if f >= 0]
+        if internal and trial % 2 == 0:                    # put a known value exactly on a threshold
+            n = internal[int(rng.integers(len(internal)))]
+            feat[n] = int(rng.choice(O.KNOWN_FEATURES))
+            thr[n] = float(want_f[feat[n]])
+        if len(internal) > 2 and trial % 5 == 0:           # two parents, one child
+            left[internal[-1]] = left[internal[0]] if internal[0] != internal[-1] else left[internal[-1]]
+        tree = S.Tree(feat, thr, left, right, kl, n_classes=8)
+        assert S.seer_tree_reachable(tree, kf) == O.reachable_classes(want_f, feat, thr, left, right, kl), trial
+    # a tree over known features only: exactly what seer_select answers
+    t = S.Tree([0, 2, -1, -1, -1], [1000.0, 5e4, 0, 0, 0], [1, 2, -1, -1, -1], [4, 3, -1, -1, -1], [-1, -1, 0, 1, 2])
+    kf = S.seer_known_features(1000, 10, 50001)
+    assert S.seer_tree_reachable(t, kf) == {S.seer_select(kf, t)} == {1}
+    with pytest.raises(S.SeerError):                        # malformed: child out of range
+        S.seer_tree_reachable(S.Tree([0, -1], [1.0, 0], [1, -1], [7, -1], [-1, 0]), kf)
+
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_select_bit_exact_vs_oracle(seed):
     rng = np.random.default_rng(seed)

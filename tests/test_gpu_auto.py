@@ -18,6 +18,34 @@ REAL_TREE = ([6, 3, 0, -1, -1, -1, -1], [50.0, 8.0, 20000.0, 0, 0, 0, 0],
              [1, 2, 3, -1, -1, -1, -1], [6, 5, 4, -1, -1, -1, -1], [-1, -1, -1, 0, 2, 1, 3])
 
 
+def check_record(A, tree, f, kid, what):
+    """The record seer_spmv_auto left: the kernel id is the oracle's walk over the full feature
+    vector; the features are the gathered ones, bit for bit -- unless the known features alone
+    leave one kernel reachable (the oracle's definition), in which case nothing was gathered
+    and the record holds the known features and the mark."""
+    want = O.features(A.rows, A.cols, A.row_ptr)
+    assert kid == O.select(want["f"], *tree.arrays), what
+    kf = O.known_features(A.rows, A.cols, A.nnz)
+    reach = O.reachable_classes(kf, *tree.arrays)
+    assert kid in reach, what
+    if len(reach) == 1:
+        assert int(f.max_len) == int(f.min_len) == int(f.empty_rows) == -1, f"{what}: gathered although decided"
+        assert (int(f.rows), int(f.cols), int(f.nnz)) == (A.rows, A.cols, A.nnz), what
+        assert f.vector().tobytes() == kf.tobytes(), what
+    else:
+        assert_features_equal(f, want, what)
+    return len(reach) == 1
+
+
+@pytest.fixture
+def no_pruning():
+    """Every schedule counts as reachable, features are always gathered (the tests of the
+    device-side derivation and of the combined kernel force schedules with one-leaf trees)."""
+    S.set_tuning("auto_prune", 0)
+    yield
+    S.set_tuning("auto_prune", -1)
+
+
 def run_auto(dA, tree, xd, rows, ws):
     import torch
     y = torch.full((max(rows, 1),), float("nan"), dtype=torch.float32, device="cuda:0")
@@ -36,25 +64,68 @@ def cases():
     return out
 
 
+@pytest.mark.parametrize("prune", [1, 0])
 @pytest.mark.parametrize("forced", [0, 1, 2, 3, 4, "tree"])
-def test_auto_matches_oracle_and_three_call_path(cases, forced):
+def test_auto_matches_oracle_and_three_call_path(cases, forced, prune):
     import torch
     tree = S.Tree(*REAL_TREE) if forced == "tree" else S.Tree.constant(forced)
+    S.set_tuning("auto_prune", prune)
+    try:
+        for A, x, y_ref, bound in cases:
+            announce(f"auto path tree={forced} prune={prune} {A.name} rows={A.rows} nnz={A.nnz}")
+            dA = upload(A)
+            xd = torch.from_numpy(x).cuda()
+            ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+            y, f, kid = run_auto(dA, tree, xd, A.rows, ws)
+            want_f = O.features(A.rows, A.cols, A.row_ptr)
+            if prune:
+                decided = check_record(A, tree, f, kid, f"auto record {A.name}")
+                assert decided == (forced != "tree" or len(O.reachable_classes(
+                    O.known_features(A.rows, A.cols, A.nnz), *tree.arrays)) == 1)
+            else:
+                assert_features_equal(f, want_f, f"auto features {A.name}")
+                assert kid == O.select(want_f["f"], *tree.arrays)
+            assert_parity(y, y_ref, bound, f"auto (kernel {kid}) on {A.name}")
+            y3 = run_spmv(kid, dA, xd, A.rows)
+            assert y.tobytes() == y3.tobytes(), f"auto and seer_spmv({kid}) differ on {A.name}"
+            # and the three-call path agrees on the features and the id
+            f3 = S.seer_features(dA)
+            assert f3.vector().tobytes() == want_f["f"].tobytes() and S.seer_select(f3, tree) == kid
+    finally:
+        S.set_tuning("auto_prune", -1)
+
+
+def test_pruning_changes_nothing_but_the_launches(cases):
+    """Trees that mix known and gathered features (so that some matrices leave one kernel, some
+    a few, some all): with and without pruning the kernel id and y are the same bits, and the
+    pruned call's record says "decided" exactly where the oracle's reachable set has one class."""
+    import torch
+    trees = [
+        S.Tree(*REAL_TREE),
+        # rows <= 5000 ? TM : (nnz <= 200000 ? (max_len <= 40 ? BM : WO) : (var_len <= 9 ? WM : MP))
+        S.Tree([0, -1, 2, 4, 6, -1, -1, -1, -1], [5000.0, 0, 200000.0, 40.0, 9.0, 0, 0, 0, 0],
+               [1, -1, 3, 5, 7, -1, -1, -1, -1], [2, -1, 4, 6, 8, -1, -1, -1, -1], [-1, 0, -1, -1, -1, 2, 4, 1, 3]),
+        # mean_len <= 6 ? (empty_frac <= 0.1 ? TM : BM) : WM     -- never merge path / nonzero split
+        S.Tree([3, 7, -1, -1, -1], [6.0, 0.1, 0, 0, 0], [1, 3, -1, -1, -1], [2, 4, -1, -1, -1], [-1, -1, 1, 0, 2]),
+    ]
+    decided_seen, undecided_seen = 0, 0
     for A, x, y_ref, bound in cases:
-        announce(f"auto path tree={forced} {A.name} rows={A.rows} nnz={A.nnz}")
-        dA = upload(A)
-        xd = torch.from_numpy(x).cuda()
+        dA, xd = upload(A), torch.from_numpy(x).cuda()
         ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
-        y, f, kid = run_auto(dA, tree, xd, A.rows, ws)
-        want_f = O.features(A.rows, A.cols, A.row_ptr)
-        assert_features_equal(f, want_f, f"auto features {A.name}")
-        assert kid == O.select(want_f["f"], *tree.arrays)
-        assert_parity(y, y_ref, bound, f"auto (kernel {kid}) on {A.name}")
-        y3 = run_spmv(kid, dA, xd, A.rows)
-        assert y.tobytes() == y3.tobytes(), f"auto and seer_spmv({kid}) differ on {A.name}"
-        # and the three-call path agrees on the features and the id
-        f3 = S.seer_features(dA)
-        assert f3.vector().tobytes() == f.vector().tobytes() and S.seer_select(f3, tree) == kid
+        for ti, tree in enumerate(trees):
+            announce(f"pruned against unpruned, tree #{ti}, {A.name} rows={A.rows} nnz={A.nnz}")
+            y1, f1, k1 = run_auto(dA, tree, xd, A.rows, ws)
+            decided = check_record(A, tree, f1, k1, f"tree #{ti} on {A.name}")
+            S.set_tuning("auto_prune", 0)
+            try:
+                y0, f0, k0 = run_auto(dA, tree, xd, A.rows, ws)
+            finally:
+                S.set_tuning("auto_prune", -1)
+            assert k0 == k1 and y0.tobytes() == y1.tobytes(), f"tree #{ti} on {A.name}: pruning changed the result"
+            assert_parity(y1, y_ref, bound, f"pruned auto tree #{ti} (kernel {k1}) on {A.name}")
+            decided_seen += decided
+            undecided_seen += not decided
+    assert decided_seen > 0 and undecided_seen > 0
 
 
 def test_auto_with_trees_of_every_depth(cases):
@@ -165,7 +236,7 @@ def test_auto_status_codes():
         S.seer_spmv_auto_result(fresh)        # nothing has selected into this workspace
 
 
-def test_auto_wide_integer_features():
+def test_auto_wide_integer_features(no_pruning):
     """rows * sum(len^2) beyond 2^64: the device's 128-bit variance numerator and its
     conversion to fp64 against exact Python integers (all values 1, x = 1, so y = len)."""
     import torch
@@ -204,11 +275,16 @@ def test_auto_wm_when_its_tiles_outnumber_the_grid():
         xd = torch.from_numpy(x).cuda()
         ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
         for forced in (S.CSR_WM, S.CSR_TM, S.CSR_WO):
-            announce(f"auto path, capped CSR,WM share: kernel {forced} on {A.name} rows={A.rows} nnz={A.nnz}")
-            y, f, kid = run_auto(dA, S.Tree.constant(forced), xd, A.rows, ws)
-            assert kid == forced
-            assert_parity(y, y_ref, bound, f"auto kernel {forced} on {A.name}")
-            assert np.array_equal(y, run_spmv(forced, dA, xd, A.rows))
+            for prune in (0, 1):      # 0: the grid is sized for all five schedules; 1: for the forced one alone
+                announce(f"auto path, capped CSR,WM share: kernel {forced} prune={prune} on {A.name} rows={A.rows} nnz={A.nnz}")
+                S.set_tuning("auto_prune", prune)
+                try:
+                    y, f, kid = run_auto(dA, S.Tree.constant(forced), xd, A.rows, ws)
+                finally:
+                    S.set_tuning("auto_prune", -1)
+                assert kid == forced
+                assert_parity(y, y_ref, bound, f"auto kernel {forced} on {A.name}")
+                assert np.array_equal(y, run_spmv(forced, dA, xd, A.rows))
 
 
 def test_classifier_selection_path(cases):

@@ -157,7 +157,16 @@ def test_nnz_at_the_int32_limit():
         announce(f"int32 limit: combined kernel answering {S.kernel_name(kid)}")
         ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
         ya = torch.full((A.rows,), float("nan"), device="cuda:0")
-        S.seer_spmv_auto(dA, S.Tree.constant(kid), xd, ya, ws)
+        S.set_tuning("auto_prune", 0)          # gather although the one-leaf tree needs no features
+        try:
+            S.seer_spmv_auto(dA, S.Tree.constant(kid), xd, ya, ws)
+        finally:
+            S.set_tuning("auto_prune", -1)
         f_dev, kid_dev = S.seer_spmv_auto_result(ws)
         assert kid_dev == kid and f_dev.vector().tobytes() == want["f"].tobytes()
+        assert np.array_equal(ya.cpu().numpy(), ys[kid])
+        ya.fill_(float("nan"))                  # and decided on the host, nothing gathered
+        S.seer_spmv_auto(dA, S.Tree.constant(kid), xd, ya, ws)
+        f_dev, kid_dev = S.seer_spmv_auto_result(ws)
+        assert kid_dev == kid and int(f_dev.max_len) == -1
         assert np.array_equal(ya.cpu().numpy(), ys[kid])

@@ -195,7 +195,7 @@ def test_model_select_hand_cases():
 
 
 def test_iteration_count_is_a_known_feature():
-    """Sec. V (multiple iterations): the number of iterations is available to every
+    """Sec. IV-E (multiple iterations): the number of iterations is available to every
     predictor.  It is the last entry of both vectors, 1 unless stated, and a tree may
     split on it."""
     rp = rp_of([1, 2, 3])
@@ -210,3 +210,57 @@ def test_iteration_count_is_a_known_feature():
     fg = O.features(3, 4, rp, iterations=19)["f"]
     assert O.model_select(3, 4, 6, fg, selector, known, known, iterations=18) == (0, 4)
     assert O.model_select(3, 4, 6, fg, selector, known, known, iterations=19) == (0, 5)
+
+
+# ---------------------------------------------------------------- reachable classes
+def test_reachable_classes_hand_cases():
+    # rows <= 100 ? (var_len <= 5 ? 2 : 3) : (nnz <= 1000 ? 1 : (max_len <= 9 ? 1 : 4))
+    tree = ([0, 6, 2, -1, -1, -1, 4, -1, -1], [100.0, 5.0, 1000.0, 0, 0, 0, 9.0, 0, 0],
+            [1, 3, 5, -1, -1, -1, 7, -1, -1], [2, 4, 6, -1, -1, -1, 8, -1, -1],
+            [-1, -1, -1, 2, 3, 1, -1, 1, 4])
+    assert O.reachable_classes(O.known_features(100, 7, 50), *tree) == {2, 3}       # on the threshold: left
+    assert O.reachable_classes(O.known_features(101, 7, 1000), *tree) == {1}        # known all the way down
+    assert O.reachable_classes(O.known_features(101, 7, 1001), *tree) == {1, 4}
+    # both children of a gathered test end in the same class: nothing to gather for
+    same = ([6, -1, -1], [5.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 3, 3])
+    assert O.reachable_classes(O.known_features(5, 5, 5), *same) == {3}
+    assert O.reachable_classes(O.known_features(5, 5, 5), [-1], [0.0], [-1], [-1], [2]) == {2}
+
+
+def test_reachable_classes_never_miss_what_select_returns():
+    """Brute force: whatever the gathered entries are, the class select returns lies in the
+    set; a tree over known entries alone leaves exactly that class; a tree over gathered
+    entries alone leaves every class some vector reaches (each leaf is shown reachable by a
+    vector built from its path where the path's tests on one entry do not contradict)."""
+    from test_abi_host import random_tree
+    rng = np.random.default_rng(31)
+    gathered_idx = [i for i in range(O.NUM_FEATURES) if i not in O.KNOWN_FEATURES]
+    for trial in range(60):
+        arrs = random_tree(rng, int(rng.integers(1, 40)), n_classes=5)
+        rows, cols = int(rng.integers(1, 10**6)), int(rng.integers(1, 10**6))
+        nnz = int(rng.integers(0, 10**7))
+        kf = O.known_features(rows, cols, nnz)
+        reach = O.reachable_classes(kf, *arrs)
+        hit = set()
+        for _ in range(200):
+            f = kf.copy()
+            f[gathered_idx] = np.exp(rng.normal(2, 3, len(gathered_idx))).astype(np.float32)
+            k = O.select(f, *arrs)
+            assert k in reach, (trial, k, reach)
+            hit.add(k)
+        assert hit <= reach
+        # only known entries tested: the set is what select answers
+        feat = np.array(arrs[0])
+        known_only = [int(rng.choice(O.KNOWN_FEATURES)) if v >= 0 else -1 for v in feat]
+        assert O.reachable_classes(kf, known_only, *arrs[1:]) == {O.select(kf, known_only, *arrs[1:])}
+        # only gathered entries tested: every leaf is possible
+        gathered_only = [int(rng.choice(gathered_idx)) if v >= 0 else -1 for v in feat]
+        leaves = set()
+        stack = [0]
+        while stack:
+            n = stack.pop()
+            if gathered_only[n] < 0:
+                leaves.add(arrs[4][n])
+            else:
+                stack += [arrs[2][n], arrs[3][n]]
+        assert O.reachable_classes(kf, gathered_only, *arrs[1:]) == leaves
