@@ -66,26 +66,57 @@ def load_model():
     return S.Model(t), {}, "hand-written default (no trained model file)"
 
 
-def load_traffic_summary(workload, kernel):
-    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc
-    (FETCH_SIZE and WRITE_SIZE, calibrated against the plain copy kernel).  Counters
-    cannot be collected from inside a timed run, so the figure comes from the committed
-    summary of that separate run; None if there is none for this workload and kernel."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
-    if not os.path.exists(path):
-        return None
+def kernel_source_sha16():
+    """Fingerprint of the device code (every file under csrc/): a profile summary taken from
+    other sources is stale."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2403_17017_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hiph", ".h")):
+            with open(os.path.join(d, name), "rb") as fh:
+                h.update(name.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
+def _read_summary(path):
     vals = {}
     with open(path) as fh:
         for ln in fh:
             if ":" in ln and not ln.startswith("#"):
                 k, v = ln.split(":", 1)
                 vals[k.strip()] = v.strip()
-    if vals.get("kernel") != kernel:
-        return None
-    try:
-        return int(float(vals["hbm_bytes_per_launch"]))
-    except (KeyError, ValueError):
-        return None
+    return vals
+
+
+def load_profile_summaries(workload, kernel):
+    """What the committed rocprofv3 summaries say about the dominant kernel of this workload:
+    HBM bytes per launch (two --pmc runs, FETCH_SIZE and WRITE_SIZE, calibrated against the
+    plain copy kernel: counters cannot be read from inside a timed run) and the kernel-trace
+    average duration.  Each summary names the kernel it was taken for and carries the
+    fingerprint of the device sources it was taken from; a summary for another kernel counts
+    as absent, one from other sources is reported as stale and its traffic figure withheld."""
+    out = {"traffic": None, "traffic_file": None, "traffic_stale": None,
+           "profile_avg_launch_us": None, "profile_file": None, "profile_stale": None}
+    sha = kernel_source_sha16()
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if os.path.exists(tpath):
+        v = _read_summary(tpath)
+        if v.get("kernel") == kernel and "hbm_bytes_per_launch" in v:
+            out["traffic_file"] = os.path.relpath(tpath, ROOT)
+            out["traffic_stale"] = v.get("source_sha16") != sha
+            if not out["traffic_stale"]:
+                out["traffic"] = int(float(v["hbm_bytes_per_launch"]))
+            else:
+                out["traffic_of_stale_summary"] = int(float(v["hbm_bytes_per_launch"]))
+    kpath = os.path.join(ROOT, "profiles", f"kernel_trace_{workload}.txt")
+    if os.path.exists(kpath):
+        v = _read_summary(kpath)
+        if v.get("kernel") == kernel and "average_ns" in v:
+            out["profile_file"] = os.path.relpath(kpath, ROOT)
+            out["profile_avg_launch_us"] = round(float(v["average_ns"]) * 1e-3, 3)
+            out["profile_stale"] = v.get("source_sha16") != sha
+    return out
 
 
 class Rotation:
@@ -177,6 +208,26 @@ def stream_copy_ceiling(nbytes=1 << 31, reps=10):
     return 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def stream_read_ceiling(nbytes=1 << 31, reps=10):
+    """Rate of the library's read-only streaming kernel over a buffer far beyond the caches:
+    the attainable rate of the access pattern an SpMV mostly is."""
+    import torch
+
+    import paper_2403_17017_amd as S
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+    out = torch.zeros(64, dtype=torch.int32, device="cuda:0")
+    for _ in range(2):
+        S.seer_stream_sum(a, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        S.seer_stream_sum(a, out)
+    e1.record()
+    torch.cuda.synchronize()
+    return nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def random_gather_ceiling(nnz, cols, reps=10):
     """Rate of the library's bare gather kernel (streamed indices and values, no rows) with
     uniformly random indices into a vector of `cols` floats: what a product with random
@@ -243,6 +294,56 @@ def selector_eval(model, meta, count):
     }
 
 
+BASELINE_CONFIGS = (("fixed16_4096", "BASELINE config 1"), ("laplace5_1024", "BASELINE config 2"),
+                    ("zipf1.6_2M", "BASELINE config 3 as stated (Zipf 1.6: 4.8e8 nonzeros)"),
+                    ("zipf1.85_2M", "BASELINE config 3 at its stated size (Zipf 1.85: 4.7e7 nonzeros)"),
+                    ("empty30_poisson4_8M", "BASELINE config 4"))
+MAX_SETS = 2048
+
+
+def config_row(name, what, tree, rot=None):
+    """One BASELINE config under the cold protocol: every kernel without preprocessing
+    (kernel time per launch, HIP graph replay on rotating copies), what seer_spmv_auto selects
+    with the shipped tree, and the whole step."""
+    import torch
+
+    import paper_2403_17017_amd as S
+    from workloads.csr_gen import dense_vector, model_bytes
+    if rot is None:
+        A = make_workload(name)
+        x = dense_vector(A.cols, 12345)
+        mb = model_bytes(A.rows, A.cols, A.nnz)
+        rot = Rotation(A, x, min(MAX_SETS, max(1, math.ceil(COLD_BYTES / mb)) + 1))
+        del A, x
+    d0 = rot[0][0]
+    mb = 8 * d0.nnz + 4 * (d0.rows + 1) + 4 * d0.cols + 4 * d0.rows
+    reps = max(rot.n, 20) if mb < 100e6 else (5 if mb < 1e9 else 3)
+    per = {}
+    for k in range(S.NUM_DIRECT_KERNELS):
+        per[S.kernel_name(k)] = round(time_spmv_graph(k, rot, reps, replays=2 if mb > 1e9 else 3), 2)
+
+    def enqueue_steps():
+        for i in range(reps):
+            d, xd, y, ws = rot[i]
+            S.seer_spmv_auto(d, tree, xd, y, ws)
+    from paper_2403_17017_amd.training import time_graph_us
+    step = time_graph_us(enqueue_steps, warmup=1, reps=1) / reps
+    _, kid = S.seer_spmv_auto_result(rot[0][3])
+    sel = S.kernel_name(kid)
+    best = min(per, key=per.get)
+    gbps = lambda us: round(mb / (us * 1e-6) / 1e9, 1)
+    return {
+        "workload": name, "what": what, "rows": d0.rows, "cols": d0.cols, "nnz": d0.nnz, "model_bytes": mb,
+        "cold_copies": rot.n, "per_kernel_cold_us": per,
+        "selected_kernel": sel, "selected_cold_us": per[sel], "selected_gbps": gbps(per[sel]),
+        "selected_frac_of_hbm_peak": round(gbps(per[sel]) / HBM_PEAK_GBPS, 4),
+        "best_fixed_kernel": best, "best_fixed_cold_us": per[best], "best_fixed_gbps": gbps(per[best]),
+        "best_fixed_frac_of_hbm_peak": round(gbps(per[best]) / HBM_PEAK_GBPS, 4),
+        "step_us_gpu_timeline": round(step, 2), "step_gbps": gbps(step),
+        "meets_60pct_of_hbm_peak": bool(gbps(per[best]) >= 0.6 * HBM_PEAK_GBPS),
+    }
+
+
 def cpu_baseline(A, x, tree, budget_s=10.0):
     """The oracle's whole step (features, tree walk, SpMV) on the host, single thread."""
     from oracle import seer_oracle as O
@@ -290,6 +391,8 @@ def main():
     ap.add_argument("--workload", default="laplace5_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel table and copy ceiling")
+    ap.add_argument("--no-configs", dest="configs", action="store_false",
+                    help="skip the table of every BASELINE config in extras")
     ap.add_argument("--selector-matrices", type=int, default=60,
                     help="held-out sweep matrices for the selector figures in extras (0 = skip)")
     args = ap.parse_args()
@@ -348,7 +451,7 @@ def main():
     # events, so that the figure is kernel time, free of launch gaps.
     spmv_avg_us = time_spmv_graph(kid, rot, args.steps)
     achieved = mb / (spmv_avg_us * 1e-6) / 1e9
-    traffic = load_traffic_summary(args.workload, S.kernel_name(kid))
+    prof = load_profile_summaries(args.workload, S.kernel_name(kid))
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
@@ -360,8 +463,10 @@ def main():
                    "model_bytes_per_step": mb, "cache_protocol": f"cold: rotates {n_sets} copies of (A,x,y), "
                    f"{n_sets * mb / 2**30:.2f} GiB", "selected_kernel": S.kernel_name(kid), "tree": tree_note},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": prof["traffic"],
                      "kernel": S.kernel_name(kid), "avg_launch_us": round(spmv_avg_us, 3),
+                     "meets_60pct_of_hbm_peak": bool(achieved >= 0.6 * HBM_PEAK_GBPS),
+                     "profiles": {k: v for k, v in prof.items() if k != "traffic"},
                      "how": f"{args.steps} launches of the selected kernel on the rotating cold copies, "
                             "one HIP graph replay bracketed by HIP events",
                      "algorithmic_bytes_per_launch": mb},
@@ -468,6 +573,7 @@ def main():
                     "n_products_best_direct_kernel_us": round(n_it * best_direct, 1)}
         del warm
         extras["stream_copy_ceiling_gbps"] = round(stream_copy_ceiling(), 1)
+        extras["read_ceiling_gbps"] = round(stream_read_ceiling(), 1)
         # warm, like the ceiling probe (which re-reads one set of buffers)
         extras["gathers"] = {
             "x_mb": round(A.cols * 4 / 1e6, 2),
@@ -475,6 +581,15 @@ def main():
             "selected_kernel_per_s": round(A.nnz / (extras["per_kernel_warm_us"][S.kernel_name(kid)] * 1e-6), -6)}
         if model_meta.get("test_matrices") and args.selector_matrices > 0:
             extras["selector_on_held_out_matrices"] = selector_eval(model, model_meta, args.selector_matrices)
+        if args.configs:
+            # every BASELINE config under the same cold protocol (this workload's copies are reused)
+            extras["configs"] = []
+            for name, what in BASELINE_CONFIGS:
+                if name == args.workload:
+                    extras["configs"].append(config_row(name, what, tree, rot))
+                    continue
+                torch.cuda.empty_cache()
+                extras["configs"].append(config_row(name, what, tree))
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

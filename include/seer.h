@@ -242,7 +242,12 @@ typedef struct {
     const seer_tree *gathered;
 } seer_model;
 
-/* Runtime inference with the classifier-selection model (Sec. III-B): the selector is
+/* model == NULL in seer_spmv_model and seer_spmv_plan selects the models the library was built
+ * with: the trained trees of selector_model.json emitted as nested if/else code
+ * (selector_model_generated.h, the deployment form of Sec. III-D) and compiled in; they choose
+ * exactly as the same trees passed as node arrays would.
+ *
+ * Runtime inference with the classifier-selection model (Sec. III-B): the selector is
  * evaluated on the host at no GPU cost; on 0 the known model's kernel is launched
  * directly (seer_spmv), on 1 the features are gathered and the gathered model is
  * applied on the device (seer_spmv_auto).  Asynchronous on `stream` either way.
@@ -301,8 +306,10 @@ size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
  * writes cols[j * R + i] / vals[j * R + i] = the j-th entry of row i in CSR order, or
  * -1 / 0 where the row is shorter, R = roundup(rows, 64), cols first, vals at half of
  * seer_ell_plan_bytes(rows, longest row).  If plan_mem is too small the call returns
- * SEER_EWORKSPACE with plan->device_bytes = the bytes needed; SEER_EINVAL if the format
- * is not applicable.
+ * SEER_EWORKSPACE and stores the bytes needed in plan->device_bytes, the one output written
+ * on an error (the rest of *plan stays as it was): seer_features_workspace_bytes(rows) while
+ * plan_mem cannot even hold the reduction's workspace, the size of the ELL form after that,
+ * so sizing may take two rounds.  SEER_EINVAL if the format is not applicable.
  * For SEER_COO_WM: writes the row index of every nonzero, in CSR order (int32 [nnz]).
  * HOST-SYNCHRONOUS: returns after the pass has finished (it reads back whether any row
  * is split, or the longest row).  plan_mem: DEVICE, 16-byte aligned, >= seer_plan_bytes();
@@ -397,6 +404,13 @@ int seer_stream_sum(const void *src, size_t n_words, void *out64, void *stream);
  * (meaningless).  Asynchronous. */
 int seer_gather_sum(const int32_t *idx, const float *val, size_t n, const float *x, void *out64,
                     void *stream);
+
+/* Measurement aid: what the host part of seer_spmv_model costs -- the known features, the
+ * walk of the classifier-selection tree and, where it answers 0, of the known model (Sec.
+ * III-B: the cost of inference is small but accounted for).  Runs exactly that `reps` times
+ * and stores the mean wall-clock nanoseconds per decision in *ns.  HOST only. */
+int seer_model_host_ns(const seer_model *model, int32_t rows, int32_t cols, int32_t nnz, int32_t reps,
+                       double *ns);
 
 int seer_num_kernels(void);
 const char *seer_kernel_name(int kernel_id); /* "CSR,TM" ...; NULL if out of range  */

@@ -117,6 +117,8 @@ def lib():
         L.seer_spmv_model.argtypes = [C.POINTER(seer_csr), C.POINTER(seer_model), vp, vp, vp, sz, vp,
                                       C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.seer_spmv_model.restype = C.c_int
+        L.seer_model_host_ns.argtypes = [C.POINTER(seer_model), i32, i32, i32, i32, C.POINTER(C.c_double)]
+        L.seer_model_host_ns.restype = C.c_int
         L.seer_plan_bytes.argtypes = [C.c_int, i32, i32]
         L.seer_plan_bytes.restype = sz
         L.seer_ell_plan_bytes.argtypes = [i32, i32]
@@ -238,6 +240,20 @@ def alloc_workspace(nbytes: int, device="cuda:0"):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def _temporary_workspace(nbytes: int, device, stream):
+    """Scratch for one asynchronous call, dropped by the caller as soon as the call has been
+    enqueued: the allocator must not hand the block to other work before `stream` has run
+    the kernels that use it.  On torch's current stream that is the allocator's own rule; a
+    torch stream other than the current one is told with record_stream; a raw stream handle
+    cannot be, so such a caller owns the workspace (as the C header asks of every caller)."""
+    ws = alloc_workspace(nbytes, device)
+    if stream is not None:
+        if not hasattr(stream, "cuda_stream"):
+            raise ValueError("pass workspace= when stream is a raw handle: a temporary one cannot be kept alive for it")
+        ws.record_stream(stream)
+    return ws
+
+
 def seer_features(A: DeviceCSR, workspace=None, stream=None) -> seer_features_t:
     """Gathered features of A (runs the reduction kernel and waits for it)."""
     if workspace is None:
@@ -306,7 +322,7 @@ def seer_spmv(kernel_id: int, A: DeviceCSR, x, y, workspace=None, stream=None) -
     assert x.numel() >= A.cols and y.numel() >= A.rows
     need = spmv_workspace_bytes(kernel_id, A.rows, A.nnz) if 0 <= kernel_id < NUM_KERNELS else 0
     if need and workspace is None:
-        workspace = alloc_workspace(need, A.row_ptr.device)
+        workspace = _temporary_workspace(need, A.row_ptr.device, stream)
     cs = A.c_struct()
     rc = lib().seer_spmv(int(kernel_id), C.byref(cs), x.data_ptr(), y.data_ptr(),
                          workspace.data_ptr() if workspace is not None else None,
@@ -400,6 +416,15 @@ def seer_spmv_model(A: DeviceCSR, model: Model, x, y, workspace, stream=None):
     return int(path.value), int(kid.value)
 
 
+def seer_model_host_ns(model: Model, rows: int, cols: int, nnz: int, reps: int = 2000) -> float:
+    """Mean wall-clock nanoseconds of the host-side decision of seer_spmv_model (measurement aid)."""
+    ns = C.c_double(0.0)
+    rc = lib().seer_model_host_ns(C.byref(model.c), rows, cols, nnz, reps, C.byref(ns))
+    if rc:
+        raise SeerError(rc, "seer_model_host_ns")
+    return float(ns.value)
+
+
 class Plan:
     """A prepared kernel for one matrix: the host-side record plus the device memory
     the preprocessing wrote (kept alive here)."""
@@ -469,7 +494,7 @@ def seer_spmv_prepared(plan: Plan, A: DeviceCSR, x, y, workspace=None, stream=No
     """y = A x with a prepared plan; asynchronous on the stream."""
     need = spmv_prepared_workspace_bytes(plan)
     if need and workspace is None:
-        workspace = alloc_workspace(need, A.row_ptr.device)
+        workspace = _temporary_workspace(need, A.row_ptr.device, stream)
     cs = A.c_struct()
     rc = lib().seer_spmv_prepared(C.byref(plan.c), C.byref(cs), x.data_ptr(), y.data_ptr(),
                                   workspace.data_ptr() if workspace is not None else None,

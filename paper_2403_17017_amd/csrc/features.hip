@@ -24,12 +24,26 @@ __global__ __launch_bounds__(kFeatWG) void features_kernel(
     }
 }
 
-// Plain streaming copy (measurement aid): one 16-byte load and store per lane and step.
+// Plain streaming copy (measurement aid): four 16-byte loads in flight per lane and step,
+// loads and stores with the streaming hint (nothing is used twice).  With one load and
+// one plain store per step the same copy ran at 4.6 TB/s, below what CSR,TM streams.
 __global__ __launch_bounds__(kWG) void stream_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
                                                           size_t n_vec)
 {
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const u4 *s = reinterpret_cast<const u4 *>(src);
+    u4 *d = reinterpret_cast<u4 *>(dst);
     const size_t stride = (size_t)gridDim.x * kWG;
-    for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n_vec; i += stride) dst[i] = src[i];
+    size_t i = (size_t)blockIdx.x * kWG + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        const u4 a = __builtin_nontemporal_load(s + i), b = __builtin_nontemporal_load(s + i + stride);
+        const u4 c = __builtin_nontemporal_load(s + i + 2 * stride), e = __builtin_nontemporal_load(s + i + 3 * stride);
+        __builtin_nontemporal_store(a, d + i);
+        __builtin_nontemporal_store(b, d + i + stride);
+        __builtin_nontemporal_store(c, d + i + 2 * stride);
+        __builtin_nontemporal_store(e, d + i + 3 * stride);
+    }
+    for (; i < n_vec; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
 }
 
 __global__ void stream_copy_tail_kernel(uint32_t *__restrict__ dst, const uint32_t *__restrict__ src, size_t from,

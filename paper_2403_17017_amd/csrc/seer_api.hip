@@ -3,6 +3,9 @@
 // decision-tree walk.  No device memory is allocated here.
 #include "../../include/seer.h"
 #include "launch.h"
+// The trained models in the form they are deployed in (Sec. III-D): nested if/else code
+// generated from the fitted trees; what the entry points use when the caller passes no model.
+#include "../selector_model_generated.h"
 
 #include <algorithm>
 #include <atomic>
@@ -680,12 +683,19 @@ int seer_spmv_auto_static(const seer_csr *A, const seer_tree *tree, const float 
 int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, float *y, void *workspace,
                     size_t workspace_bytes, void *stream, int *path, int *kernel_id)
 {
-    if (!A || !model || !model->gathered) return SEER_EINVAL;
-    if (model->selector && !model->known) return SEER_EINVAL;
+    if (!A) return SEER_EINVAL;
+    if (model && (!model->gathered || (model->selector && !model->known))) return SEER_EINVAL;
     if (A->rows < 0 || A->cols < 0 || A->nnz < 0) return SEER_EINVAL;
     int use_gathered = 1;
     int kid = -1;
-    if (model->selector) {
+    const seer_tree *gathered = model ? model->gathered : &seer_model_gathered_tree;
+    if (!model) {                       // the built-in models: generated code for the two host-side trees
+        seer_features_t kf;
+        const int rc = seer_known_features(A->rows, A->cols, A->nnz, &kf);
+        if (rc != SEER_OK) return rc;
+        use_gathered = seer_model_selector(kf.f) != 0;
+        if (!use_gathered) kid = seer_model_known(kf.f);
+    } else if (model->selector) {
         seer_features_t kf;
         int rc = seer_known_features(A->rows, A->cols, A->nnz, &kf);
         if (rc != SEER_OK) return rc;
@@ -696,17 +706,36 @@ int seer_spmv_model(const seer_csr *A, const seer_model *model, const float *x, 
             if (model->known->n_classes > SEER_NUM_KERNELS) return SEER_ETREE;
             rc = seer_select(&kf, model->known, &kid);
             if (rc != SEER_OK) return rc;
-            if (kid >= SEER_NUM_DIRECT_KERNELS) return SEER_ETREE;   // needs preprocessing: seer_spmv_plan
         }
     }
+    if (!use_gathered && (kid < 0 || kid >= SEER_NUM_DIRECT_KERNELS)) return SEER_ETREE;   // needs preprocessing: seer_spmv_plan
     if (A->rows > 0 && (!workspace || !aligned16(workspace) ||
                         workspace_bytes < auto_workspace_bytes(A->rows, A->nnz)))
         return SEER_EWORKSPACE;
-    const int rc = use_gathered ? seer_spmv_auto(A, model->gathered, x, y, workspace, workspace_bytes, stream)
+    const int rc = use_gathered ? seer_spmv_auto(A, gathered, x, y, workspace, workspace_bytes, stream)
                                 : seer_spmv(kid, A, x, y, workspace, workspace_bytes, stream);
     if (rc != SEER_OK) return rc;
     if (path) *path = use_gathered;
     if (kernel_id) *kernel_id = kid;
+    return SEER_OK;
+}
+
+int seer_model_host_ns(const seer_model *model, int32_t rows, int32_t cols, int32_t nnz, int32_t reps, double *ns)
+{
+    if (!model || !model->selector || !model->known || !ns || reps < 1) return SEER_EINVAL;
+    volatile int sink = 0;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int32_t i = 0; i < reps; ++i) {
+        seer_features_t kf;
+        int use_gathered = 1, kid = -1;
+        int rc = seer_known_features(rows, cols, nnz, &kf);
+        if (rc == SEER_OK) rc = seer_select(&kf, model->selector, &use_gathered);
+        if (rc == SEER_OK && !use_gathered) rc = seer_select(&kf, model->known, &kid);
+        if (rc != SEER_OK) return rc;
+        sink = sink + use_gathered + kid;
+    }
+    const auto t1 = std::chrono::steady_clock::now();
+    *ns = std::chrono::duration<double, std::nano>(t1 - t0).count() / (double)reps;
     return SEER_OK;
 }
 
@@ -867,6 +896,11 @@ static int prepare_ell(const seer_csr *A, void *plan_mem, size_t plan_bytes, voi
 {
     if (!plan_mem || !aligned16(plan_mem)) return SEER_EWORKSPACE;
     if (max_len < 0) {
+        // the longest row is found with plan_mem as the reduction's workspace: it must hold that first
+        if (plan_bytes < features_workspace_bytes(A->rows)) {
+            plan->device_bytes = features_workspace_bytes(A->rows);
+            return SEER_EWORKSPACE;
+        }
         seer_features_t f;
         const int rc = seer_features(A, &f, plan_mem, plan_bytes, stream);
         if (rc != SEER_OK) return rc;
@@ -887,13 +921,10 @@ static int prepare_ell(const seer_csr *A, void *plan_mem, size_t plan_bytes, voi
     return SEER_OK;
 }
 
-int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream,
-                      seer_plan *plan)
+// seer_spmv_prepare into a plan of the library's own; the caller's is written on success only.
+static int prepare_into(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream,
+                        seer_plan *plan)
 {
-    if (!plan) return SEER_EINVAL;
-    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS) return SEER_EKERNEL;
-    const int rc = check_csr(A, true);
-    if (rc != SEER_OK) return rc;
     std::memset(plan, 0, sizeof *plan);
     plan->kernel_id = kernel_id;
     plan->rows = A->rows;
@@ -932,6 +963,20 @@ int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t p
     plan->device = plan_mem;
     plan->device_bytes = need;
     return SEER_OK;
+}
+
+int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream,
+                      seer_plan *plan)
+{
+    if (!plan) return SEER_EINVAL;
+    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS) return SEER_EKERNEL;
+    const int rc = check_csr(A, true);
+    if (rc != SEER_OK) return rc;
+    seer_plan made;
+    const int prc = prepare_into(kernel_id, A, plan_mem, plan_bytes, stream, &made);
+    if (prc == SEER_OK) *plan = made;
+    else if (prc == SEER_EWORKSPACE && kernel_id == SEER_ELL_TM) plan->device_bytes = made.device_bytes;   // the documented exception
+    return prc;
 }
 
 size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan)
@@ -992,23 +1037,28 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
                    size_t plan_bytes, void *workspace, size_t workspace_bytes, void *stream, seer_plan *plan,
                    int *path)
 {
-    if (!A || !model || !model->gathered || !plan || iterations < 1) return SEER_EINVAL;
-    if (model->selector && !model->known) return SEER_EINVAL;
+    if (!A || !plan || iterations < 1) return SEER_EINVAL;
+    if (model && (!model->gathered || (model->selector && !model->known))) return SEER_EINVAL;
     int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     int use_gathered = 1, kid = -1;
     int64_t max_len = -1;
-    if (model->selector) {
+    if (!model || model->selector) {
         seer_features_t kf;
         rc = seer_known_features(A->rows, A->cols, A->nnz, &kf);
         if (rc != SEER_OK) return rc;
         kf.f[SEER_F_ITERATIONS] = (float)iterations;
-        if (model->selector->n_classes > 2) return SEER_ETREE;
-        rc = seer_select(&kf, model->selector, &use_gathered);
-        if (rc != SEER_OK) return rc;
-        if (!use_gathered) {
-            rc = seer_select(&kf, model->known, &kid);
+        if (!model) {                   // the built-in models for several products
+            use_gathered = seer_model_iterative_selector(kf.f) != 0;
+            if (!use_gathered) kid = seer_model_iterative_known(kf.f);
+        } else {
+            if (model->selector->n_classes > 2) return SEER_ETREE;
+            rc = seer_select(&kf, model->selector, &use_gathered);
             if (rc != SEER_OK) return rc;
+            if (!use_gathered) {
+                rc = seer_select(&kf, model->known, &kid);
+                if (rc != SEER_OK) return rc;
+            }
         }
     }
     if (use_gathered) {
@@ -1017,21 +1067,34 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
         if (rc != SEER_OK) return rc;
         gf.f[SEER_F_ITERATIONS] = (float)iterations;
         max_len = gf.max_len;
-        rc = seer_select(&gf, model->gathered, &kid);
-        if (rc != SEER_OK) return rc;
+        if (!model) {
+            kid = seer_model_iterative_gathered(gf.f);
+        } else {
+            rc = seer_select(&gf, model->gathered, &kid);
+            if (rc != SEER_OK) return rc;
+        }
     }
     if (kid < 0 || kid >= SEER_NUM_KERNELS) return SEER_ETREE;
-    if (path) *path = use_gathered;
+    seer_plan made;
     if (kid == SEER_ELL_TM && A->rows > 0) {
-        std::memset(plan, 0, sizeof *plan);
-        plan->kernel_id = kid;
-        plan->rows = A->rows;
-        plan->nnz = A->nnz;
-        rc = prepare_ell(A, plan_mem, plan_bytes, stream, plan, max_len);
+        std::memset(&made, 0, sizeof made);
+        made.kernel_id = kid;
+        made.rows = A->rows;
+        made.nnz = A->nnz;
+        rc = prepare_ell(A, plan_mem, plan_bytes, stream, &made, max_len);
+        if (rc == SEER_OK) {
+            *plan = made;
+            if (path) *path = use_gathered;
+            return SEER_OK;
+        }
         if (rc != SEER_EWORKSPACE && rc != SEER_EINVAL) return rc;
         kid = SEER_CSR_A;            // the ELL arrays do not fit: take the schedule that is safe everywhere
     }
-    return seer_spmv_prepare(kid, A, plan_mem, plan_bytes, stream, plan);
+    rc = prepare_into(kid, A, plan_mem, plan_bytes, stream, &made);
+    if (rc != SEER_OK) return rc;
+    *plan = made;                    // outputs are written on success only
+    if (path) *path = use_gathered;
+    return SEER_OK;
 }
 
 } // extern "C"

@@ -57,25 +57,11 @@ ITER_GRID = [1, 2, 3, 5, 8, 12, 19, 30, 50, 100]   # iteration counts the iterat
 ND = S.NUM_DIRECT_KERNELS
 
 
-def time_kernel_us(kid, dA, x, y, ws, warmup=10, reps=10):
-    import torch
-    for _ in range(warmup):
-        S.seer_spmv(kid, dA, x, y, workspace=ws)
-    torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        for _ in range(reps):
-            S.seer_spmv(kid, dA, x, y, workspace=ws)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    g.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / reps
-
-
-def time_graph_us(enqueue, warmup=3, reps=10):
-    """Mean time of `enqueue()` (which only enqueues GPU work) replayed from a HIP graph."""
+def time_graph_us(enqueue, warmup=10, reps=10, replays=3):
+    """Time of one `enqueue()` (which only enqueues GPU work) on the GPU timeline.  THE timing
+    protocol of every path that is compared with another (Sec. IV-B: 10 warm-up runs, mean of
+    10 timed runs): `warmup` eager calls, `reps` calls captured into one HIP graph, one untimed
+    replay, then `replays` timed replays between two HIP events; the median replay / reps."""
     import torch
     for _ in range(warmup):
         enqueue()
@@ -86,12 +72,63 @@ def time_graph_us(enqueue, warmup=3, reps=10):
             enqueue()
     g.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    g.replay()
-    e1.record()
+    ts = []
+    for _ in range(replays):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3 / reps)
+    return sorted(ts)[len(ts) // 2]
+
+
+def time_kernel_us(kid, dA, x, y, ws):
+    """One product with a fixed kernel through seer_spmv, by the common protocol."""
+    return time_graph_us(lambda: S.seer_spmv(kid, dA, x, y, workspace=ws))
+
+
+COLD_BYTES = 320 << 20      # more than the 256 MB last-level cache plus the eight 4 MB L2s
+COLD_MAX_SETS = 32
+
+
+def cold_sets(dA, x, y, ws):
+    """Independent device copies of (A, x, y, workspace), enough that a pass over all of them
+    moves more than the caches hold (at most COLD_MAX_SETS: a matrix below 10 MB stays partly
+    cached).  The first set is the given one."""
+    foot = 8 * dA.nnz + 4 * (dA.rows + 1) + 4 * dA.cols + 4 * dA.rows
+    n = max(2, min(COLD_MAX_SETS, -(-COLD_BYTES // max(foot, 1)) + 1))
+    sets = [(dA, x, y, ws)]
+    for _ in range(n - 1):
+        sets.append((S.DeviceCSR(dA.rows, dA.cols, dA.row_ptr.clone(), dA.col_idx.clone(), dA.values.clone(), dA.nnz),
+                     x.clone(), y.clone(), ws.clone()))
+    return sets
+
+
+def time_graph_cold_us(enqueue_on, sets, replays=3):
+    """As time_graph_us, but successive calls go to successive sets of buffers (one graph of one
+    call per set, at least ten calls), so that a call finds its operands evicted."""
+    import torch
+    n = len(sets)
+    reps = n * -(-10 // n)
+    for i in range(reps):
+        enqueue_on(*sets[i % n])
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / reps
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(reps):
+            enqueue_on(*sets[i % n])
+    g.replay()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(replays):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3 / reps)
+    return sorted(ts)[len(ts) // 2]
 
 
 def time_prepare_us(kid, dA, plan_mem, warmup=3, reps=10):
@@ -141,18 +178,18 @@ def measure_matrix(spec, device="cuda:0", extra=None):
                 t_prep, plan = time_prepare_us(k, dA, plan_mem)
                 row[f"t_prep_k{k}_us"] = round(t_prep, 3)
                 row[f"t_single_k{k}_us"] = "inf"           # no one-call form
-                row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws), warmup=10), 3)
+                row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws)), 3)
                 del plan, plan_mem
         elif k in PREP_KERNELS:
             plan_mem = S.alloc_workspace(S.plan_bytes(k, dA.rows, dA.nnz), device)
             t_prep, plan = time_prepare_us(k, dA, plan_mem)
             row[f"t_prep_k{k}_us"] = round(t_prep, 3)
             row[f"t_single_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
-            row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws), warmup=10), 3)
+            row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws)), 3)
         else:
             row[f"t_k{k}_us"] = round(time_kernel_us(k, dA, x, y, ws), 3)
             direct = S.seer_spmv_prepare(k, dA)
-            row[f"t_rep_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(direct, dA, x, y, ws), warmup=10), 3)
+            row[f"t_rep_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(direct, dA, x, y, ws)), 3)
         ys.append(y)
     # the asynchronous path with a constant tree: its excess over the bare kernel is the
     # device-side cost of gathering and selecting
@@ -588,16 +625,22 @@ def fit_tree(csv_path, out_json, test_frac=0.2, seed=0):
     return t
 
 
-def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr, matrices=None):
+COLD_EVAL_MAX_BYTES = 256 << 20    # matrices up to here are also timed cold (larger ones are cold anyway)
+
+
+def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr, matrices=None, cold=True):
     """Runs the held-out matrices again (or `matrices`, e.g. sweep numbers no fit has seen)
-    and times, end to end on the GPU timeline (HIP graph replay): every fixed kernel, the
-    always-gather path (seer_spmv_auto) and the classifier-selection path (seer_spmv_model)."""
+    and times, end to end on the GPU timeline and all by the one protocol of time_graph_us:
+    every fixed kernel, the always-gather path (seer_spmv_auto) and the classifier-selection
+    path (seer_spmv_model), whose host-side decision (wall clock) is charged on top.  A matrix
+    that fits the last-level cache is timed a second time cold, on rotating copies."""
     import torch
 
     from workloads.sweep_gen import build_on_device, sweep_spec
     model, meta = load_model(model_json)
     fields = ["m", "family", "rows", "nnz"] + [f"t_k{k}_us" for k in range(ND)] + \
-             ["t_auto_us", "t_model_us", "auto_kernel", "model_path", "model_kernel"]
+             ["t_auto_us", "t_model_us", "t_model_host_us", "auto_kernel", "model_path", "model_kernel", "cold_sets"] + \
+             [f"t_k{k}_cold_us" for k in range(ND)] + ["t_auto_cold_us", "t_model_cold_us"]
     with open(out_csv, "w", newline="") as fh:
         w = csv.DictWriter(fh, fieldnames=fields)
         w.writeheader()
@@ -613,14 +656,34 @@ def evaluate_model(csv_path, model_json, out_csv, log=sys.stderr, matrices=None)
             row["t_auto_us"] = round(time_graph_us(lambda: S.seer_spmv_auto(dA, model.gathered, x, y, ws)), 3)
             _, row["auto_kernel"] = S.seer_spmv_auto_result(ws)
             row["t_model_us"] = round(time_graph_us(lambda: S.seer_spmv_model(dA, model, x, y, ws)), 3)
+            row["t_model_host_us"] = round(S.seer_model_host_ns(model, dA.rows, dA.cols, dA.nnz) * 1e-3, 4)
             row["model_path"], row["model_kernel"] = S.seer_spmv_model(dA, model, x, y, ws)
             if row["model_path"] == 1:
                 _, row["model_kernel"] = S.seer_spmv_auto_result(ws)
+            foot = 8 * dA.nnz + 8 * dA.rows + 4 * dA.cols
+            if cold and foot <= COLD_EVAL_MAX_BYTES:
+                sets = cold_sets(dA, x, y, ws)
+                row["cold_sets"] = len(sets)
+                for k in range(ND):
+                    row[f"t_k{k}_cold_us"] = round(time_graph_cold_us(
+                        lambda d, xx, yy, w_: S.seer_spmv(k, d, xx, yy, workspace=w_), sets), 3)
+                row["t_auto_cold_us"] = round(time_graph_cold_us(
+                    lambda d, xx, yy, w_: S.seer_spmv_auto(d, model.gathered, xx, yy, w_), sets), 3)
+                row["t_model_cold_us"] = round(time_graph_cold_us(
+                    lambda d, xx, yy, w_: S.seer_spmv_model(d, model, xx, yy, w_), sets), 3)
+                del sets
+            else:                           # beyond the caches: the one-set timings are cold already
+                row["cold_sets"] = 1
+                for k in range(ND):
+                    row[f"t_k{k}_cold_us"] = row[f"t_k{k}_us"]
+                row["t_auto_cold_us"], row["t_model_cold_us"] = row["t_auto_us"], row["t_model_us"]
             w.writerow(row)
             fh.flush()
             print(f"[eval] m={m} {spec.family} nnz={dA.nnz} kernels={[row[f't_k{k}_us'] for k in range(ND)]} "
                   f"auto={row['t_auto_us']} (k{row['auto_kernel']}) model={row['t_model_us']} "
-                  f"(path {row['model_path']}, k{row['model_kernel']})", file=log, flush=True)
+                  f"(path {row['model_path']}, k{row['model_kernel']}) cold x{row['cold_sets']}: "
+                  f"{[row[f't_k{k}_cold_us'] for k in range(ND)]} auto={row['t_auto_cold_us']} "
+                  f"model={row['t_model_cold_us']}", file=log, flush=True)
     return summarize_evaluation(out_csv)
 
 
@@ -648,7 +711,7 @@ def evaluate_iterative(model_json, out_csv, counts=ITER_EVAL_COUNTS, matrices=No
             for _ in range(5):
                 plan, path = S.seer_spmv_plan(dA, model, n, plan_mem, ws)
             row[f"t_plan_us_n{n}"] = round((time.perf_counter() - t0) / 5 * 1e6, 3)
-            row[f"t_product_us_n{n}"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws), warmup=10), 3)
+            row[f"t_product_us_n{n}"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws)), 3)
             row[f"kernel_n{n}"], row[f"path_n{n}"] = plan.kernel_id, path
 
     with open(out_csv, "w", newline="") as fh:
@@ -687,19 +750,33 @@ def summarize_iterative_evaluation(eval_csv, counts=ITER_EVAL_COUNTS):
     return out
 
 
-def summarize_evaluation(eval_csv):
+def summarize_evaluation(eval_csv, suffix="", families=None):
+    """suffix "" = the same buffers every time (warm), "_cold" = rotating copies.  families:
+    restrict to these matrix families.  The classifier-selection path is charged its host-side
+    decision (t_model_host_us) on top of what the GPU timeline shows."""
     with open(eval_csv) as fh:
         rows = list(csv.DictReader(fh))
-    T = np.array([[float(r[f"t_k{k}_us"]) for k in range(ND)] for r in rows])
-    ta = np.array([float(r["t_auto_us"]) for r in rows])
-    tm = np.array([float(r["t_model_us"]) for r in rows])
+    if families is not None:
+        rows = [r for r in rows if r["family"] in families]
+    if suffix and (not rows or f"t_auto{suffix}_us" not in rows[0] or rows[0][f"t_auto{suffix}_us"] in ("", None)):
+        return None
+    T = np.array([[float(r[f"t_k{k}{suffix}_us"]) for k in range(ND)] for r in rows])
+    ta = np.array([float(r[f"t_auto{suffix}_us"]) for r in rows])
+    host = np.array([float(r.get("t_model_host_us") or 0.0) for r in rows])
+    tm = np.array([float(r[f"t_model{suffix}_us"]) for r in rows]) + host
     t_fixed = T.sum(axis=0)
     best = int(np.argmin(t_fixed))
     geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
+    # where the classifier-selection path ran a fixed kernel on known features, how its time
+    # compares with that kernel's own column: same kernel, same buffers, same protocol
+    same = np.array([int(r["model_path"]) == 0 for r in rows])
+    chosen = np.array([int(r["model_kernel"]) for r in rows])
+    ratio = float(T[same, chosen[same]].sum() / (tm[same] - host[same]).sum()) if same.any() else float("nan")
     return {
         "matrices": len(rows), "t_fixed_us": [float(v) for v in t_fixed], "best_fixed_kernel": best,
         "t_oracle_us": float(T.min(axis=1).sum()), "t_always_gather_us": float(ta.sum()),
-        "t_classifier_selection_us": float(tm.sum()),
+        "t_classifier_selection_us": float(tm.sum()), "t_host_decisions_us": float(host.sum()),
+        "same_kernel_fixed_over_model": ratio,
         "aggregate_speedup_vs_best_fixed": {"always_gather": float(t_fixed[best] / ta.sum()),
                                             "classifier_selection": float(t_fixed[best] / tm.sum())},
         "per_matrix_geomean_vs_best_fixed": {"always_gather": geo(T[:, best], ta),
@@ -728,7 +805,8 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
          "--model selector_model.json --eval eval.csv" + (" --fresh-eval eval_fresh.csv" if fresh_csv else "") +
          (" --iterative-eval eval_iterative.csv" if iter_csv else "") + " --out profiles/selector_evaluation.md", "",
          f"Population: {len(rows)} seeded synthetic matrices (workloads/sweep_gen.py), timing 10 warm-up + 10 timed "
-         "runs per kernel, HIP-graph replay, same buffers (warm).  CSR,A and ELL,TM are timed with a prepared plan; "
+         "runs per kernel by one protocol for all eight (HIP-graph replay after an untimed replay), same buffers "
+         "(warm).  CSR,A, ELL,TM and COO,WM are timed with a prepared plan; "
          "their preprocessing calls are timed apart (host wall clock, they wait for the device).  Where the ELL "
          "form is not applicable (beyond 2 GiB here) ELL,TM is charged what CSR,A costs: that is what "
          "seer_spmv_plan falls back to.", "",
@@ -769,12 +847,41 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
         out.append(f"| oracle | {e['t_oracle_us']:.0f} | {tb / e['t_oracle_us']:.3f} | | 1.000 |")
         out += ["", f"Geomean over the fixed kernels of (kernel total / classifier-selection total): "
                 f"{e['geomean_over_fixed_kernels_of_aggregate_speedup']:.2f}x.  Features gathered on "
-                f"{100 * e['gathered_fraction']:.0f} % of {whom}."]
+                f"{100 * e['gathered_fraction']:.0f} % of {whom}.  Every path is timed by the same protocol "
+                "(10 eager warm-up calls, 10 calls in one HIP graph, one untimed replay, median of three timed "
+                f"replays); the classifier-selection total includes {e['t_host_decisions_us']:.1f} us of host-side "
+                "decisions (wall clock).  Check of the protocol: where that path ran a fixed kernel on the known "
+                f"features, the kernel's own column over the path's time is {e['same_kernel_fixed_over_model']:.4f} "
+                "(same kernel, same buffers)."]
+        four = summarize_evaluation(path, families=("uniform", "banded", "poisson", "zipf"))
+        if four and four["matrices"] != e["matrices"]:
+            fb = names[four["best_fixed_kernel"]]
+            out += ["", f"On the four families of BASELINE config 5 alone (uniform, banded, Poisson, Zipf; "
+                    f"{four['matrices']} matrices, best fixed kernel {fb}): classifier selection "
+                    f"{four['aggregate_speedup_vs_best_fixed']['classifier_selection']:.3f}x in total, "
+                    f"{four['per_matrix_geomean_vs_best_fixed']['classifier_selection']:.3f}x per matrix; always gather "
+                    f"{four['aggregate_speedup_vs_best_fixed']['always_gather']:.3f}x / "
+                    f"{four['per_matrix_geomean_vs_best_fixed']['always_gather']:.3f}x."]
+        c = summarize_evaluation(path, suffix="_cold")
+        if c:
+            cb = names[c["best_fixed_kernel"]]
+            with open(path) as fh:
+                n_cold = sum(int(r["cold_sets"]) > 1 for r in csv.DictReader(fh))
+            out += ["", f"Cold (the {n_cold} matrices of at most 256 MiB timed on rotating copies of A, x, y -- up to "
+                    f"{COLD_MAX_SETS}, more than 320 MiB in total where that many suffice --, the larger ones as above): "
+                    f"best fixed kernel {cb} {c['t_fixed_us'][c['best_fixed_kernel']]:.0f} us, oracle {c['t_oracle_us']:.0f} us, "
+                    f"always gather {c['t_always_gather_us']:.0f} us "
+                    f"({c['aggregate_speedup_vs_best_fixed']['always_gather']:.3f}x in total, "
+                    f"{c['per_matrix_geomean_vs_best_fixed']['always_gather']:.3f}x per matrix), classifier selection "
+                    f"{c['t_classifier_selection_us']:.0f} us "
+                    f"({c['aggregate_speedup_vs_best_fixed']['classifier_selection']:.3f}x / "
+                    f"{c['per_matrix_geomean_vs_best_fixed']['classifier_selection']:.3f}x; "
+                    f"{c['time_lost_vs_oracle']['classifier_selection']:.3f} of the oracle)."]
         # by family: where the classifier-selection path gains on the best fixed kernel and where it loses
         with open(path) as fh:
             rr = list(csv.DictReader(fh))
         Tk = np.array([[float(r[f"t_k{k}_us"]) for k in range(ND)] for r in rr])
-        tm = np.array([float(r["t_model_us"]) for r in rr])
+        tm = np.array([float(r["t_model_us"]) + float(r.get("t_model_host_us") or 0.0) for r in rr])
         fam = np.array([r["family"] for r in rr])
         b = e["best_fixed_kernel"]
         out += ["", f"| family | matrices | {best} total us | classifier selection total us | oracle total us | "
@@ -876,7 +983,18 @@ def export_header(model_json, out_h, prefix="seer_model"):
             _emit_node(grp[key], 0, 1, lines)
             lines.append("}")
             lines.append("")
-    lines.append("#endif")
+    # The gathered model of the single-product path is walked on the device, which needs the
+    # node array rather than code: the same tree once more, as data, for users of the C ABI.
+    g = m["gathered"]
+    lines += ["#ifdef SEER_H   /* only where include/seer.h has been included before this file */",
+              f"static const seer_node {prefix}_gathered_nodes[{len(g['feature'])}] = {{"]
+    for i in range(len(g["feature"])):
+        lines.append(f"    {{{int(g['feature'][i])}, {int(g['left'][i])}, {int(g['right'][i])}, {int(g['klass'][i])}, "
+                     f"{float(g['threshold'][i]).hex()}}},")
+    lines += ["};",
+              f"static const seer_tree {prefix}_gathered_tree = {{{len(g['feature'])}, {len(names)}, {S.NUM_KERNELS}, "
+              f"{prefix}_gathered_nodes}};",
+              "#endif", "", "#endif"]
     with open(out_h, "w") as fh:
         fh.write("\n".join(lines) + "\n")
     return out_h

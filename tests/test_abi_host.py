@@ -275,7 +275,23 @@ def test_plan_argument_errors_and_sizes_without_gpu():
     t = S.Tree.constant(S.CSR_BM)
     model = S.Model(t)
     assert L.seer_spmv_plan(C.byref(A), C.byref(model.c), 0, None, 0, None, 0, None, C.byref(plan), None) == -1
-    assert L.seer_spmv_plan(C.byref(A), None, 1, None, 0, None, 0, None, C.byref(plan), None) == -1
+    half = S.Model(t)
+    half.c.selector = model.c.gathered                      # a selector without a known model
+    assert L.seer_spmv_plan(C.byref(A), C.byref(half.c), 1, None, 0, None, 0, None, C.byref(plan), None) == -1
+    # no model: the built-in one (generated code) decides; this tiny matrix needs neither features
+    # nor preprocessing, so the call touches no device and only records its choice
+    path = C.c_int(-1)
+    before = bytes(plan)
+    rc = L.seer_spmv_plan(C.byref(A), None, 1, None, 0, None, 0, None, C.byref(plan), C.byref(path))
+    kf = S.seer_known_features(3, 5, 2)
+    from paper_2403_17017_amd import training as T
+    import os
+    it_model, _ = T.load_model(os.path.join(os.path.dirname(T.__file__), "selector_model.json"), iterative=True)
+    if S.seer_select(kf, it_model.selector) == 0 and S.seer_select(kf, it_model.known) < S.NUM_DIRECT_KERNELS:
+        assert rc == 0 and path.value == 0
+        assert plan.kernel_id == S.seer_select(kf, it_model.known) and bytes(plan) != before
+    else:       # the shipped model wants features or a plan here: refused for want of memory, outputs untouched
+        assert rc == -4 and path.value == -1 and bytes(plan) == before
     assert L.seer_spmv_plan(C.byref(A), C.byref(model.c), 1, None, 0, None, 0, None, None, None) == -1
     # sizes
     assert S.plan_bytes(S.CSR_BM, 10**6, 10**7) == 0 and S.plan_bytes(S.ELL_TM, 10**6, 10**7) == 0

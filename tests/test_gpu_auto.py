@@ -335,3 +335,47 @@ def test_shipped_model_loads_and_runs(cases):
         p, kid = S.seer_spmv_model(dA, model, xd, y, ws)
         torch.cuda.synchronize()
         assert_parity(y.cpu().numpy(), y_ref, bound, f"shipped model on {A.name}")
+
+
+def test_builtin_model_chooses_like_the_shipped_trees(cases):
+    """model == NULL (the generated if/else code compiled into the library) against the same
+    trees loaded from selector_model.json and passed as node arrays: same path, same kernel,
+    same y, for single products and for planned ones."""
+    import ctypes as C
+    import os
+    import torch
+    from paper_2403_17017_amd import training as T
+    path_json = os.path.join(os.path.dirname(T.__file__), "selector_model.json")
+    model, _ = T.load_model(path_json)
+    it_model, _ = T.load_model(path_json, iterative=True)
+    L = S.lib()
+    for A, x, y_ref, bound in cases:
+        if A.rows == 0:
+            continue
+        announce(f"built-in model against the loaded trees, {A.name}")
+        dA, xd = upload(A), torch.from_numpy(x).cuda()
+        ws = S.alloc_workspace(S.spmv_auto_workspace_bytes(A.rows, A.nnz))
+        y1 = torch.full((A.rows,), float("nan"), device="cuda:0")
+        p1, k1 = S.seer_spmv_model(dA, model, xd, y1, ws)
+        if p1 == 1:
+            _, k1 = S.seer_spmv_auto_result(ws)
+        y0 = torch.full((A.rows,), float("nan"), device="cuda:0")
+        cs = dA.c_struct()
+        p0, k0 = C.c_int(-1), C.c_int(-1)
+        rc = L.seer_spmv_model(C.byref(cs), None, xd.data_ptr(), y0.data_ptr(), ws.data_ptr(), ws.numel(),
+                               None if torch.cuda.current_stream().cuda_stream == 0 else C.c_void_p(torch.cuda.current_stream().cuda_stream),
+                               C.byref(p0), C.byref(k0))
+        assert rc == 0
+        k0 = S.seer_spmv_auto_result(ws)[1] if p0.value == 1 else k0.value
+        torch.cuda.synchronize()
+        assert (p0.value, k0) == (p1, k1), A.name
+        assert torch.equal(y0, y1)
+        assert_parity(y0.cpu().numpy(), y_ref, bound, f"built-in model on {A.name}")
+        for n in (1, 19, 100):
+            plan1, pp1 = S.seer_spmv_plan(dA, it_model, n)
+            plan_mem = S.alloc_workspace(plan1.plan_mem.numel() if plan1.plan_mem is not None else 256)
+            fws = S.alloc_workspace(S.features_workspace_bytes(A.rows))
+            c, pp0 = S.binding.seer_plan(), C.c_int(-1)
+            rc = L.seer_spmv_plan(C.byref(cs), None, n, plan_mem.data_ptr(), plan_mem.numel(), fws.data_ptr(), fws.numel(),
+                                  None, C.byref(c), C.byref(pp0))
+            assert rc == 0 and (pp0.value, c.kernel_id) == (pp1, plan1.kernel_id), (A.name, n)

@@ -67,6 +67,36 @@ def test_config3_zipf_literal_parameters():
     check_all(A, prepared=(5, 7))
 
 
+@pytest.mark.parametrize("workload", ["laplace5_1024", "empty30_poisson4_8M"])
+def test_planned_products_at_full_size(workload):
+    """seer_spmv_plan with the shipped models for 1, 19 and 100 products, then the product from
+    the plan it returns, at the full size of BASELINE configs 2 and 4: the chosen kernel is what
+    the oracle's three-tree inference says for that iteration count, y matches the oracle."""
+    import os
+    import torch
+    from paper_2403_17017_amd import training as T
+    A = G.laplacian_5pt(1024) if workload == "laplace5_1024" else G.empty_poisson()
+    model_path = os.path.join(os.path.dirname(T.__file__), "selector_model.json")
+    model, meta = T.load_model(model_path, iterative=True)
+    x = G.dense_vector(A.cols, 99)
+    y_ref, bound = oracle_of(A, x)
+    dA = upload(A)
+    xd = torch.from_numpy(x).cuda()
+    for n in (1, 19, 100):
+        announce(f"full size {A.name}: seer_spmv_plan for {n} products")
+        plan, path = S.seer_spmv_plan(dA, model, n)
+        fg = O.features(A.rows, A.cols, A.row_ptr, iterations=n)["f"]
+        want_path, want_kid = O.model_select(A.rows, A.cols, A.nnz, fg, model.selector.arrays, model.known.arrays,
+                                             model.gathered.arrays, iterations=n)
+        assert path == want_path
+        # (ELL,TM falls back to CSR,A where the plan memory cannot hold the padded form)
+        assert plan.kernel_id == want_kid or (want_kid == S.ELL_TM and plan.kernel_id == S.CSR_A)
+        y = torch.full((A.rows,), float("nan"), device="cuda:0")
+        S.seer_spmv_prepared(plan, dA, xd, y)
+        assert_parity(y.cpu().numpy(), y_ref, bound, f"{S.kernel_name(plan.kernel_id)} planned for {n} products on {A.name}")
+        del plan
+
+
 @pytest.mark.parametrize("extra", [1, 255, 256, 300, 511])
 def test_thread_mapped_two_rows_per_lane_ragged_tail(extra):
     """From 2^20 short rows on CSR,TM takes two rows per lane (tiles of 512 rows): a last tile

@@ -131,3 +131,14 @@ def test_exported_header_is_equivalent_to_the_node_arrays(tmp_path):
             got = fn(v.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
             assert got == O.select(v, *arrs)
     assert "if ((double)f[" in open(hdr).read()
+
+
+def test_committed_header_is_the_export_of_the_committed_model(tmp_path):
+    """paper_2403_17017_amd/selector_model_generated.h is compiled into the library as its
+    built-in model: it must be exactly what export-header writes for the committed
+    selector_model.json, byte for byte."""
+    import os
+    here = os.path.dirname(T.__file__)
+    fresh = T.export_header(os.path.join(here, "selector_model.json"), str(tmp_path / "fresh.h"))
+    with open(fresh) as a, open(os.path.join(here, "selector_model_generated.h")) as b:
+        assert a.read() == b.read(), "run `python -m paper_2403_17017_amd.training export-header` and rebuild"
