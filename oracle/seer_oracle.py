@@ -44,6 +44,11 @@ What it defines
                    plan_spmv_python executes it literally so that tests can
                    check it assigns every nonzero to its row exactly once.
 
+  * slab_plan -- the preprocessing result of the column-slabbed schedule: every row cut
+                   into one virtual row per slab of 2^19 columns, entries stored slab after
+                   slab, so that the gathers of one stretch of the matrix stay inside one
+                   slab of x.  slab_spmv_python multiplies from it literally.
+
   * csr_defects -- the input contract of the kernels (Sec. IV-A: they consume the CSR
                    offsets and entries as given), counted: how many offsets and how
                    many column indices break it.  Not part of the paper's method; the
@@ -382,6 +387,53 @@ def coo_spmv_python(rows, coo_row, col_idx, values, x):
     for r, c, v in zip(coo_row, col_idx, values):
         y[int(r)] += v * x[int(c)]
     return y
+
+
+SLAB_SHIFT = 19      # a slab of x holds 2^19 columns = 2 MiB, half of one XCD's L2
+
+
+def slab_plan(rows: int, cols: int, row_ptr, col_idx, shift: int = SLAB_SHIFT):
+    """The preprocessing result of the column-slabbed schedule (Sec. IV: a kernel may have a
+    preprocessing step whose cost is amortised over the products; the format itself is this
+    build's).  Column c belongs to slab c >> shift; there are S = ceil(cols / 2^shift) slabs.
+    Row i is cut into S virtual rows, virtual row s * rows + i holding the entries of row i
+    whose column lies in slab s, in the order they have in row i, and the entries are stored
+    virtual row after virtual row -- all of slab 0 first, then slab 1, ...  Returns
+        n_slabs, rp_v [S * rows + 1] (offsets of the virtual rows), perm [nnz] (perm[p] = the
+        CSR position of the p-th entry of the slabbed order),
+    or None where the form does not apply: fewer than two slabs, S * rows >= 2^31, or a row
+    whose columns do not ascend (then a virtual row would not be one piece of its row)."""
+    rp = np.asarray(row_ptr, dtype=np.int64)
+    nnz = int(rp[rows] - rp[0]) if rows > 0 else 0
+    ci = np.asarray(col_idx[:nnz], dtype=np.int64)
+    n_slabs = -(-int(cols) // (1 << shift))
+    if rows <= 0 or n_slabs < 2 or n_slabs * rows >= 2 ** 31:
+        return None
+    lens = np.diff(rp[: rows + 1])
+    row_of = np.repeat(np.arange(rows, dtype=np.int64), lens)
+    if nnz > 1:
+        descends = (ci[1:] < ci[:-1]) & (row_of[1:] == row_of[:-1])
+        if np.any(descends):
+            return None
+    slab = ci >> shift
+    perm = np.argsort(slab, kind="stable")           # slab-major; inside a slab the CSR order (row-major) stays
+    v = slab[perm] * rows + row_of[perm]
+    rp_v = np.zeros(n_slabs * rows + 1, dtype=np.int64)
+    np.cumsum(np.bincount(v, minlength=n_slabs * rows), out=rp_v[1:])
+    return {"n_slabs": n_slabs, "rp_v": rp_v, "perm": perm}
+
+
+def slab_spmv_python(rows, plan, col_idx, values, x):
+    """y from the slabbed form, executed literally: the virtual rows' sums first, then, per row,
+    the sum over its slabs in slab order.  Exact arithmetic is the caller's business (use
+    integer-valued data): pure Python, tiny inputs only."""
+    S, rp_v, perm = plan["n_slabs"], plan["rp_v"], plan["perm"]
+    yv = [0] * (S * rows)
+    for v in range(S * rows):
+        for p in range(int(rp_v[v]), int(rp_v[v + 1])):
+            k = int(perm[p])
+            yv[v] += values[k] * x[int(col_idx[k])]
+    return [sum(yv[s * rows + i] for s in range(S)) for i in range(rows)]
 
 
 def csr_defects(rows: int, cols: int, nnz: int, row_ptr, col_idx):

@@ -1,0 +1,85 @@
+"""Pins of the oracle's column-slab plan (oracle.slab_plan): a worked case, brute-force
+restatements on small random matrices, the literal product from the plan, and the cases in
+which the form does not apply."""
+import numpy as np
+import pytest
+
+from oracle import seer_oracle as O
+from workloads import csr_gen as G
+
+
+def small(seed, rows=40, cols=70, lo=0, hi=9):
+    A = G.random_lengths(rows, cols, lo, hi, seed)
+    return A
+
+
+def test_worked_case():
+    # 3 rows, 8 columns, slabs of 4 columns (shift 2):
+    # row 0: cols 1 5 6 | row 1: (empty) | row 2: cols 0 3 4
+    rp = np.array([0, 3, 3, 6], np.int32)
+    ci = np.array([1, 5, 6, 0, 3, 4], np.int32)
+    p = O.slab_plan(3, 8, rp, ci, shift=2)
+    assert p["n_slabs"] == 2
+    # slab 0: row 0 {1}, row 1 {}, row 2 {0, 3}; slab 1: row 0 {5, 6}, row 1 {}, row 2 {4}
+    assert p["rp_v"].tolist() == [0, 1, 1, 3, 5, 5, 6]
+    assert p["perm"].tolist() == [0, 3, 4, 1, 2, 5]
+
+
+def test_brute_force_restatement():
+    """Each virtual row, listed by looping over the matrix the slow way, is what the plan says."""
+    for seed in range(12):
+        A = small(seed, rows=23 + seed, cols=50 + 3 * seed)
+        shift = 2 + seed % 3
+        p = O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx, shift)
+        S = -(-A.cols // (1 << shift))
+        assert p is not None and p["n_slabs"] == S
+        want_perm, want_rp = [], [0]
+        for s in range(S):
+            for i in range(A.rows):
+                for k in range(int(A.row_ptr[i]), int(A.row_ptr[i + 1])):
+                    if int(A.col_idx[k]) // (1 << shift) == s:
+                        want_perm.append(k)
+                want_rp.append(len(want_perm))
+        assert p["perm"].tolist() == want_perm and p["rp_v"].tolist() == want_rp
+        assert sorted(want_perm) == list(range(A.nnz))            # every entry exactly once
+
+
+def test_literal_product_equals_row_sums():
+    rng = np.random.default_rng(5)
+    for seed in range(6):
+        A = small(100 + seed, rows=31, cols=90, hi=14)
+        vals = rng.integers(-4, 5, A.nnz).astype(np.int64)
+        x = rng.integers(-3, 4, A.cols).astype(np.int64)
+        p = O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx, shift=3 + seed % 3)
+        got = O.slab_spmv_python(A.rows, p, A.col_idx, vals.tolist(), x.tolist())
+        want = [int(sum(vals[k] * x[A.col_idx[k]] for k in range(A.row_ptr[i], A.row_ptr[i + 1]))) for i in range(A.rows)]
+        assert got == want
+        # and a planted mistake is caught: one offset moved by one hands an entry to the wrong row
+        inner = [v for v in range(1, p["n_slabs"] * A.rows) if v % A.rows and p["rp_v"][v] > p["rp_v"][v - 1]]
+        v = inner[0]
+        bad = {"n_slabs": p["n_slabs"], "perm": p["perm"], "rp_v": p["rp_v"].copy()}
+        bad["rp_v"][v] -= 1                               # the last entry of virtual row v - 1 now counts for row v
+        k = int(p["perm"][bad["rp_v"][v]])
+        if vals[k] * x[A.col_idx[k]] != 0:
+            assert O.slab_spmv_python(A.rows, bad, A.col_idx, vals.tolist(), x.tolist()) != want
+
+
+def test_where_the_form_does_not_apply():
+    A = small(7)
+    assert O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx, shift=7) is None      # 70 columns: one slab
+    assert O.slab_plan(0, 100, np.zeros(1, np.int32), np.zeros(0, np.int32), shift=2) is None
+    # a row whose columns descend somewhere
+    rp = np.array([0, 3, 5], np.int32)
+    assert O.slab_plan(2, 16, rp, np.array([1, 9, 4, 2, 3], np.int32), shift=2) is None
+    assert O.slab_plan(2, 16, rp, np.array([1, 4, 9, 2, 3], np.int32), shift=2) is not None   # a descent across rows is fine
+    assert O.slab_plan(2, 16, rp, np.array([1, 4, 4, 3, 3], np.int32), shift=2) is not None   # repeats ascend
+    # too many virtual rows for 32-bit offsets (decided from the sizes alone)
+    assert O.slab_plan(2 ** 20, 2 ** 20 * 8, np.zeros(2 ** 20 + 1, np.int32), np.zeros(0, np.int32), shift=12) is None
+
+
+def test_default_slab_is_two_mebibytes_of_x():
+    assert (1 << O.SLAB_SHIFT) * 4 == 2 << 20
+    A = G.HostCSR(3, (1 << 20) + 1, np.array([0, 1, 2, 3], np.int32), np.array([5, 1 << 19, 1 << 20], np.int32),
+                  np.ones(3, np.float32), "three-slabs")
+    p = O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx)
+    assert p["n_slabs"] == 3 and p["rp_v"].tolist() == [0, 1, 1, 1, 1, 2, 2, 2, 2, 3] and p["perm"].tolist() == [0, 1, 2]
