@@ -484,23 +484,28 @@ def main():
         # the kernels with preprocessing, from a prepared plan (one plan per rotating copy)
         extras["prepared_cold_us"], extras["prepared_warm_us"], extras["prepare_call_us"] = {}, {}, {}
         max_len = int(S.seer_features(warm[0][0]).max_len)
-        for k in (S.CSR_A, S.ELL_TM, S.COO_WM):
+        for k in (S.CSR_A, S.ELL_TM, S.COO_WM, S.CSR_S):
             if k == S.ELL_TM and S.ell_plan_bytes(A.rows, max_len) == 0:
                 continue                                   # padded arrays beyond 2^31 words: not applicable
+            if k == S.CSR_S and S.slab_plan_bytes(A.rows, A.cols, A.nnz) == 0:
+                continue                                   # x is a single slab: not applicable
             for R, key in ((rot, "prepared_cold_us"), (warm, "prepared_warm_us")):
                 plans = [S.seer_spmv_prepare(k, R[i][0]) for i in range(R.n)]
+                # (a plan's products may need more scratch than the one-call kernels: CSR,S keeps its partials there)
+                wss = [S.alloc_workspace(max(S.spmv_prepared_workspace_bytes(p_), 256)) for p_ in plans]
                 reps = max(n_sets, 20)
 
                 def enqueue_all():
                     for i in range(reps):
-                        d, xd, y, ws = R[i]
-                        S.seer_spmv_prepared(plans[i % R.n], d, xd, y, ws)
+                        d, xd, y, _ = R[i]
+                        S.seer_spmv_prepared(plans[i % R.n], d, xd, y, wss[i % R.n])
                 from paper_2403_17017_amd.training import time_graph_us
                 extras[key][S.kernel_name(k)] = round(time_graph_us(enqueue_all, warmup=1, reps=1) / reps, 2)
-                del plans
+                del plans, wss
             d = warm[0][0]
             pm = S.alloc_workspace(max(S.plan_bytes(k, A.rows, A.nnz), S.features_workspace_bytes(A.rows),
-                                       S.ell_plan_bytes(A.rows, max_len) if k == S.ELL_TM else 0))
+                                       S.ell_plan_bytes(A.rows, max_len) if k == S.ELL_TM else 0,
+                                       S.slab_plan_bytes(A.rows, A.cols, A.nnz) if k == S.CSR_S else 0))
             S.seer_spmv_prepare(k, d, pm)
             t0 = time.perf_counter()
             for _ in range(10):
@@ -552,9 +557,11 @@ def main():
             # buffers a solver would allocate once: plan memory with room for the padded (ELL) form
             # of up to 1.5 x the CSR entries, the feature workspace, the products' workspace
             plan_mem = S.alloc_workspace(max(S.plan_bytes(S.CSR_A, d.rows, d.nnz), S.plan_bytes(S.COO_WM, d.rows, d.nnz),
-                                             12 * d.nnz + (1 << 20)))
+                                             12 * d.nnz + (1 << 20), S.slab_plan_bytes(d.rows, d.cols, d.nnz)))
             fws = S.alloc_workspace(S.features_workspace_bytes(d.rows))
-            pws = S.alloc_workspace(max(S.spmv_workspace_bytes(k, d.rows, d.nnz) for k in range(S.NUM_KERNELS)) + 256)
+            # products' scratch: the most any plan for this matrix can ask for (CSR,S: its partials and carries)
+            pws = S.alloc_workspace(max(S.spmv_workspace_bytes(k, d.rows, d.nnz) for k in range(S.NUM_KERNELS)) + 256
+                                    + 4 * d.rows * (-(-d.cols >> 19)) + 8 * (d.nnz // 2048 + 64))
             for n_it in (1, 19, 100):
                 wplan, _ = S.seer_spmv_plan(d, it_model, n_it, plan_mem, fws)   # warm the path once, the kernel's first launch included
                 S.seer_spmv_prepared(wplan, d, xd, y, pws)

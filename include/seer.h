@@ -74,7 +74,14 @@ enum {
                         (row, column, value) triples and reduces them by row (Table II,
                         "WM ... CSR, COO").  Its preprocessing expands row_ptr into one
                         row index per nonzero; columns and values are the CSR arrays.   */
-    SEER_NUM_KERNELS = 8
+    SEER_CSR_S = 8,  /* column slabbed (this build's addition to the pool, not in Table II): a
+                        preprocessing pass stores the matrix a second time, every row cut into
+                        one virtual row per slab of 2^19 columns and the entries laid out slab
+                        after slab; the product is CSR,WO over those virtual rows followed by a
+                        sum over each row's slabs, so that the gathers of a long stretch of
+                        work stay inside 2 MiB of x.  For large matrices with scattered
+                        columns, whose x no longer fits one XCD's L2.  No one-call form.       */
+    SEER_NUM_KERNELS = 9
 };
 
 /* CSR matrix, fp32 values, int32 indices.  All pointers DEVICE, caller-owned.
@@ -183,8 +190,8 @@ int seer_tree_reachable(const seer_tree *tree, const seer_features_t *known, uin
  * ids 0-2, then workspace may be NULL).
  * SEER_CSR_A and SEER_COO_WM in this single call run their preprocessing pass first, every
  * time (what one product with them costs); seer_spmv_prepare / seer_spmv_prepared split the two.
- * SEER_ELL_TM has no one-call form (SEER_EKERNEL): the size of its plan is only known
- * after a look at the matrix. */
+ * SEER_ELL_TM and SEER_CSR_S have no one-call form (SEER_EKERNEL): whether they apply and
+ * what their plans take is only known after a look at the matrix. */
 int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y,
               void *workspace, size_t workspace_bytes, void *stream);
 size_t seer_spmv_workspace_bytes(int kernel_id, int32_t rows, int32_t nnz);
@@ -277,10 +284,11 @@ int seer_spmv_auto_result(const void *workspace, void *stream, seer_features_t *
 typedef struct {
     int32_t kernel_id;
     int32_t rows, nnz;    /* of the matrix it was prepared for                          */
-    int32_t n_blocks;     /* SEER_CSR_A: row blocks in the plan                         */
+    int32_t n_blocks;     /* SEER_CSR_A: row blocks in the plan; SEER_CSR_S: column slabs  */
     int32_t split_rows;   /* SEER_CSR_A: 1 if some row is shared between blocks (the
                              product then needs the carry workspace and a second launch) */
-    int32_t ell_width;    /* SEER_ELL_TM: slots per row = the longest row               */
+    int32_t ell_width;    /* SEER_ELL_TM: slots per row = the longest row; SEER_CSR_S: log2
+                             of the columns per slab                                     */
     void *device;         /* DEVICE, inside plan_mem; NULL for kernels without a plan   */
     size_t device_bytes;
 } seer_plan;
@@ -293,6 +301,12 @@ size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz);
  * entries: 2 arrays of roundup(rows, 64) * max_len 4-byte words (each padded to 256 bytes).
  * 0 if that is 2^31 words or more: the format is then not applicable. */
 size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
+
+/* Device bytes of the column-slabbed form of a rows x cols matrix with nnz nonzeros: the
+ * offsets of S * rows virtual rows, S = ceil(cols / 2^19), a second copy of col_idx and of
+ * values, and the preprocessing's own scratch.  0 if the form does not apply by size alone:
+ * S < 2 (x is one slab) or S * rows >= 2^31. */
+size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz);
 
 /* Runs the preprocessing of `kernel_id` for A on `stream` and fills *plan.  For
  * SEER_CSR_A: one pass over A->row_ptr that writes, for block k = 0 .. n-1 of
@@ -311,6 +325,14 @@ size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
  * plan_mem cannot even hold the reduction's workspace, the size of the ELL form after that,
  * so sizing may take two rounds.  SEER_EINVAL if the format is not applicable.
  * For SEER_COO_WM: writes the row index of every nonzero, in CSR order (int32 [nnz]).
+ * For SEER_CSR_S: with S = ceil(cols / 2^19) slabs, writes rp_v[v] (uint32, v = 0 .. S * rows)
+ * = the number of entries in virtual rows below v, virtual row s * rows + i being the entries
+ * of row i with column >> 19 == s in their CSR order; then col_idx and values in that order
+ * (virtual row after virtual row), each array padded to 256 bytes; plan->n_blocks = S.
+ * plan_mem must hold seer_slab_plan_bytes(rows, cols, nnz) (SEER_EWORKSPACE otherwise, with
+ * the bytes needed in plan->device_bytes, as for SEER_ELL_TM).  SEER_EINVAL if the form does
+ * not apply: by size (seer_slab_plan_bytes gives 0), or because some row's columns do not
+ * ascend -- a virtual row must be one contiguous piece of its row.
  * HOST-SYNCHRONOUS: returns after the pass has finished (it reads back whether any row
  * is split, or the longest row).  plan_mem: DEVICE, 16-byte aligned, >= seer_plan_bytes();
  * may be NULL for kernels that need no plan (the call then only records the id).  Not
@@ -332,9 +354,9 @@ size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan);
  * (preprocessing + iterations * run time) can tell when preprocessing is amortised; then
  * seer_spmv_prepare for the chosen kernel.  The features, when the selector asks for
  * them, are gathered with seer_features.  HOST-SYNCHRONOUS.  Any kernel id may be
- * chosen; if it is SEER_ELL_TM and plan_mem cannot hold the ELL arrays (or the format is
- * not applicable) the call prepares SEER_CSR_A instead, the schedule that is safe on
- * every matrix.  *path (may be NULL): 0 known model, 1 gathered model.
+ * chosen; if it is SEER_ELL_TM or SEER_CSR_S and plan_mem cannot hold the converted matrix
+ * (or the form is not applicable) the call prepares SEER_CSR_A instead, the schedule that
+ * is safe on every matrix.  *path (may be NULL): 0 known model, 1 gathered model.
  * workspace: >= seer_features_workspace_bytes(rows); plan_mem: >= seer_plan_bytes(
  * SEER_CSR_A, rows, nnz) unless the model cannot answer SEER_CSR_A. */
 int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iterations,
@@ -380,6 +402,8 @@ int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx
  *               launch of its own (both 0: always)
  *   "auto_prune" 0: seer_spmv_auto does not prune the tree with the known features (every
  *               schedule counts as reachable, the features are always gathered); default 1
+ *   "slab_shift" CSR,S: log2 of the columns per slab, 1..30 (default 19: 2 MiB of x); the
+ *               size functions follow it
  *   "coo_runs"  COO,WM: 1 (default): a lane sums a run of eight consecutive triples,
  *               0: lane <-> triple in rounds of 64
  *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise

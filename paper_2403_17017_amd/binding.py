@@ -17,9 +17,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libseer.so")
 
 NUM_FEATURES = 13
-NUM_KERNELS = 8
+NUM_KERNELS = 9
 NUM_DIRECT_KERNELS = 5          # ids below this need no preprocessing
-CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, ELL_TM, COO_WM = range(8)
+CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, ELL_TM, COO_WM, CSR_S = range(9)
 ONE_CALL_KERNELS = (CSR_TM, CSR_WM, CSR_BM, CSR_MP, CSR_WO, CSR_A, COO_WM)   # what seer_spmv accepts
 FEATURE_NAMES = (
     "rows", "cols", "nnz", "mean_len", "max_len", "min_len", "var_len", "empty_frac",
@@ -123,6 +123,8 @@ def lib():
         L.seer_plan_bytes.restype = sz
         L.seer_ell_plan_bytes.argtypes = [i32, i32]
         L.seer_ell_plan_bytes.restype = sz
+        L.seer_slab_plan_bytes.argtypes = [i32, i32, i32]
+        L.seer_slab_plan_bytes.restype = sz
         L.seer_spmv_prepare.argtypes = [C.c_int, C.POINTER(seer_csr), vp, sz, vp, C.POINTER(seer_plan)]
         L.seer_spmv_prepare.restype = C.c_int
         L.seer_spmv_prepared.argtypes = [C.POINTER(seer_plan), C.POINTER(seer_csr), vp, vp, vp, sz, vp]
@@ -447,6 +449,18 @@ class Plan:
         vals = self.plan_mem[half: half + n * 4].view(torch.float32).cpu().numpy().reshape(self.ell_width, rows_pad)
         return cols, vals
 
+    def slab_arrays(self):
+        """(rp_v uint32 [S * rows + 1], col_idx int32 [nnz], values fp32 [nnz]) of a CSR,S plan, as host arrays."""
+        import torch
+        nv = self.n_blocks * int(self.c.rows) + 1
+        pad = lambda b: (b + 255) & ~255
+        nnz = int(self.c.nnz)
+        o1, o2 = pad(nv * 4), pad(nv * 4) + pad(nnz * 4)
+        rp_v = self.plan_mem[: nv * 4].view(torch.int32).cpu().numpy().view(np.uint32)
+        ci = self.plan_mem[o1: o1 + nnz * 4].view(torch.int32).cpu().numpy()
+        va = self.plan_mem[o2: o2 + nnz * 4].view(torch.float32).cpu().numpy()
+        return rp_v, ci, va
+
     def coo_rows(self) -> np.ndarray:
         """Row index of every nonzero (int32 [nnz]) as a host array."""
         import torch
@@ -467,6 +481,11 @@ def ell_plan_bytes(rows: int, max_len: int) -> int:
     return int(lib().seer_ell_plan_bytes(rows, max_len))
 
 
+def slab_plan_bytes(rows: int, cols: int, nnz: int) -> int:
+    """Plan memory of CSR,S; 0 where the form does not apply by size."""
+    return int(lib().seer_slab_plan_bytes(rows, cols, nnz))
+
+
 def seer_spmv_prepare(kernel_id: int, A: DeviceCSR, plan_mem=None, stream=None, max_len: int = None) -> Plan:
     """Runs the preprocessing of kernel_id for A (waits for it) and returns the plan.
     For ELL_TM the plan memory is sized from max_len (the longest row) when none is given."""
@@ -475,6 +494,8 @@ def seer_spmv_prepare(kernel_id: int, A: DeviceCSR, plan_mem=None, stream=None, 
         if max_len is None:
             max_len = int(seer_features(A, stream=stream).max_len)
         need = max(ell_plan_bytes(A.rows, max_len), features_workspace_bytes(A.rows))
+    if kernel_id == CSR_S and plan_mem is None:
+        need = slab_plan_bytes(A.rows, A.cols, A.nnz)
     if plan_mem is None and need:
         plan_mem = alloc_workspace(need, A.row_ptr.device)
     cs = A.c_struct()
@@ -510,7 +531,8 @@ def seer_spmv_plan(A: DeviceCSR, model: Model, iterations: int, plan_mem=None, w
         # room for any kernel's plan: CSR,A's blocks, COO,WM's row indices (4 bytes per nonzero),
         # and the ELL arrays as long as padding adds at most half to the 8 bytes per nonzero
         # (beyond that the call prepares CSR,A instead, as the C header says)
-        need = max(plan_bytes(CSR_A, A.rows, A.nnz), plan_bytes(COO_WM, A.rows, A.nnz), 12 * A.nnz + (1 << 20))
+        need = max(plan_bytes(CSR_A, A.rows, A.nnz), plan_bytes(COO_WM, A.rows, A.nnz), 12 * A.nnz + (1 << 20),
+                   slab_plan_bytes(A.rows, A.cols, A.nnz))
         plan_mem = alloc_workspace(need, A.row_ptr.device)
     if workspace is None:
         workspace = alloc_workspace(features_workspace_bytes(A.rows), A.row_ptr.device)

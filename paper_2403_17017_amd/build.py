@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libseer.so")
-SOURCES = ["seer_api.hip", "spmv_rowmapped.hip", "spmv_mergepath.hip", "spmv_workoriented.hip", "spmv_adaptive.hip", "spmv_ell.hip", "spmv_coo.hip", "features.hip", "spmv_auto.hip"]
+SOURCES = ["seer_api.hip", "spmv_rowmapped.hip", "spmv_mergepath.hip", "spmv_workoriented.hip", "spmv_adaptive.hip", "spmv_ell.hip", "spmv_coo.hip", "spmv_slab.hip", "features.hip", "spmv_auto.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
     # the compiler must not form packed-fp32 instructions on its own

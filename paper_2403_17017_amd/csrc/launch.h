@@ -64,6 +64,18 @@ void launch_coo_convert(int rows, const int *rp, void *plan_mem, hipStream_t st)
 void launch_coo(const SpmvArgs &a, bool runs /* lane-owned runs of triples (the default form) */, const void *plan_mem,
                 void *carry_ws, hipStream_t st);
 
+// CSR,S: plan_mem holds the virtual rows' offsets, the slabbed col_idx and values (slab_plan_bytes());
+// workspace: slab_workspace_bytes() (the partials, then CSR,WO's carries over the virtual matrix)
+constexpr int kSlabShift = 19;              // a slab of x: 2^19 columns = 2 MiB, half of one XCD's L2
+uint32_t slab_count(int rows, int cols, int shift);     // 0: the form does not apply (one slab, or too many virtual rows)
+size_t slab_plan_bytes(int rows, int cols, int nnz, int shift);
+size_t slab_workspace_bytes(int rows, int cols, int nnz, int shift);
+int *slab_flag(void *plan_mem, int rows, int cols, int nnz, int shift);
+void launch_slab_count(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, void *plan_mem, hipStream_t st);
+void launch_slab_fill(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, const float *va, void *plan_mem,
+                      hipStream_t st);
+void launch_slab(const SpmvArgs &a, uint32_t n_slabs, const void *plan_mem, void *workspace, hipStream_t st);
+
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory
     int32_t max_len, min_len;

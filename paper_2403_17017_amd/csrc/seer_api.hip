@@ -48,6 +48,7 @@ std::atomic<int> g_tune_nt{-1};
 std::atomic<int> g_tune_vec{-1};
 std::atomic<int> g_tune_poll{-1};
 std::atomic<int> g_tune_coo_runs{-1};
+std::atomic<int> g_tune_slab_shift{-1};
 
 std::mutex g_mailbox_mutex;
 FeatureRaw *g_mailbox_host = nullptr;   // pinned, mapped
@@ -129,6 +130,12 @@ int bm_rows(int rows, int nnz)
 bool coo_runs()
 {
     return g_tune_coo_runs.load() != 0;
+}
+
+int slab_shift()
+{
+    const int t = g_tune_slab_shift.load();
+    return t >= 1 && t <= 30 ? t : kSlabShift;
 }
 
 int bm_chunk()
@@ -375,7 +382,7 @@ bool tree_is_acyclic(const seer_tree *t)
     return true;
 }
 
-const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM", "COO,WM"};
+const char *const kKernelNames[SEER_NUM_KERNELS] = {"CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM", "COO,WM", "CSR,S"};
 
 } // namespace
 
@@ -419,6 +426,7 @@ int seer_set_tuning(const char *name, int value)
     else if (!std::strcmp(name, "vec")) g_tune_vec.store(value);
     else if (!std::strcmp(name, "poll")) g_tune_poll.store(value);
     else if (!std::strcmp(name, "coo_runs")) g_tune_coo_runs.store(value);
+    else if (!std::strcmp(name, "slab_shift")) g_tune_slab_shift.store(value);
     else return SEER_EINVAL;
     return SEER_OK;
 }
@@ -826,7 +834,8 @@ int seer_spmv(int kernel_id, const seer_csr *A, const float *x, float *y, void *
 static int spmv_dispatch(int kernel_id, const seer_csr *A, const float *x, float *y, void *workspace,
                          size_t workspace_bytes, void *stream, int nt)
 {
-    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS || kernel_id == SEER_ELL_TM) return SEER_EKERNEL;
+    if (kernel_id < 0 || kernel_id >= SEER_NUM_KERNELS || kernel_id == SEER_ELL_TM || kernel_id == SEER_CSR_S)
+        return SEER_EKERNEL;
     const int rc = check_csr(A, true);
     if (rc != SEER_OK) return rc;
     if (A->rows == 0) return SEER_OK;
@@ -890,6 +899,48 @@ size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz)
 
 size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len) { return ell_plan_bytes(rows, max_len); }
 
+size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz)
+{
+    if (rows < 0 || cols < 0 || nnz < 0) return 0;
+    return slab_plan_bytes(rows, cols, nnz, slab_shift());
+}
+
+// The column-slabbed form: counts and the check of the column order, then, if every row's
+// columns ascend, the offsets and the entries.
+static int prepare_slab(const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream, seer_plan *plan)
+{
+    const int shift = slab_shift();
+    const uint32_t S = slab_count(A->rows, A->cols, shift);
+    if (S == 0) return SEER_EINVAL;                        // one slab, or too many virtual rows
+    const size_t need = slab_plan_bytes(A->rows, A->cols, A->nnz, shift);
+    plan->device_bytes = need;
+    if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int *flag = slab_flag(plan_mem, A->rows, A->cols, A->nnz, shift);
+    hipError_t e = hipMemsetAsync(plan_mem, 0, ((size_t)S * (size_t)A->rows + 1) * 4, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipMemsetAsync(flag, 0, sizeof(int), st);
+    if (e != hipSuccess) return hip_fail(e);
+    launch_slab_count(A->rows, A->cols, A->nnz, shift, A->row_ptr, A->col_idx, plan_mem, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    int descends = 0;
+    e = hipMemcpyAsync(&descends, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    if (descends) return SEER_EINVAL;                      // a virtual row would not be one piece of its row
+    launch_slab_fill(A->rows, A->cols, A->nnz, shift, A->row_ptr, A->col_idx, A->values, plan_mem, st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_fail(e);
+    plan->n_blocks = (int32_t)S;
+    plan->ell_width = shift;                               // kept with the plan: the knob may move afterwards
+    plan->device = plan_mem;
+    return SEER_OK;
+}
+
 // The ELL conversion.  max_len < 0: not known yet, find it with the feature reduction.
 static int prepare_ell(const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream, seer_plan *plan,
                        int64_t max_len)
@@ -930,6 +981,7 @@ static int prepare_into(int kernel_id, const seer_csr *A, void *plan_mem, size_t
     plan->rows = A->rows;
     plan->nnz = A->nnz;
     if (kernel_id == SEER_ELL_TM && A->rows > 0) return prepare_ell(A, plan_mem, plan_bytes, stream, plan, -1);
+    if (kernel_id == SEER_CSR_S) return A->rows > 0 ? prepare_slab(A, plan_mem, plan_bytes, stream, plan) : SEER_EINVAL;
     if (kernel_id == SEER_COO_WM && A->rows > 0) {
         const size_t need = coo_plan_bytes(A->rows, A->nnz);
         if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
@@ -975,7 +1027,8 @@ int seer_spmv_prepare(int kernel_id, const seer_csr *A, void *plan_mem, size_t p
     seer_plan made;
     const int prc = prepare_into(kernel_id, A, plan_mem, plan_bytes, stream, &made);
     if (prc == SEER_OK) *plan = made;
-    else if (prc == SEER_EWORKSPACE && kernel_id == SEER_ELL_TM) plan->device_bytes = made.device_bytes;   // the documented exception
+    else if (prc == SEER_EWORKSPACE && (kernel_id == SEER_ELL_TM || kernel_id == SEER_CSR_S))
+        plan->device_bytes = made.device_bytes;            // the documented exception
     return prc;
 }
 
@@ -985,6 +1038,9 @@ size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan)
     if (plan->kernel_id == SEER_CSR_A)
         return plan->split_rows ? carry_workspace_bytes((uint32_t)plan->n_blocks) : 0;
     if (plan->kernel_id == SEER_ELL_TM) return 0;
+    if (plan->kernel_id == SEER_CSR_S)      // the partials, then CSR,WO's carries over the virtual matrix
+        return (((size_t)plan->n_blocks * (size_t)plan->rows * 4 + 255) & ~(size_t)255) +
+               carry_workspace_bytes(wo_num_tiles((int)((uint32_t)plan->n_blocks * (uint32_t)plan->rows), plan->nnz));
     if (plan->kernel_id == SEER_COO_WM) return carry_workspace_bytes(coo_num_intervals(plan->rows, plan->nnz));
     return seer_spmv_workspace_bytes(plan->kernel_id, plan->rows, plan->nnz);
 }
@@ -993,7 +1049,8 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
                        size_t workspace_bytes, void *stream)
 {
     if (!plan) return SEER_EINVAL;
-    if (plan->kernel_id != SEER_CSR_A && plan->kernel_id != SEER_ELL_TM && plan->kernel_id != SEER_COO_WM)
+    if (plan->kernel_id != SEER_CSR_A && plan->kernel_id != SEER_ELL_TM && plan->kernel_id != SEER_COO_WM &&
+        plan->kernel_id != SEER_CSR_S)
         return spmv_dispatch(plan->kernel_id, A, x, y, workspace, workspace_bytes, stream,
                              A ? use_nt_repeated(csr_footprint(A)) : use_nt());
     const int rc = check_csr(A, true);
@@ -1008,6 +1065,17 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
         SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
                    use_nt_repeated(csr_footprint(A) + 4ull * (uint64_t)A->nnz)};
         launch_coo(a, coo_runs(), plan->device, workspace, static_cast<hipStream_t>(stream));
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SEER_OK : hip_fail(e);
+    }
+    if (plan->kernel_id == SEER_CSR_S) {
+        if (plan->n_blocks < 2 || !workspace || !aligned16(workspace) ||
+            workspace_bytes < seer_spmv_prepared_workspace_bytes(plan))
+            return plan->n_blocks < 2 ? SEER_EINVAL : SEER_EWORKSPACE;
+        SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
+                   use_nt_repeated((uint64_t)plan->device_bytes + 4ull * ((uint64_t)A->cols + (uint64_t)A->rows) +
+                                   8ull * (uint64_t)plan->n_blocks * (uint64_t)A->rows)};
+        launch_slab(a, (uint32_t)plan->n_blocks, plan->device, workspace, static_cast<hipStream_t>(stream));
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SEER_OK : hip_fail(e);
     }
@@ -1089,6 +1157,16 @@ int seer_spmv_plan(const seer_csr *A, const seer_model *model, int32_t iteration
         }
         if (rc != SEER_EWORKSPACE && rc != SEER_EINVAL) return rc;
         kid = SEER_CSR_A;            // the ELL arrays do not fit: take the schedule that is safe everywhere
+    }
+    if (kid == SEER_CSR_S) {
+        rc = prepare_into(kid, A, plan_mem, plan_bytes, stream, &made);
+        if (rc == SEER_OK) {
+            *plan = made;
+            if (path) *path = use_gathered;
+            return SEER_OK;
+        }
+        if (rc != SEER_EWORKSPACE && rc != SEER_EINVAL) return rc;
+        kid = SEER_CSR_A;            // no room for the second copy, or the form does not apply
     }
     rc = prepare_into(kid, A, plan_mem, plan_bytes, stream, &made);
     if (rc != SEER_OK) return rc;

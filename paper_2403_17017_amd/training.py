@@ -44,7 +44,8 @@ MAX_DEPTH = 6   # fixed before looking at any test data (the paper caps depth, v
 # sees it, t_single_k{k}_us the one-call form that prepares and multiplies.  t_rep_k{k}_us
 # is a kernel without preprocessing run through seer_spmv_prepared, the entry point for
 # repeated products (it differs from seer_spmv in how a cache-sized matrix is loaded).
-PREP_KERNELS = [S.CSR_A, S.ELL_TM, S.COO_WM]
+PREP_KERNELS = [S.CSR_A, S.ELL_TM, S.COO_WM, S.CSR_S]
+FALLBACK_KERNELS = [S.ELL_TM, S.CSR_S]      # where their form does not apply, seer_spmv_plan prepares CSR,A instead
 ELL_MAX_BYTES = 2 << 30     # the sweep does not build ELL forms beyond this; the run-time rule is the caller's memory
 CSV_FIELDS = (["m", "family", "rows", "cols", "nnz"] + [f"f_{n}" for n in S.FEATURE_NAMES]
               + ["t_features_us"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)]
@@ -180,6 +181,26 @@ def measure_matrix(spec, device="cuda:0", extra=None):
                 row[f"t_single_k{k}_us"] = "inf"           # no one-call form
                 row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws)), 3)
                 del plan, plan_mem
+        elif k == S.CSR_S:
+            need = S.slab_plan_bytes(dA.rows, dA.cols, dA.nnz)
+            plan = None
+            if need and need <= ELL_MAX_BYTES * 2:
+                plan_mem = S.alloc_workspace(need, device)
+                try:
+                    t_prep, plan = time_prepare_us(k, dA, plan_mem)
+                except S.SeerError as err:             # some row's columns do not ascend: not applicable
+                    if err.status != -1:
+                        raise
+            if plan is None:
+                row[f"t_prep_k{k}_us"] = row[f"t_single_k{k}_us"] = row[f"t_k{k}_us"] = "inf"
+                y.zero_()
+                y += ys[3]
+            else:
+                wsk = S.alloc_workspace(S.spmv_prepared_workspace_bytes(plan), device)
+                row[f"t_prep_k{k}_us"] = round(t_prep, 3)
+                row[f"t_single_k{k}_us"] = "inf"           # no one-call form
+                row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, wsk)), 3)
+                del plan, plan_mem, wsk
         elif k in PREP_KERNELS:
             plan_mem = S.alloc_workspace(S.plan_bytes(k, dA.rows, dA.nnz), device)
             t_prep, plan = time_prepare_us(k, dA, plan_mem)
@@ -236,12 +257,13 @@ def load_csv(path):
     with open(path) as fh:
         rows = list(csv.DictReader(fh))
     X = np.array([[float(r[f"f_{n}"]) for n in S.FEATURE_NAMES] for r in rows], dtype=np.float32)
-    T = np.array([[float(r[f"t_k{k}_us"]) for k in range(S.NUM_KERNELS)] for r in rows])
+    T = np.array([[float(r.get(f"t_k{k}_us") or "inf") for k in range(S.NUM_KERNELS)] for r in rows])
     tf = np.array([float(r["t_features_us"]) for r in rows])
-    # where the ELL form is not applicable the run time falls back to CSR,A: that is what
-    # choosing ELL,TM costs there
-    na = ~np.isfinite(T[:, S.ELL_TM])
-    T[na, S.ELL_TM] = T[na, S.CSR_A]
+    # where the ELL or the column-slabbed form is not applicable the run time falls back to
+    # CSR,A: that is what choosing ELL,TM or CSR,S costs there
+    for k in FALLBACK_KERNELS:
+        na = ~np.isfinite(T[:, k])
+        T[na, k] = T[na, S.CSR_A]
     return rows, X, T, tf
 
 
@@ -259,9 +281,10 @@ def load_prep(rows):
     """Preprocessing time per matrix and kernel (zero for kernels that have none)."""
     P = np.zeros((len(rows), S.NUM_KERNELS))
     for k in PREP_KERNELS:
-        P[:, k] = [float(r[f"t_prep_k{k}_us"]) for r in rows]
-    na = ~np.isfinite(P[:, S.ELL_TM])
-    P[na, S.ELL_TM] = P[na, S.CSR_A]
+        P[:, k] = [float(r.get(f"t_prep_k{k}_us") or "inf") for r in rows]
+    for k in FALLBACK_KERNELS:
+        na = ~np.isfinite(P[:, k])
+        P[na, k] = P[na, S.CSR_A]
     return P
 
 
@@ -968,7 +991,7 @@ def export_header(model_json, out_h, prefix="seer_model"):
     names = m.get("feature_names", list(S.FEATURE_NAMES))
     lines = ["/* Generated by paper_2403_17017_amd.training export-header; do not edit.",
              f" * {m.get('note', '')}", " * Feature vector f[]: " + ", ".join(f"{i} {n}" for i, n in enumerate(names)),
-             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO  5 CSR,A  6 ELL,TM  7 COO,WM;",
+             " * Return values: kernel ids 0 CSR,TM  1 CSR,WM  2 CSR,BM  3 CSR,MP  4 CSR,WO  5 CSR,A  6 ELL,TM  7 COO,WM  8 CSR,S;",
              " * the selector returns 0 = use the known model, 1 = gather features first. */",
              "#ifndef SEER_MODEL_GENERATED_H", "#define SEER_MODEL_GENERATED_H", ""]
     groups = [("", m)] + ([("_iterative", m["iterative"])] if "iterative" in m else [])

@@ -39,9 +39,9 @@ def test_struct_layouts_match_header():
 
 
 def test_names_and_errors():
-    assert S.lib().seer_num_kernels() == 8 == S.NUM_KERNELS
-    assert [S.kernel_name(k) for k in range(8)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM", "COO,WM"]
-    assert S.lib().seer_kernel_name(8) is None
+    assert S.lib().seer_num_kernels() == 9 == S.NUM_KERNELS
+    assert [S.kernel_name(k) for k in range(9)] == ["CSR,TM", "CSR,WM", "CSR,BM", "CSR,MP", "CSR,WO", "CSR,A", "ELL,TM", "COO,WM", "CSR,S"]
+    assert S.lib().seer_kernel_name(9) is None
     assert S.strerror(0) == "ok" and "tree" in S.strerror(-3)
     with pytest.raises(S.SeerError):
         S.set_tuning("no_such_knob", 1)
@@ -189,7 +189,7 @@ def test_malformed_trees_are_rejected():
         S.Tree([0, -1, -1], [1.0, 0, 0], [1, -1, -1], [7, -1, -1], [-1, 0, 1]),     # child out of range
         S.Tree([0, 0], [1e30, 1e30], [1, 0], [1, 0], [0, 0]),                       # cycle
         S.Tree([13, -1, -1], [1.0, 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),    # feature index too large
-        S.Tree([-1], [0.0], [-1], [-1], [8]),                                       # class out of range
+        S.Tree([-1], [0.0], [-1], [-1], [S.NUM_KERNELS]),                           # class out of range
         S.Tree([0, -1, -1], [float("nan"), 0, 0], [1, -1, -1], [2, -1, -1], [-1, 0, 1]),
     ]
     for t in bad:
@@ -387,5 +387,5 @@ def test_plain_c_client_compiles_against_the_header_and_runs(tmp_path):
     assert lines[0] == "derive 0 mean 5.000000 density 0.250000 var 0.000000"
     assert lines[1] == "select 0 kernel 0 CSR,TM"
     assert lines[2] == "select 0 kernel 4 CSR,WO"
-    assert lines[3] == 'kernels 8 workspace 0 error "%s"' % S.strerror(-3)
+    assert lines[3] == 'kernels 9 workspace 0 error "%s"' % S.strerror(-3)
     assert lines[4] == "null matrix -1"

@@ -12,7 +12,7 @@ from gpu_util import announce, assert_features_equal, assert_parity, oracle_of, 
 pytestmark = pytest.mark.gpu
 
 
-def check_all(A, kernels=(0, 1, 2, 3, 4, 5, 7), prepared=(5, 6, 7)):
+def check_all(A, kernels=(0, 1, 2, 3, 4, 5, 7), prepared=(5, 6, 7, 8)):
     import torch
     x = G.dense_vector(A.cols, 4242)
     y_ref, bound = oracle_of(A, x)
@@ -57,14 +57,14 @@ def test_config3_zipf_nnz_matched():
     A = G.zipf_rows(s=1.85)
     assert A.rows == 2_000_000 and int(np.diff(A.row_ptr).max()) == 200_000
     assert S.ell_plan_bytes(A.rows, 200_000) == 0          # ELL,TM does not apply to this matrix
-    check_all(A, prepared=(5, 7))
+    check_all(A, prepared=(5, 7, 8))
 
 
 def test_config3_zipf_literal_parameters():
     """Zipf exponent 1.6 as stated (~4.8e8 nonzeros, 3.8 GB of entries)."""
     A = G.zipf_rows(s=1.6)
     assert A.nnz > 4e8 and int(np.diff(A.row_ptr).max()) == 200_000
-    check_all(A, prepared=(5, 7))
+    check_all(A, prepared=(5, 7, 8))
 
 
 @pytest.mark.parametrize("workload", ["laplace5_1024", "empty30_poisson4_8M"])

@@ -1,0 +1,144 @@
+"""GPU parity of CSR,S, the column-slabbed schedule: the preprocessing's arrays against the
+oracle's slab plan entry for entry, the product against the oracle's row sums, and the cases
+in which the form does not apply."""
+import numpy as np
+import pytest
+
+import paper_2403_17017_amd as S
+from oracle import seer_oracle as O
+from workloads import csr_gen as G
+
+from gpu_util import announce, assert_parity, oracle_of, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def shift(request):
+    S.set_tuning("slab_shift", request.param)
+    yield request.param
+    S.set_tuning("slab_shift", -1)
+
+
+def small_cases():
+    return [
+        G.explicit_lengths([0, 7, 0, 0, 3, 0], 70, 4, "empties"),
+        G.explicit_lengths([9] * 6, 40, 6, "few-columns-with-repeats"),
+        G.explicit_lengths([0] * 500 + [30_000] + [0] * 500, 70_000, 7, "giant-row-among-empties"),
+        G.explicit_lengths([33, 32, 31, 64, 65, 1, 0, 2048, 4097], 5_000, 13, "around-the-long-row-limit"),
+        G.random_lengths(5_003, 3_000, 0, 40, 21),
+        G.random_lengths(1_237, 9_000, 50, 700, 22),
+        G.zipf_rows(20_011, s=1.6, cap=5_000, seed=23),
+        G.laplacian_5pt(100),
+        G.empty_poisson(100_003, 20_000, 0.3, 4.0, seed=25),
+        G.banded(30_001, 9, 26),
+    ]
+
+
+def check_plan_and_product(A, sh):
+    import torch
+    want = O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx, sh)
+    dA = upload(A)
+    if want is None:
+        with pytest.raises(S.SeerError) as ei:
+            S.seer_spmv_prepare(S.CSR_S, dA)
+        assert ei.value.status == -1
+        return False
+    plan = S.seer_spmv_prepare(S.CSR_S, dA)
+    assert plan.kernel_id == S.CSR_S and plan.n_blocks == want["n_slabs"]
+    rp_v, ci, va = plan.slab_arrays()
+    assert np.array_equal(rp_v.astype(np.int64), want["rp_v"]), f"{A.name}: virtual row offsets differ"
+    assert np.array_equal(ci, A.col_idx[want["perm"]]) and np.array_equal(va, A.values[want["perm"]]), \
+        f"{A.name}: slabbed entries differ"
+    x = G.dense_vector(A.cols, 3)
+    y_ref, bound = oracle_of(A, x)
+    y = torch.full((A.rows,), float("nan"), dtype=torch.float32, device="cuda:0")
+    S.seer_spmv_prepared(plan, dA, torch.from_numpy(x).cuda(), y)
+    torch.cuda.synchronize()
+    assert_parity(y.cpu().numpy(), y_ref, bound, f"CSR,S on {A.name} (shift {sh})")
+    return True
+
+
+@pytest.mark.parametrize("shift", [3, 6, 10, 12], indirect=True)
+def test_slab_plan_bit_exact_and_product_parity(shift):
+    ran = 0
+    for A in small_cases():
+        announce(f"CSR,S shift={shift} {A.name} rows={A.rows} cols={A.cols} nnz={A.nnz}")
+        ran += check_plan_and_product(A, shift)
+    assert ran >= 5
+
+
+def test_default_slab_size_on_a_matrix_with_several_slabs():
+    """Slabs of 2^19 columns as shipped: 1.3 M columns are three slabs; rows of 0 to 30 entries."""
+    A = G.random_lengths(300_007, 1_300_000, 0, 30, 77)
+    announce(f"CSR,S default shift {A.name} rows={A.rows} cols={A.cols} nnz={A.nnz}")
+    assert S.slab_plan_bytes(A.rows, A.cols, A.nnz) > 8 * A.nnz + 4 * 3 * A.rows
+    assert check_plan_and_product(A, O.SLAB_SHIFT)
+
+
+def test_where_the_slabbed_form_does_not_apply():
+    import torch
+    # one slab at the default size
+    A = G.random_lengths(2_000, 3_000, 0, 9, 5)
+    assert S.slab_plan_bytes(A.rows, A.cols, A.nnz) == 0
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv_prepare(S.CSR_S, upload(A))
+    assert ei.value.status == -1
+    # no one-call form
+    with pytest.raises(S.SeerError) as ei:
+        S.seer_spmv(S.CSR_S, upload(A), torch.zeros(A.cols, device="cuda:0"), torch.zeros(A.rows, device="cuda:0"))
+    assert ei.value.status == -2
+    S.set_tuning("slab_shift", 8)
+    try:
+        # a row whose columns descend: short (walked) and long (cut by searches)
+        for n in (5, 200):
+            B = G.random_lengths(300, 3_000, n, n, 6)
+            ci = B.col_idx.copy()
+            a = int(B.row_ptr[17])
+            ci[a], ci[a + n - 1] = ci[a + n - 1], ci[a]
+            if ci[a] == ci[a + n - 1]:
+                continue
+            bad = G.HostCSR(B.rows, B.cols, B.row_ptr, ci, B.values, f"descending-{n}")
+            assert O.slab_plan(bad.rows, bad.cols, bad.row_ptr, bad.col_idx, 8) is None
+            announce(f"CSR,S refuses {bad.name}")
+            with pytest.raises(S.SeerError) as ei:
+                S.seer_spmv_prepare(S.CSR_S, upload(bad))
+            assert ei.value.status == -1
+        # plan memory too small: the size needed comes back
+        import ctypes as C
+        dA = upload(A)
+        cs = dA.c_struct()
+        need = S.slab_plan_bytes(A.rows, A.cols, A.nnz)
+        assert need > 0
+        small = S.alloc_workspace(1024)
+        c = S.binding.seer_plan()
+        rc = S.lib().seer_spmv_prepare(S.CSR_S, C.byref(cs), small.data_ptr(), small.numel(), None, C.byref(c))
+        assert rc == -4 and c.device_bytes == need and c.kernel_id == 0
+    finally:
+        S.set_tuning("slab_shift", -1)
+
+
+def test_plan_falls_back_when_the_slabbed_form_is_chosen_but_cannot_be_built():
+    """A model that always answers CSR,S: seer_spmv_plan prepares it where it applies and
+    CSR,A where it does not (one slab; descending columns; no room)."""
+    import torch
+    model = S.Model(S.Tree.constant(S.CSR_S), S.Tree.constant(S.CSR_S), S.Tree([-1], [0.0], [-1], [-1], [0], n_classes=2))
+    A = G.random_lengths(40_000, 2_000, 0, 20, 8)            # one slab at the default size
+    dA = upload(A)
+    plan, path = S.seer_spmv_plan(dA, model, 50)
+    assert path == 0 and plan.kernel_id == S.CSR_A
+    S.set_tuning("slab_shift", 7)
+    try:
+        plan, path = S.seer_spmv_plan(dA, model, 50)
+        assert plan.kernel_id == S.CSR_S and plan.n_blocks == -(-2_000 // 128)
+        x = G.dense_vector(A.cols, 4)
+        y_ref, bound = oracle_of(A, x)
+        y = torch.full((A.rows,), float("nan"), dtype=torch.float32, device="cuda:0")
+        S.seer_spmv_prepared(plan, dA, torch.from_numpy(x).cuda(), y)
+        torch.cuda.synchronize()
+        assert_parity(y.cpu().numpy(), y_ref, bound, "planned CSR,S")
+        tiny = S.alloc_workspace(S.plan_bytes(S.CSR_A, A.rows, A.nnz))   # room for CSR,A's plan only
+        plan, path = S.seer_spmv_plan(dA, model, 50, plan_mem=tiny)
+        assert plan.kernel_id == S.CSR_A
+    finally:
+        S.set_tuning("slab_shift", -1)

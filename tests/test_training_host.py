@@ -46,7 +46,7 @@ def test_fit_recovers_planted_rule(tmp_path):
         for m in range(300):
             f = np.exp(rng.normal(2, 2, S.NUM_FEATURES)).astype(np.float32)
             fast = 2 if f[6] <= 40 else 3
-            t = [100.0, 90.0, 80.0, 70.0, 75.0, 16.0, float("inf"), 95.0]   # kernel 5 is a little faster per product ...
+            t = [100.0, 90.0, 80.0, 70.0, 75.0, 16.0, float("inf"), 95.0, float("inf")]   # kernel 5 is a little faster per product ...
             t[fast] = 20.0
             row = {"m": m, "family": "x", "rows": int(f[0]) + 1, "cols": 1, "nnz": 1, "t_features_us": 5.0,
                    "max_disagreement": 0.0}
@@ -55,6 +55,7 @@ def test_fit_recovers_planted_rule(tmp_path):
             row["t_prep_k5_us"], row["t_single_k5_us"] = 60.0, 76.0   # ... but needs 60 us of preprocessing
             row["t_prep_k6_us"], row["t_single_k6_us"] = "inf", "inf"  # the ELL form applies to none of them
             row["t_prep_k7_us"], row["t_single_k7_us"] = 40.0, 135.0
+            row["t_prep_k8_us"], row["t_single_k8_us"] = "inf", "inf"  # nor does the column-slabbed one
             row.update({f"t_rep_k{k}_us": t[k] for k in range(S.NUM_DIRECT_KERNELS)})
             row["t_auto_mp_us"] = t[3] + 4.0          # gathering on the device costs 4 us
             w.writerow(row)
@@ -92,7 +93,7 @@ def test_fit_recovers_planted_rule(tmp_path):
     assert S.seer_select(f, mi.gathered) == 2
     f.f[12] = 50.0
     # (kernel 6 costs what kernel 5 costs wherever its format does not apply: either answer is right)
-    assert S.seer_select(f, mi.gathered) in (5, 6) and S.seer_select(f, mi.known) in (5, 6)
+    assert S.seer_select(f, mi.gathered) in (5, 6, 8) and S.seer_select(f, mi.known) in (5, 6, 8)
 
 
 def test_exported_header_is_equivalent_to_the_node_arrays(tmp_path):
