@@ -161,21 +161,31 @@ def time_spmv_back_to_back(kid, rot, reps, warmup):
     return e0.elapsed_time(e1) * 1e3 / reps   # microseconds
 
 
-def time_spmv_graph(kid, rot, reps, replays=3):
+def time_spmv_graph(kid, rot, reps, replays=3, prepared=False):
     """Average kernel time per launch with the launches replayed from one HIP graph,
-    which takes the host's launch cost out of the measurement."""
+    which takes the host's launch cost out of the measurement.  prepared: through
+    seer_spmv_prepared from one plan per rotating copy (the kernels with preprocessing)."""
     import torch
 
     import paper_2403_17017_amd as S
+    if prepared:
+        plans = [S.seer_spmv_prepare(kid, rot[i][0]) for i in range(rot.n)]
+        wss = [S.alloc_workspace(max(S.spmv_prepared_workspace_bytes(p_), 256)) for p_ in plans]
+
+        def launch(i):
+            d, x, y, _ = rot[i]
+            S.seer_spmv_prepared(plans[i % rot.n], d, x, y, wss[i % rot.n])
+    else:
+        def launch(i):
+            d, x, y, ws = rot[i]
+            S.seer_spmv(kid, d, x, y, workspace=ws)
     for i in range(min(reps, rot.n)):
-        d, x, y, ws = rot[i]
-        S.seer_spmv(kid, d, x, y, workspace=ws)
+        launch(i)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         for i in range(reps):
-            d, x, y, ws = rot[i]
-            S.seer_spmv(kid, d, x, y, workspace=ws)
+            launch(i)
     g.replay()
     torch.cuda.synchronize()
     total = 0.0
@@ -391,6 +401,9 @@ def main():
     ap.add_argument("--workload", default="laplace5_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel table and copy ceiling")
+    ap.add_argument("--roofline-kernel", type=int, default=-1,
+                    help="price this kernel id in `roofline` instead of the one the step selects (a kernel with "
+                         "preprocessing is timed from prepared plans); for profiling a particular schedule")
     ap.add_argument("--no-configs", dest="configs", action="store_false",
                     help="skip the table of every BASELINE config in extras")
     ap.add_argument("--selector-matrices", type=int, default=60,
@@ -449,9 +462,11 @@ def main():
     # Duration of the dominant kernel (the selected SpMV schedule): the same number of
     # launches on the same rotating copies, replayed from one HIP graph between two HIP
     # events, so that the figure is kernel time, free of launch gaps.
-    spmv_avg_us = time_spmv_graph(kid, rot, args.steps)
+    rk = kid if args.roofline_kernel < 0 else args.roofline_kernel
+    spmv_avg_us = time_spmv_graph(rk, rot, args.steps, prepared=rk not in S.ONE_CALL_KERNELS or
+                                  (rk >= S.NUM_DIRECT_KERNELS and args.roofline_kernel >= 0))
     achieved = mb / (spmv_avg_us * 1e-6) / 1e9
-    prof = load_profile_summaries(args.workload, S.kernel_name(kid))
+    prof = load_profile_summaries(args.workload + ("" if args.roofline_kernel < 0 else f"_k{rk}"), S.kernel_name(rk))
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
@@ -464,7 +479,7 @@ def main():
                    f"{n_sets * mb / 2**30:.2f} GiB", "selected_kernel": S.kernel_name(kid), "tree": tree_note},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": prof["traffic"],
-                     "kernel": S.kernel_name(kid), "avg_launch_us": round(spmv_avg_us, 3),
+                     "kernel": S.kernel_name(rk), "avg_launch_us": round(spmv_avg_us, 3),
                      "meets_60pct_of_hbm_peak": bool(achieved >= 0.6 * HBM_PEAK_GBPS),
                      "profiles": {k: v for k, v in prof.items() if k != "traffic"},
                      "how": f"{args.steps} launches of the selected kernel on the rotating cold copies, "

@@ -77,9 +77,9 @@ enum {
     SEER_CSR_S = 8,  /* column slabbed (this build's addition to the pool, not in Table II): a
                         preprocessing pass stores the matrix a second time, every row cut into
                         one virtual row per slab of 2^19 columns and the entries laid out slab
-                        after slab; the product is CSR,WO over those virtual rows followed by a
-                        sum over each row's slabs, so that the gathers of a long stretch of
-                        work stay inside 2 MiB of x.  For large matrices with scattered
+                        after slab; the product is CSR,WO over the virtual rows that hold
+                        entries followed by a sum over each row's pieces, so that the gathers
+                        of a long stretch of work stay inside 2 MiB of x.  For large matrices with scattered
                         columns, whose x no longer fits one XCD's L2.  No one-call form.       */
     SEER_NUM_KERNELS = 9
 };
@@ -286,7 +286,8 @@ typedef struct {
     int32_t rows, nnz;    /* of the matrix it was prepared for                          */
     int32_t n_blocks;     /* SEER_CSR_A: row blocks in the plan; SEER_CSR_S: column slabs  */
     int32_t split_rows;   /* SEER_CSR_A: 1 if some row is shared between blocks (the
-                             product then needs the carry workspace and a second launch) */
+                             product then needs the carry workspace and a second launch);
+                             SEER_CSR_S: the number of virtual rows kept                 */
     int32_t ell_width;    /* SEER_ELL_TM: slots per row = the longest row; SEER_CSR_S: log2
                              of the columns per slab                                     */
     void *device;         /* DEVICE, inside plan_mem; NULL for kernels without a plan   */
@@ -302,9 +303,10 @@ size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz);
  * 0 if that is 2^31 words or more: the format is then not applicable. */
 size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
 
-/* Device bytes of the column-slabbed form of a rows x cols matrix with nnz nonzeros: the
- * offsets of S * rows virtual rows, S = ceil(cols / 2^19), a second copy of col_idx and of
- * values, and the preprocessing's own scratch.  0 if the form does not apply by size alone:
+/* Device bytes of the column-slabbed form of a rows x cols matrix with nnz nonzeros: offsets
+ * and piece lists for up to min(nnz, S * rows) kept virtual rows, S = ceil(cols / 2^19), a
+ * second copy of col_idx and of values, and the preprocessing's own scratch (8 bytes per
+ * virtual row).  0 if the form does not apply by size alone:
  * S < 2 (x is one slab) or S * rows >= 2^31. */
 size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz);
 
@@ -325,10 +327,14 @@ size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz);
  * plan_mem cannot even hold the reduction's workspace, the size of the ELL form after that,
  * so sizing may take two rounds.  SEER_EINVAL if the format is not applicable.
  * For SEER_COO_WM: writes the row index of every nonzero, in CSR order (int32 [nnz]).
- * For SEER_CSR_S: with S = ceil(cols / 2^19) slabs, writes rp_v[v] (uint32, v = 0 .. S * rows)
- * = the number of entries in virtual rows below v, virtual row s * rows + i being the entries
- * of row i with column >> 19 == s in their CSR order; then col_idx and values in that order
- * (virtual row after virtual row), each array padded to 256 bytes; plan->n_blocks = S.
+ * For SEER_CSR_S: with S = ceil(cols / 2^19) slabs, virtual row s * rows + i is the entries of
+ * row i with column >> 19 == s, in their CSR order; only the virtual rows that hold entries
+ * are kept, numbered in the order of s * rows + i.  With K of them and M = min(nnz, S * rows),
+ * plan_mem receives, each array padded to 256 bytes: rp_z (uint32 [M + 1], used [K + 1]: the
+ * entries before kept row j; rp_z[K] = nnz), p_idx (uint32 [M + 1], used [K]: the kept rows that
+ * are pieces of row 0, then of row 1, ..., in slab order), rp_j (uint32 [rows + 1]: the pieces
+ * before row i), then col_idx and values ([nnz + 1] each) in the order of the kept rows;
+ * plan->n_blocks = S, plan->split_rows = K.
  * plan_mem must hold seer_slab_plan_bytes(rows, cols, nnz) (SEER_EWORKSPACE otherwise, with
  * the bytes needed in plan->device_bytes, as for SEER_ELL_TM).  SEER_EINVAL if the form does
  * not apply: by size (seer_slab_plan_bytes gives 0), or because some row's columns do not

@@ -398,9 +398,14 @@ def slab_plan(rows: int, cols: int, row_ptr, col_idx, shift: int = SLAB_SHIFT):
     build's).  Column c belongs to slab c >> shift; there are S = ceil(cols / 2^shift) slabs.
     Row i is cut into S virtual rows, virtual row s * rows + i holding the entries of row i
     whose column lies in slab s, in the order they have in row i, and the entries are stored
-    virtual row after virtual row -- all of slab 0 first, then slab 1, ...  Returns
-        n_slabs, rp_v [S * rows + 1] (offsets of the virtual rows), perm [nnz] (perm[p] = the
-        CSR position of the p-th entry of the slabbed order),
+    virtual row after virtual row -- all of slab 0 first, then slab 1, ...  Only the virtual
+    rows that hold entries are kept, numbered 0 .. K - 1 in that order.  Returns
+        n_slabs,
+        rp_v  [S * rows + 1]  offsets of all virtual rows,
+        perm  [nnz]           perm[p] = the CSR position of the p-th entry of the slabbed order,
+        rp_z  [K + 1]         offsets of the kept virtual rows,
+        rp_j  [rows + 1], p_idx [K]   row i's pieces are the kept rows p_idx[rp_j[i] : rp_j[i+1]],
+                              in slab order,
     or None where the form does not apply: fewer than two slabs, S * rows >= 2^31, or a row
     whose columns do not ascend (then a virtual row would not be one piece of its row)."""
     rp = np.asarray(row_ptr, dtype=np.int64)
@@ -420,20 +425,27 @@ def slab_plan(rows: int, cols: int, row_ptr, col_idx, shift: int = SLAB_SHIFT):
     v = slab[perm] * rows + row_of[perm]
     rp_v = np.zeros(n_slabs * rows + 1, dtype=np.int64)
     np.cumsum(np.bincount(v, minlength=n_slabs * rows), out=rp_v[1:])
-    return {"n_slabs": n_slabs, "rp_v": rp_v, "perm": perm}
+    kept = np.flatnonzero(np.diff(rp_v) > 0)         # the virtual rows with entries, ascending
+    rp_z = np.append(rp_v[kept], nnz)
+    # row i's pieces: the kept rows whose number is i modulo rows, in slab (= ascending) order
+    owner = kept % rows
+    order = np.argsort(owner, kind="stable")
+    rp_j = np.zeros(rows + 1, dtype=np.int64)
+    np.cumsum(np.bincount(owner, minlength=rows), out=rp_j[1:])
+    return {"n_slabs": n_slabs, "rp_v": rp_v, "perm": perm, "rp_z": rp_z, "rp_j": rp_j, "p_idx": order.astype(np.int64)}
 
 
 def slab_spmv_python(rows, plan, col_idx, values, x):
-    """y from the slabbed form, executed literally: the virtual rows' sums first, then, per row,
-    the sum over its slabs in slab order.  Exact arithmetic is the caller's business (use
-    integer-valued data): pure Python, tiny inputs only."""
-    S, rp_v, perm = plan["n_slabs"], plan["rp_v"], plan["perm"]
-    yv = [0] * (S * rows)
-    for v in range(S * rows):
-        for p in range(int(rp_v[v]), int(rp_v[v + 1])):
+    """y from the slabbed form, executed literally: the kept virtual rows' sums first, then,
+    per row, the sum over its pieces in the listed order.  Exact arithmetic is the caller's
+    business (use integer-valued data): pure Python, tiny inputs only."""
+    rp_z, perm, rp_j, p_idx = plan["rp_z"], plan["perm"], plan["rp_j"], plan["p_idx"]
+    yz = [0] * (len(rp_z) - 1)
+    for j in range(len(yz)):
+        for p in range(int(rp_z[j]), int(rp_z[j + 1])):
             k = int(perm[p])
-            yv[v] += values[k] * x[int(col_idx[k])]
-    return [sum(yv[s * rows + i] for s in range(S)) for i in range(rows)]
+            yz[j] += values[k] * x[int(col_idx[k])]
+    return [sum(yz[int(p_idx[t])] for t in range(int(rp_j[i]), int(rp_j[i + 1]))) for i in range(rows)]
 
 
 def csr_defects(rows: int, cols: int, nnz: int, row_ptr, col_idx):

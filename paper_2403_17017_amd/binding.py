@@ -449,17 +449,21 @@ class Plan:
         vals = self.plan_mem[half: half + n * 4].view(torch.float32).cpu().numpy().reshape(self.ell_width, rows_pad)
         return cols, vals
 
-    def slab_arrays(self):
-        """(rp_v uint32 [S * rows + 1], col_idx int32 [nnz], values fp32 [nnz]) of a CSR,S plan, as host arrays."""
+    def slab_arrays(self, cols: int):
+        """(rp_z uint32 [K + 1], p_idx uint32 [K], rp_j uint32 [rows + 1], col_idx int32 [nnz],
+        values fp32 [nnz]) of a CSR,S plan for a matrix of `cols` columns, as host arrays."""
         import torch
-        nv = self.n_blocks * int(self.c.rows) + 1
+        rows, nnz, S_, K = int(self.c.rows), int(self.c.nnz), self.n_blocks, int(self.c.split_rows)
         pad = lambda b: (b + 255) & ~255
-        nnz = int(self.c.nnz)
-        o1, o2 = pad(nv * 4), pad(nv * 4) + pad(nnz * 4)
-        rp_v = self.plan_mem[: nv * 4].view(torch.int32).cpu().numpy().view(np.uint32)
-        ci = self.plan_mem[o1: o1 + nnz * 4].view(torch.int32).cpu().numpy()
-        va = self.plan_mem[o2: o2 + nnz * 4].view(torch.float32).cpu().numpy()
-        return rp_v, ci, va
+        m = min(nnz, S_ * rows)
+        o_idx = pad((m + 1) * 4)
+        o_j = o_idx + pad(m * 4 + 4)
+        o_ci = o_j + pad((rows + 1) * 4)
+        o_va = o_ci + pad(nnz * 4 + 4)
+        u32 = lambda off, n: self.plan_mem[off: off + n * 4].view(torch.int32).cpu().numpy().view(np.uint32)
+        ci = self.plan_mem[o_ci: o_ci + nnz * 4].view(torch.int32).cpu().numpy()
+        va = self.plan_mem[o_va: o_va + nnz * 4].view(torch.float32).cpu().numpy()
+        return u32(0, K + 1), u32(o_idx, K), u32(o_j, rows + 1), ci, va
 
     def coo_rows(self) -> np.ndarray:
         """Row index of every nonzero (int32 [nnz]) as a host array."""

@@ -64,17 +64,19 @@ void launch_coo_convert(int rows, const int *rp, void *plan_mem, hipStream_t st)
 void launch_coo(const SpmvArgs &a, bool runs /* lane-owned runs of triples (the default form) */, const void *plan_mem,
                 void *carry_ws, hipStream_t st);
 
-// CSR,S: plan_mem holds the virtual rows' offsets, the slabbed col_idx and values (slab_plan_bytes());
-// workspace: slab_workspace_bytes() (the partials, then CSR,WO's carries over the virtual matrix)
+// CSR,S: plan_mem holds the kept virtual rows' offsets, each row's list of pieces, the slabbed
+// col_idx and values, then the preprocessing's scratch (slab_plan_bytes());
+// workspace: slab_workspace_bytes() (one partial per kept virtual row, then CSR,WO's carries)
 constexpr int kSlabShift = 19;              // a slab of x: 2^19 columns = 2 MiB, half of one XCD's L2
 uint32_t slab_count(int rows, int cols, int shift);     // 0: the form does not apply (one slab, or too many virtual rows)
 size_t slab_plan_bytes(int rows, int cols, int nnz, int shift);
-size_t slab_workspace_bytes(int rows, int cols, int nnz, int shift);
+size_t slab_workspace_bytes(uint32_t n_kept, int nnz);
 int *slab_flag(void *plan_mem, int rows, int cols, int nnz, int shift);
+const uint32_t *slab_kept_count(const void *plan_mem, int rows, int cols, int nnz, int shift);
 void launch_slab_count(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, void *plan_mem, hipStream_t st);
-void launch_slab_fill(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, const float *va, void *plan_mem,
-                      hipStream_t st);
-void launch_slab(const SpmvArgs &a, uint32_t n_slabs, const void *plan_mem, void *workspace, hipStream_t st);
+void launch_slab_fill(int rows, int cols, int nnz, int shift, uint32_t n_kept, const int *rp, const int *ci, const float *va,
+                      void *plan_mem, hipStream_t st);
+void launch_slab(const SpmvArgs &a, uint32_t n_slabs, uint32_t n_kept, const void *plan_mem, void *workspace, hipStream_t st);
 
 // feature reduction
 struct FeatureRaw {           // written by the device into pinned host memory

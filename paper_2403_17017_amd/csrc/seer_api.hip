@@ -905,8 +905,9 @@ size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz)
     return slab_plan_bytes(rows, cols, nnz, slab_shift());
 }
 
-// The column-slabbed form: counts and the check of the column order, then, if every row's
-// columns ascend, the offsets and the entries.
+// The column-slabbed form: counts, the check of the column order and the number of virtual
+// rows that hold entries; then, if every row's columns ascend, the offsets, the lists of
+// pieces and the entries.
 static int prepare_slab(const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream, seer_plan *plan)
 {
     const int shift = slab_shift();
@@ -916,27 +917,28 @@ static int prepare_slab(const seer_csr *A, void *plan_mem, size_t plan_bytes, vo
     plan->device_bytes = need;
     if (!plan_mem || !aligned16(plan_mem) || plan_bytes < need) return SEER_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int *flag = slab_flag(plan_mem, A->rows, A->cols, A->nnz, shift);
-    hipError_t e = hipMemsetAsync(plan_mem, 0, ((size_t)S * (size_t)A->rows + 1) * 4, st);
-    if (e != hipSuccess) return hip_fail(e);
-    e = hipMemsetAsync(flag, 0, sizeof(int), st);
-    if (e != hipSuccess) return hip_fail(e);
     launch_slab_count(A->rows, A->cols, A->nnz, shift, A->row_ptr, A->col_idx, plan_mem, st);
-    e = hipGetLastError();
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     int descends = 0;
-    e = hipMemcpyAsync(&descends, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+    uint32_t n_kept = 0;
+    e = hipMemcpyAsync(&descends, slab_flag(plan_mem, A->rows, A->cols, A->nnz, shift), sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipMemcpyAsync(&n_kept, slab_kept_count(plan_mem, A->rows, A->cols, A->nnz, shift), sizeof n_kept,
+                       hipMemcpyDeviceToHost, st);
     if (e != hipSuccess) return hip_fail(e);
     e = hipStreamSynchronize(st);
     if (e != hipSuccess) return hip_fail(e);
     if (descends) return SEER_EINVAL;                      // a virtual row would not be one piece of its row
-    launch_slab_fill(A->rows, A->cols, A->nnz, shift, A->row_ptr, A->col_idx, A->values, plan_mem, st);
+    if ((size_t)n_kept > (size_t)A->nnz) return hip_fail(hipErrorUnknown);
+    launch_slab_fill(A->rows, A->cols, A->nnz, shift, n_kept, A->row_ptr, A->col_idx, A->values, plan_mem, st);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
     e = hipStreamSynchronize(st);
     if (e != hipSuccess) return hip_fail(e);
     plan->n_blocks = (int32_t)S;
     plan->ell_width = shift;                               // kept with the plan: the knob may move afterwards
+    plan->split_rows = (int32_t)n_kept;
     plan->device = plan_mem;
     return SEER_OK;
 }
@@ -1038,10 +1040,8 @@ size_t seer_spmv_prepared_workspace_bytes(const seer_plan *plan)
     if (plan->kernel_id == SEER_CSR_A)
         return plan->split_rows ? carry_workspace_bytes((uint32_t)plan->n_blocks) : 0;
     if (plan->kernel_id == SEER_ELL_TM) return 0;
-    if (plan->kernel_id == SEER_CSR_S)      // the partials, then CSR,WO's carries over the virtual matrix
-        return (((size_t)plan->n_blocks * (size_t)plan->rows * 4 + 255) & ~(size_t)255) +
-               carry_workspace_bytes(wo_num_tiles((int)((uint32_t)plan->n_blocks * (uint32_t)plan->rows), plan->nnz));
-    if (plan->kernel_id == SEER_COO_WM) return carry_workspace_bytes(coo_num_intervals(plan->rows, plan->nnz));
+    if (plan->kernel_id == SEER_CSR_S)      // one partial per kept virtual row, then CSR,WO's carries over them
+        return plan->split_rows < 0 ? 0 : slab_workspace_bytes((uint32_t)plan->split_rows, plan->nnz);
     return seer_spmv_workspace_bytes(plan->kernel_id, plan->rows, plan->nnz);
 }
 
@@ -1069,13 +1069,14 @@ int seer_spmv_prepared(const seer_plan *plan, const seer_csr *A, const float *x,
         return e == hipSuccess ? SEER_OK : hip_fail(e);
     }
     if (plan->kernel_id == SEER_CSR_S) {
-        if (plan->n_blocks < 2 || !workspace || !aligned16(workspace) ||
-            workspace_bytes < seer_spmv_prepared_workspace_bytes(plan))
-            return plan->n_blocks < 2 ? SEER_EINVAL : SEER_EWORKSPACE;
+        if (plan->n_blocks < 2 || plan->split_rows < 0 || plan->split_rows > A->nnz) return SEER_EINVAL;
+        if (!workspace || !aligned16(workspace) || workspace_bytes < seer_spmv_prepared_workspace_bytes(plan))
+            return SEER_EWORKSPACE;
         SpmvArgs a{A->rows, A->cols, A->nnz, A->row_ptr, A->col_idx, A->values, x, y, use_remap(),
-                   use_nt_repeated((uint64_t)plan->device_bytes + 4ull * ((uint64_t)A->cols + (uint64_t)A->rows) +
-                                   8ull * (uint64_t)plan->n_blocks * (uint64_t)A->rows)};
-        launch_slab(a, (uint32_t)plan->n_blocks, plan->device, workspace, static_cast<hipStream_t>(stream));
+                   use_nt_repeated(8ull * (uint64_t)A->nnz + 4ull * ((uint64_t)A->cols + 2ull * (uint64_t)A->rows) +
+                                   16ull * (uint64_t)plan->split_rows)};
+        launch_slab(a, (uint32_t)plan->n_blocks, (uint32_t)plan->split_rows, plan->device, workspace,
+                    static_cast<hipStream_t>(stream));
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SEER_OK : hip_fail(e);
     }

@@ -10,13 +10,18 @@
 //     of row i that fall into slab s (one contiguous piece of the row: its columns must
 //     ascend, else the form does not apply);
 //   * the entries are stored virtual row after virtual row -- all of slab 0, then slab 1 ...
+//   * only the virtual rows that hold entries are kept: rp_z are their offsets, and for
+//     each row rp_j / p_idx list which of them are its pieces, in slab order.
 //
-// The product is then CSR,WO over that virtual matrix (equal shares of nonzeros, so a long
+// The product is then CSR,WO over the kept virtual rows (equal shares of nonzeros, so a long
 // stretch of consecutive workgroups -- one XCD's contiguous run of tiles -- gathers from
-// one slab of x, which its L2 holds), into S * rows partial results, and a last pass adds
-// each row's S partials in slab order.  Same power-law matrix: 382 -> 231 us per product.
-// It costs S times the row handling (offsets read, partials written and read again), so
-// it loses where rows are short and x fits L2 anyway; the selector decides.
+// one slab of x, which its L2 holds), into one partial per kept virtual row, and a last pass
+// adds each row's partials in slab order.  Same power-law matrix: 382 -> about 230 us per
+// product.  It costs a second set of offsets and the partials' round trip, so it loses where
+// rows are short and x fits L2 anyway; the selector decides.
+// (A first form kept all S * rows virtual rows.  A band or a stencil leaves almost all of
+// them empty, in runs of hundreds of thousands that CSR,WO hands to single workgroups: 50
+// times the plain kernels' time on such matrices.)
 #include "spmv_bodies.hiph"
 
 namespace seer {
@@ -196,14 +201,64 @@ __global__ __launch_bounds__(kWG) void slab_scatter_kernel(
     }
 }
 
-// ---- the product's last pass: y[i] = sum over the slabs, in slab order, of the partial of
-// virtual row s * rows + i.
-__global__ __launch_bounds__(kWG) void slab_combine_kernel(int rows, uint32_t n_slabs, const float *__restrict__ yv, float *__restrict__ y)
+// ---- preprocessing 4 to 6: which virtual rows hold entries.
+// Pieces per row (cnt still holds the counts): lane <-> row.
+__global__ __launch_bounds__(kWG) void slab_row_pieces_kernel(int rows, uint32_t n_slabs, const uint32_t *__restrict__ cnt,
+                                                              uint32_t *__restrict__ pieces /* [rows + 1], last stays 0 */)
 {
     const uint32_t i = blockIdx.x * kWG + threadIdx.x;
     if (i >= (uint32_t)rows) return;
-    float t = __builtin_nontemporal_load(yv + i);
-    for (uint32_t s = 1; s < n_slabs; ++s) t += __builtin_nontemporal_load(yv + (size_t)s * (uint32_t)rows + i);
+    uint32_t n = 0;
+    for (uint32_t s = 0; s < n_slabs; ++s) n += cnt[(size_t)s * (uint32_t)rows + i] != 0u;
+    pieces[i] = n;
+}
+
+// 1 for a virtual row with entries, else 0 (then prefix-summed into the kept rows' numbers).
+__global__ __launch_bounds__(kWG) void slab_flags_kernel(size_t nv, const uint32_t *__restrict__ cnt, uint32_t *__restrict__ keep)
+{
+    const size_t stride = (size_t)gridDim.x * kWG;
+    for (size_t v = (size_t)blockIdx.x * kWG + threadIdx.x; v < nv; v += stride) keep[v] = v + 1 < nv && cnt[v] != 0u;
+}
+
+// With rp_v (offsets of all virtual rows) and num_v (number of kept rows before each) done:
+// the kept rows' offsets rp_z, and per row the numbers of its pieces, in slab order.
+__global__ __launch_bounds__(kWG) void slab_compact_kernel(
+    int rows, uint32_t n_slabs, const uint32_t *__restrict__ rp_v, const uint32_t *__restrict__ num_v,
+    const uint32_t *__restrict__ rp_j, uint32_t n_kept, uint32_t nnz, uint32_t *__restrict__ rp_z, uint32_t *__restrict__ p_idx)
+{
+    const uint32_t i = blockIdx.x * kWG + threadIdx.x;
+    if (i == 0) rp_z[n_kept] = nnz;
+    if (i >= (uint32_t)rows) return;
+    uint32_t t = rp_j[i];
+    for (uint32_t s = 0; s < n_slabs; ++s) {
+        const size_t v = (size_t)s * (uint32_t)rows + i;
+        const uint32_t a = rp_v[v];
+        if (rp_v[v + 1] != a) {
+            const uint32_t j = num_v[v];
+            rp_z[j] = a;
+            p_idx[t++] = j;
+        }
+    }
+}
+
+// ---- the product's last pass: y[i] = sum of the partials of row i's pieces, in slab order.
+__global__ __launch_bounds__(kWG) void slab_combine_kernel(
+    int rows, const uint32_t *__restrict__ rp_j, const uint32_t *__restrict__ p_idx, const float *__restrict__ yz,
+    float *__restrict__ y)
+{
+    const uint32_t i = blockIdx.x * kWG + threadIdx.x;
+    if (i >= (uint32_t)rows) return;
+    const uint32_t a = __builtin_nontemporal_load(rp_j + i), e = __builtin_nontemporal_load(rp_j + i + 1);
+    float t = 0.f;
+    if (e - a <= 4u) {                               // the usual case: fetched together
+        float p[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q)
+            if (a + q < e) p[q] = yz[__builtin_nontemporal_load(p_idx + a + q)];
+        t = ((p[0] + p[1]) + p[2]) + p[3];
+    } else {
+        for (uint32_t k = a; k < e; ++k) t += yz[__builtin_nontemporal_load(p_idx + k)];
+    }
     store_y(y + i, t);
 }
 
@@ -218,71 +273,122 @@ uint32_t slab_count(int rows, int cols, int shift)
     return (uint32_t)s;
 }
 
-// plan_mem: offsets of the virtual rows [S * rows + 1], the slabbed col_idx [nnz], the slabbed
-// values [nnz] (each padded to 256 bytes), then what only the preprocessing uses: the prefix
-// sum's tile sums and the flag.
+// Where things lie in plan_mem.  What the products read comes first, sized for the most
+// virtual rows that can hold entries (min(nnz, S * rows)), so that the layout follows from the
+// sizes alone: rp_z, p_idx, rp_j, the slabbed col_idx, the slabbed values; then what only the
+// preprocessing uses: the offsets and the kept-row numbers of all S * rows virtual rows, the
+// prefix sums' tile sums, the flag.
+struct SlabLayout {
+    size_t nv, max_kept;
+    size_t rp_z, p_idx, rp_j, ci, va, rp_v, num_v, scan, flag, total;
+};
+static SlabLayout slab_layout(uint32_t S, int rows, int nnz)
+{
+    SlabLayout L;
+    L.nv = (size_t)S * (size_t)rows + 1;
+    L.max_kept = (size_t)nnz < L.nv - 1 ? (size_t)nnz : L.nv - 1;
+    size_t o = 0;
+    L.rp_z = o;  o += pad256((L.max_kept + 1) * 4);
+    L.p_idx = o; o += pad256(L.max_kept * 4 + 4);
+    L.rp_j = o;  o += pad256(((size_t)rows + 1) * 4);
+    L.ci = o;    o += pad256((size_t)nnz * 4 + 4);
+    L.va = o;    o += pad256((size_t)nnz * 4 + 4);
+    L.rp_v = o;  o += pad256(L.nv * 4);
+    L.num_v = o; o += pad256(L.nv * 4);
+    L.scan = o;  o += pad256(scan_scratch_words(L.nv) * 4 + 4);
+    L.flag = o;  o += 256;
+    L.total = o;
+    return L;
+}
+
 size_t slab_plan_bytes(int rows, int cols, int nnz, int shift)
 {
     const uint32_t S = slab_count(rows, cols, shift);
     if (S == 0 || nnz < 0) return 0;
-    const size_t nv = (size_t)S * (size_t)rows + 1;
-    return pad256(nv * 4) + 2 * pad256((size_t)nnz * 4) + pad256(scan_scratch_words(nv) * 4) + 256;
+    return slab_layout(S, rows, nnz).total;
 }
 
-// the products' scratch: the S * rows partials, then CSR,WO's carries over the virtual matrix
-size_t slab_workspace_bytes(int rows, int cols, int nnz, int shift)
+// the products' scratch: one partial per kept virtual row, then CSR,WO's carries over them
+size_t slab_workspace_bytes(uint32_t n_kept, int nnz)
 {
-    const uint32_t S = slab_count(rows, cols, shift);
-    if (S == 0) return 0;
-    return pad256((size_t)S * (size_t)rows * 4) + carry_workspace_bytes(wo_num_tiles((int)(S * (uint32_t)rows), nnz));
+    return pad256((size_t)n_kept * 4 + 4) + carry_workspace_bytes(wo_num_tiles((int)n_kept, nnz));
 }
 
 int *slab_flag(void *plan_mem, int rows, int cols, int nnz, int shift)
 {
-    return reinterpret_cast<int *>(static_cast<char *>(plan_mem) + slab_plan_bytes(rows, cols, nnz, shift) - 256);
+    return reinterpret_cast<int *>(static_cast<char *>(plan_mem) + slab_layout(slab_count(rows, cols, shift), rows, nnz).flag);
 }
 
-// First half of the preprocessing: counts and the check (the caller clears the counts and
-// the flag before, and reads the flag after).
+const uint32_t *slab_kept_count(const void *plan_mem, int rows, int cols, int nnz, int shift)
+{
+    // rp_j[rows] = the number of kept virtual rows, once launch_slab_count has run
+    return reinterpret_cast<const uint32_t *>(static_cast<const char *>(plan_mem) +
+                                              slab_layout(slab_count(rows, cols, shift), rows, nnz).rp_j) + rows;
+}
+
+// First half of the preprocessing: entries per virtual row with the check of the column
+// order, and the pieces per row prefix-summed into rp_j.  Clears what it needs cleared.  The
+// caller then waits, reads the flag and rp_j[rows].
 void launch_slab_count(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, void *plan_mem, hipStream_t st)
 {
     const uint32_t S = slab_count(rows, cols, shift);
-    hipLaunchKernelGGL(slab_count_kernel, dim3(((uint32_t)rows + kWG - 1) / kWG), dim3(kWG), 0, st, rows, shift, S, rp, ci,
-                       static_cast<uint32_t *>(plan_mem), slab_flag(plan_mem, rows, cols, nnz, shift));
+    const SlabLayout L = slab_layout(S, rows, nnz);
+    char *base = static_cast<char *>(plan_mem);
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(base + L.rp_v);
+    uint32_t *rp_j = reinterpret_cast<uint32_t *>(base + L.rp_j);
+    (void)hipMemsetAsync(cnt, 0, L.nv * 4, st);
+    (void)hipMemsetAsync(base + L.flag, 0, sizeof(int), st);
+    (void)hipMemsetAsync(rp_j + rows, 0, 4, st);
+    const dim3 by_rows(((uint32_t)rows + kWG - 1) / kWG);
+    hipLaunchKernelGGL(slab_count_kernel, by_rows, dim3(kWG), 0, st, rows, shift, S, rp, ci, cnt,
+                       reinterpret_cast<int *>(base + L.flag));
+    hipLaunchKernelGGL(slab_row_pieces_kernel, by_rows, dim3(kWG), 0, st, rows, S, static_cast<const uint32_t *>(cnt), rp_j);
+    launch_scan_exclusive(rp_j, (size_t)rows + 1, reinterpret_cast<uint32_t *>(base + L.scan), st);
 }
 
-// Second half: offsets from the counts, then the entries into their places.
-void launch_slab_fill(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, const float *va, void *plan_mem,
-                      hipStream_t st)
+// Second half: the numbers of the kept rows, the offsets of all virtual rows, the kept rows'
+// offsets and each row's list of pieces, then the entries into their places.
+void launch_slab_fill(int rows, int cols, int nnz, int shift, uint32_t n_kept, const int *rp, const int *ci, const float *va,
+                      void *plan_mem, hipStream_t st)
 {
     const uint32_t S = slab_count(rows, cols, shift);
-    const size_t nv = (size_t)S * (size_t)rows + 1;
+    const SlabLayout L = slab_layout(S, rows, nnz);
     char *base = static_cast<char *>(plan_mem);
-    uint32_t *rp_v = reinterpret_cast<uint32_t *>(base);
-    int *out_ci = reinterpret_cast<int *>(base + pad256(nv * 4));
-    float *out_va = reinterpret_cast<float *>(base + pad256(nv * 4) + pad256((size_t)nnz * 4));
-    uint32_t *scratch = reinterpret_cast<uint32_t *>(base + pad256(nv * 4) + 2 * pad256((size_t)nnz * 4));
-    launch_scan_exclusive(rp_v, nv, scratch, st);
-    hipLaunchKernelGGL(slab_scatter_kernel, dim3(((uint32_t)rows + kWG - 1) / kWG), dim3(kWG), 0, st, rows, shift, S, rp, ci,
-                       va, static_cast<const uint32_t *>(rp_v), out_ci, out_va);
+    uint32_t *rp_v = reinterpret_cast<uint32_t *>(base + L.rp_v), *num_v = reinterpret_cast<uint32_t *>(base + L.num_v);
+    uint32_t *scratch = reinterpret_cast<uint32_t *>(base + L.scan);
+    const size_t want = (L.nv + kWG * 8 - 1) / (kWG * 8);
+    hipLaunchKernelGGL(slab_flags_kernel, dim3((uint32_t)(want < 65536 ? want : 65536)), dim3(kWG), 0, st, L.nv,
+                       static_cast<const uint32_t *>(rp_v), num_v);
+    launch_scan_exclusive(num_v, L.nv, scratch, st);
+    launch_scan_exclusive(rp_v, L.nv, scratch, st);
+    const dim3 by_rows(((uint32_t)rows + kWG - 1) / kWG);
+    hipLaunchKernelGGL(slab_compact_kernel, by_rows, dim3(kWG), 0, st, rows, S, static_cast<const uint32_t *>(rp_v),
+                       static_cast<const uint32_t *>(num_v), reinterpret_cast<const uint32_t *>(base + L.rp_j), n_kept,
+                       (uint32_t)nnz, reinterpret_cast<uint32_t *>(base + L.rp_z), reinterpret_cast<uint32_t *>(base + L.p_idx));
+    hipLaunchKernelGGL(slab_scatter_kernel, by_rows, dim3(kWG), 0, st, rows, shift, S, rp, ci, va,
+                       static_cast<const uint32_t *>(rp_v), reinterpret_cast<int *>(base + L.ci),
+                       reinterpret_cast<float *>(base + L.va));
 }
 
-// The product: CSR,WO over the virtual matrix into the partials, its carry fix-up, the sum
-// over the slabs.
-void launch_slab(const SpmvArgs &a, uint32_t n_slabs, const void *plan_mem, void *workspace, hipStream_t st)
+// The product: CSR,WO over the kept virtual rows into their partials, its carry fix-up, the
+// sum over each row's pieces.
+void launch_slab(const SpmvArgs &a, uint32_t n_slabs, uint32_t n_kept, const void *plan_mem, void *workspace, hipStream_t st)
 {
-    const size_t nv = (size_t)n_slabs * (size_t)a.rows + 1;
+    const SlabLayout L = slab_layout(n_slabs, a.rows, a.nnz);
     const char *base = static_cast<const char *>(plan_mem);
-    float *yv = static_cast<float *>(workspace);
-    SpmvArgs v = a;
-    v.rows = (int)(n_slabs * (uint32_t)a.rows);
-    v.rp = reinterpret_cast<const int *>(base);
-    v.ci = reinterpret_cast<const int *>(base + pad256(nv * 4));
-    v.va = reinterpret_cast<const float *>(base + pad256(nv * 4) + pad256((size_t)a.nnz * 4));
-    v.y = yv;
-    launch_wo(v, true, static_cast<char *>(workspace) + pad256((size_t)v.rows * 4), st);
-    hipLaunchKernelGGL(slab_combine_kernel, dim3(((uint32_t)a.rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows, n_slabs,
-                       static_cast<const float *>(yv), a.y);
+    float *yz = static_cast<float *>(workspace);
+    if (n_kept) {
+        SpmvArgs v = a;
+        v.rows = (int)n_kept;
+        v.rp = reinterpret_cast<const int *>(base + L.rp_z);
+        v.ci = reinterpret_cast<const int *>(base + L.ci);
+        v.va = reinterpret_cast<const float *>(base + L.va);
+        v.y = yz;
+        launch_wo(v, true, static_cast<char *>(workspace) + pad256((size_t)n_kept * 4 + 4), st);
+    }
+    hipLaunchKernelGGL(slab_combine_kernel, dim3(((uint32_t)a.rows + kWG - 1) / kWG), dim3(kWG), 0, st, a.rows,
+                       reinterpret_cast<const uint32_t *>(base + L.rp_j), reinterpret_cast<const uint32_t *>(base + L.p_idx),
+                       static_cast<const float *>(yz), a.y);
 }
 
 } // namespace seer

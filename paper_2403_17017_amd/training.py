@@ -229,6 +229,64 @@ def measure_matrix(spec, device="cuda:0", extra=None):
     return row
 
 
+def measure_slab_only(spec, device="cuda:0"):
+    """The CSR,S columns of a sweep row alone (same matrix, same protocol): for adding the
+    kernel to a sweep that was run before it existed."""
+    import torch
+
+    from workloads.sweep_gen import build_on_device
+    rp, ci, va, x = build_on_device(spec, device)
+    dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
+    k = S.CSR_S
+    row = {"m": spec.m, f"t_prep_k{k}_us": "inf", f"t_single_k{k}_us": "inf", f"t_k{k}_us": "inf"}
+    need = S.slab_plan_bytes(dA.rows, dA.cols, dA.nnz)
+    if need and need <= ELL_MAX_BYTES * 2:
+        plan_mem = S.alloc_workspace(need, device)
+        try:
+            t_prep, plan = time_prepare_us(k, dA, plan_mem)
+        except S.SeerError as err:
+            if err.status != -1:
+                raise
+            return row
+        y = torch.empty(dA.rows, device=device)
+        wsk = S.alloc_workspace(S.spmv_prepared_workspace_bytes(plan), device)
+        row[f"t_prep_k{k}_us"] = round(t_prep, 3)
+        row[f"t_k{k}_us"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, wsk)), 3)
+    return row
+
+
+def run_slab_sweep(ms, out_csv, nnz_cap=200_000_000, max_rows_exp=7.0, log=sys.stderr):
+    from workloads.sweep_gen import sweep_spec
+    k = S.CSR_S
+    fields = ["m", f"t_k{k}_us", f"t_prep_k{k}_us", f"t_single_k{k}_us"]
+    with open(out_csv, "w", newline="") as fh:
+        w = csv.DictWriter(fh, fieldnames=fields)
+        w.writeheader()
+        t_start = time.time()
+        for m in ms:
+            row = measure_slab_only(sweep_spec(m, nnz_cap, max_rows_exp))
+            w.writerow(row)
+            fh.flush()
+            print(f"[sweep-slab] m={m} t={row[f't_k{k}_us']} prep={row[f't_prep_k{k}_us']} ({time.time() - t_start:.0f}s)",
+                  file=log, flush=True)
+
+
+def merge_columns(base_csv, extra_csv, out_csv):
+    """base_csv with the columns of extra_csv (matched by sweep number m) filled in."""
+    with open(extra_csv) as fh:
+        extra = {int(r["m"]): r for r in csv.DictReader(fh)}
+    with open(base_csv) as fh:
+        rows = list(csv.DictReader(fh))
+    with open(out_csv, "w", newline="") as fh:
+        w = csv.DictWriter(fh, fieldnames=CSV_FIELDS)
+        w.writeheader()
+        for r in rows:
+            e = extra.get(int(r["m"]), {})
+            r.update({k: v for k, v in e.items() if k != "m"})
+            w.writerow({k: r.get(k, "") for k in CSV_FIELDS})
+    return out_csv
+
+
 def run_sweep(ms, out_csv, nnz_cap=200_000_000, max_rows_exp=7.0, log=sys.stderr):
     from workloads.sweep_gen import sweep_spec
     done = set()
@@ -1053,6 +1111,14 @@ def main(argv=None):
     a.add_argument("--out", default="sweep.csv")
     a.add_argument("--nnz-cap", type=int, default=200_000_000)
     a.add_argument("--max-rows-exp", type=float, default=7.0)
+    a2 = sub.add_parser("sweep-slab", help="the CSR,S columns alone, for merging into an earlier sweep")
+    a2.add_argument("--first", type=int, default=0)
+    a2.add_argument("--count", type=int, default=3000)
+    a2.add_argument("--out", default="sweep_slab.csv")
+    a3 = sub.add_parser("merge")
+    a3.add_argument("--csv", required=True)
+    a3.add_argument("--extra", required=True)
+    a3.add_argument("--out", required=True)
     b = sub.add_parser("fit")
     b.add_argument("--csv", required=True)
     b.add_argument("--out", default=os.path.join(os.path.dirname(__file__), "selector_model.json"))
@@ -1085,7 +1151,11 @@ def main(argv=None):
     if args.cmd == "export-header":
         print(export_header(args.model, args.out))
         return
-    if args.cmd == "sweep":
+    if args.cmd == "sweep-slab":
+        run_slab_sweep(range(args.first, args.first + args.count), args.out)
+    elif args.cmd == "merge":
+        print(merge_columns(args.csv, args.extra, args.out))
+    elif args.cmd == "sweep":
         run_sweep(range(args.first, args.first + args.count), args.out, args.nnz_cap, args.max_rows_exp)
     elif args.cmd == "fit":
         m = fit_model(args.csv, args.out)

@@ -46,8 +46,11 @@ def check_plan_and_product(A, sh):
         return False
     plan = S.seer_spmv_prepare(S.CSR_S, dA)
     assert plan.kernel_id == S.CSR_S and plan.n_blocks == want["n_slabs"]
-    rp_v, ci, va = plan.slab_arrays()
-    assert np.array_equal(rp_v.astype(np.int64), want["rp_v"]), f"{A.name}: virtual row offsets differ"
+    assert int(plan.c.split_rows) == len(want["rp_z"]) - 1, f"{A.name}: number of kept virtual rows"
+    rp_z, p_idx, rp_j, ci, va = plan.slab_arrays(A.cols)
+    assert np.array_equal(rp_z.astype(np.int64), want["rp_z"]), f"{A.name}: kept virtual rows' offsets differ"
+    assert np.array_equal(rp_j.astype(np.int64), want["rp_j"]) and np.array_equal(p_idx.astype(np.int64), want["p_idx"]), \
+        f"{A.name}: rows' piece lists differ"
     assert np.array_equal(ci, A.col_idx[want["perm"]]) and np.array_equal(va, A.values[want["perm"]]), \
         f"{A.name}: slabbed entries differ"
     x = G.dense_vector(A.cols, 3)
@@ -72,7 +75,7 @@ def test_default_slab_size_on_a_matrix_with_several_slabs():
     """Slabs of 2^19 columns as shipped: 1.3 M columns are three slabs; rows of 0 to 30 entries."""
     A = G.random_lengths(300_007, 1_300_000, 0, 30, 77)
     announce(f"CSR,S default shift {A.name} rows={A.rows} cols={A.cols} nnz={A.nnz}")
-    assert S.slab_plan_bytes(A.rows, A.cols, A.nnz) > 8 * A.nnz + 4 * 3 * A.rows
+    assert S.slab_plan_bytes(A.rows, A.cols, A.nnz) > 8 * A.nnz + 8 * 3 * A.rows
     assert check_plan_and_product(A, O.SLAB_SHIFT)
 
 

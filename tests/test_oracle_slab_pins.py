@@ -23,6 +23,9 @@ def test_worked_case():
     # slab 0: row 0 {1}, row 1 {}, row 2 {0, 3}; slab 1: row 0 {5, 6}, row 1 {}, row 2 {4}
     assert p["rp_v"].tolist() == [0, 1, 1, 3, 5, 5, 6]
     assert p["perm"].tolist() == [0, 3, 4, 1, 2, 5]
+    # kept: virtual rows 0, 2, 3, 5; row 0 owns kept rows 0 and 2, row 1 none, row 2 owns 1 and 3
+    assert p["rp_z"].tolist() == [0, 1, 3, 5, 6]
+    assert p["rp_j"].tolist() == [0, 2, 2, 4] and p["p_idx"].tolist() == [0, 2, 1, 3]
 
 
 def test_brute_force_restatement():
@@ -42,6 +45,12 @@ def test_brute_force_restatement():
                 want_rp.append(len(want_perm))
         assert p["perm"].tolist() == want_perm and p["rp_v"].tolist() == want_rp
         assert sorted(want_perm) == list(range(A.nnz))            # every entry exactly once
+        # the kept rows and each row's pieces, the slow way
+        kept = [v for v in range(S * A.rows) if want_rp[v + 1] > want_rp[v]]
+        assert p["rp_z"].tolist() == [want_rp[v] for v in kept] + [A.nnz]
+        pieces = [[j for j, v in enumerate(kept) if v % A.rows == i] for i in range(A.rows)]
+        assert p["p_idx"].tolist() == [j for pc in pieces for j in pc]
+        assert p["rp_j"].tolist() == [0] + list(np.cumsum([len(pc) for pc in pieces]))
 
 
 def test_literal_product_equals_row_sums():
@@ -54,13 +63,14 @@ def test_literal_product_equals_row_sums():
         got = O.slab_spmv_python(A.rows, p, A.col_idx, vals.tolist(), x.tolist())
         want = [int(sum(vals[k] * x[A.col_idx[k]] for k in range(A.row_ptr[i], A.row_ptr[i + 1]))) for i in range(A.rows)]
         assert got == want
-        # and a planted mistake is caught: one offset moved by one hands an entry to the wrong row
-        inner = [v for v in range(1, p["n_slabs"] * A.rows) if v % A.rows and p["rp_v"][v] > p["rp_v"][v - 1]]
-        v = inner[0]
-        bad = {"n_slabs": p["n_slabs"], "perm": p["perm"], "rp_v": p["rp_v"].copy()}
-        bad["rp_v"][v] -= 1                               # the last entry of virtual row v - 1 now counts for row v
-        k = int(p["perm"][bad["rp_v"][v]])
-        if vals[k] * x[A.col_idx[k]] != 0:
+        # and a planted mistake is caught: one offset moved by one hands an entry to the wrong piece
+        bad = dict(p)
+        bad["rp_z"] = p["rp_z"].copy()
+        j = next(j for j in range(1, len(p["rp_z"]) - 1) if p["rp_z"][j] - p["rp_z"][j - 1] > 0)
+        bad["rp_z"][j] -= 1                               # the last entry of kept row j - 1 now counts for kept row j
+        k = int(p["perm"][bad["rp_z"][j]])
+        owners = {int(pj): i for i in range(A.rows) for pj in p["p_idx"][p["rp_j"][i]:p["rp_j"][i + 1]]}
+        if vals[k] * x[A.col_idx[k]] != 0 and owners[j] != owners[j - 1]:
             assert O.slab_spmv_python(A.rows, bad, A.col_idx, vals.tolist(), x.tolist()) != want
 
 
@@ -83,3 +93,4 @@ def test_default_slab_is_two_mebibytes_of_x():
                   np.ones(3, np.float32), "three-slabs")
     p = O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx)
     assert p["n_slabs"] == 3 and p["rp_v"].tolist() == [0, 1, 1, 1, 1, 2, 2, 2, 2, 3] and p["perm"].tolist() == [0, 1, 2]
+    assert p["rp_z"].tolist() == [0, 1, 2, 3] and p["rp_j"].tolist() == [0, 1, 2, 3] and p["p_idx"].tolist() == [0, 1, 2]
