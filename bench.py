@@ -186,7 +186,8 @@ def time_spmv_graph(kid, rot, reps, replays=3, prepared=False):
     with torch.cuda.graph(g):
         for i in range(reps):
             launch(i)
-    g.replay()
+    for _ in range(2):          # untimed: the first replays after other work run up to 2 % slower (clocks, caches)
+        g.replay()
     torch.cuda.synchronize()
     total = 0.0
     for _ in range(replays):
@@ -463,7 +464,7 @@ def main():
     # launches on the same rotating copies, replayed from one HIP graph between two HIP
     # events, so that the figure is kernel time, free of launch gaps.
     rk = kid if args.roofline_kernel < 0 else args.roofline_kernel
-    spmv_avg_us = time_spmv_graph(rk, rot, args.steps, prepared=rk not in S.ONE_CALL_KERNELS or
+    spmv_avg_us = time_spmv_graph(rk, rot, args.steps, replays=5, prepared=rk not in S.ONE_CALL_KERNELS or
                                   (rk >= S.NUM_DIRECT_KERNELS and args.roofline_kernel >= 0))
     achieved = mb / (spmv_avg_us * 1e-6) / 1e9
     prof = load_profile_summaries(args.workload + ("" if args.roofline_kernel < 0 else f"_k{rk}"), S.kernel_name(rk))
