@@ -287,7 +287,8 @@ def selector_eval(model, meta, count):
         y = torch.empty(dA.rows, device="cuda:0")
         tk.append([T.time_kernel_us(k, dA, x, y, ws) for k in range(S.NUM_DIRECT_KERNELS)])
         ta.append(T.time_graph_us(lambda: S.seer_spmv_auto(dA, model.gathered, x, y, ws)))
-        tm.append(T.time_graph_us(lambda: S.seer_spmv_model(dA, model, x, y, ws)))
+        tm.append(T.time_graph_us(lambda: S.seer_spmv_model(dA, model, x, y, ws))
+                  + S.seer_model_host_ns(model, dA.rows, dA.cols, dA.nnz) * 1e-3)   # + its host-side decision
         del rp, ci, va, x, dA, y, ws
     import numpy as np
     tk, ta, tm = np.array(tk), np.array(ta), np.array(tm)
@@ -295,6 +296,9 @@ def selector_eval(model, meta, count):
     best = int(np.argmin(fixed))
     geo = lambda a, b: float(np.exp(np.mean(np.log(a / b))))
     return {
+        "protocol": "every path by one protocol (10 eager warm-up calls, 10 calls in one HIP graph, one untimed replay, "
+                    "median of three timed replays), same buffers (warm); the classifier-selection path includes its "
+                    "host-side decision (wall clock)",
         "matrices": len(tk), "best_fixed_kernel": S.kernel_name(best),
         "t_fixed_us": [round(float(v), 1) for v in fixed], "t_oracle_us": round(float(tk.min(axis=1).sum()), 1),
         "t_always_gather_us": round(float(ta.sum()), 1), "t_classifier_selection_us": round(float(tm.sum()), 1),

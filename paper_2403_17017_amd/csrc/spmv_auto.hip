@@ -2,17 +2,19 @@
 // run the chosen kernel -- as a few launches with no host round trip in between:
 //
 //   1. the feature reduction (one launch for a small matrix, two for a large one);
-//      its finishing workgroup (features_select_kernel) derives the feature vector
-//      on the device, walks the tree (handed over by value in the kernel arguments)
-//      and leaves the chosen kernel id in device memory;
+//      its finishing launch -- a single wave after a first pass, a workgroup for a small
+//      matrix -- derives the feature vector on the device, walks the tree (handed over by
+//      value in the kernel arguments) and leaves the chosen kernel id in device memory;
 //   2. spmv_auto_kernel: one kernel that contains the five CSR schedules that need no
 //      preprocessing; every workgroup reads the chosen id and runs that schedule's
-//      body (the grid is sized for the schedule that needs the most workgroups, the
-//      rest exit);
+//      body (the grid is sized for the reachable schedule that needs the most workgroups,
+//      the rest exit);
 //   3. spmv_auto_fixup_kernel: the carry fix-up of merge path and of the nonzero
-//      split; exits at once unless one of them was chosen.
+//      split; exits at once unless one of them was chosen, and is not enqueued at all if
+//      the host can tell from rows, cols and nnz that the tree cannot answer either.
 // When the product's grid is small, steps 1 and 2 share a launch (or, for a small
-// matrix, are one launch): see spmv_auto_fused_kernel.
+// matrix, are one launch): see spmv_auto_fused_kernel.  When the known features leave the
+// tree a single answer, step 1 is dropped: see spmv_auto_decided_kernel.
 //
 // The host only enqueues; feature collection costs the reduction kernel itself
 // instead of a launch, a wait and a second launch.  The sequence has no host-side
@@ -371,12 +373,11 @@ __global__ __launch_bounds__(kWG) void spmv_auto_decided_kernel(
 // the same feature vector, walks the same tree, and hands the kernel id to the other waves
 // through LDS; then the workgroup runs its share of the chosen schedule.  The redundant work
 // is a few hundred instructions of one wave behind one load of two kilobytes that hits L2,
-// about what reading the choice of a selection launch costs; that launch itself costs the
-// path four to five microseconds.  Workgroup 0 leaves the record for seer_spmv_auto_result
-// and the fix-up kernel.
-// (An earlier form folded with LDS atomics between barriers and derived on a single lane; it
-// cost each workgroup two to three microseconds and only paid off for grids of up to a
-// thousand workgroups.)
+// while a selection launch costs the path about three microseconds.  Workgroup 0 leaves the
+// record for seer_spmv_auto_result and the fix-up kernel.
+// Used for grids of up to about a thousand workgroups.  Beyond, it was measured slower than
+// the separate launch (a 54 MB stencil: 24.4 us per step against 22.8; the product itself
+// 17.2 against 13.0 us, and a first pass of 64 fat workgroups 6.3 against 4.6 us for 512).
 template <int IPT, bool VEC, bool RPVEC>
 __global__ __launch_bounds__(kWG) void spmv_auto_fused_kernel(
     int rows, int cols, int nnz, const int *__restrict__ rp, const int *__restrict__ ci,

@@ -51,7 +51,10 @@ CSV_FIELDS = (["m", "family", "rows", "cols", "nnz"] + [f"f_{n}" for n in S.FEAT
               + ["t_features_us"] + [f"t_k{k}_us" for k in range(S.NUM_KERNELS)]
               + [f"t_prep_k{k}_us" for k in PREP_KERNELS] + [f"t_single_k{k}_us" for k in PREP_KERNELS]
               + [f"t_rep_k{k}_us" for k in range(S.NUM_DIRECT_KERNELS)]
-              + ["t_auto_mp_us", "max_disagreement"])
+              + ["t_auto_mp_us", "max_disagreement"]
+              # one product with operands that are not in any cache (rotating copies): what the
+              # single-product models are fitted to when the sweep has these columns
+              + [f"t_cold_k{k}_us" for k in range(S.NUM_DIRECT_KERNELS)] + ["t_cold_auto_mp_us", "cold_sets"])
 KNOWN_IDX = [0, 1, 2, 3, 8]   # rows, cols, nnz, mean_len, mean_density: what seer_known_features fills
 KNOWN_ITER_IDX = KNOWN_IDX + [S.F_ITERATIONS]
 ITER_GRID = [1, 2, 3, 5, 8, 12, 19, 30, 50, 100]   # iteration counts the iterative models are trained on
@@ -229,6 +232,46 @@ def measure_matrix(spec, device="cuda:0", extra=None):
     return row
 
 
+def measure_cold_only(spec, device="cuda:0"):
+    """The cold columns of a sweep row alone: every kernel without preprocessing, and the
+    asynchronous path with a one-leaf merge-path tree (its excess over the bare kernel is the
+    cost of gathering and selecting), each call on the next of several copies of (A, x, y)."""
+    import torch
+
+    from workloads.sweep_gen import build_on_device
+    rp, ci, va, x = build_on_device(spec, device)
+    dA = S.DeviceCSR(spec.rows, spec.rows, rp, ci, va, int(ci.numel()))
+    ws = S.alloc_workspace(max([S.spmv_auto_workspace_bytes(dA.rows, dA.nnz)]
+                               + [S.spmv_workspace_bytes(k, dA.rows, dA.nnz) for k in range(ND)]), device)
+    y = torch.empty(dA.rows, device=device)
+    sets = cold_sets(dA, x, y, ws)
+    row = {"m": spec.m, "cold_sets": len(sets)}
+    for k in range(ND):
+        row[f"t_cold_k{k}_us"] = round(time_graph_cold_us(lambda d, xx, yy, w_: S.seer_spmv(k, d, xx, yy, workspace=w_), sets), 3)
+    mp_only = S.Tree.constant(S.CSR_MP)
+    S.set_tuning("auto_prune", 0)
+    try:
+        row["t_cold_auto_mp_us"] = round(time_graph_cold_us(lambda d, xx, yy, w_: S.seer_spmv_auto(d, mp_only, xx, yy, w_), sets), 3)
+    finally:
+        S.set_tuning("auto_prune", -1)
+    return row
+
+
+def run_cold_sweep(ms, out_csv, nnz_cap=200_000_000, max_rows_exp=7.0, log=sys.stderr):
+    from workloads.sweep_gen import sweep_spec
+    fields = ["m", "cold_sets"] + [f"t_cold_k{k}_us" for k in range(ND)] + ["t_cold_auto_mp_us"]
+    with open(out_csv, "w", newline="") as fh:
+        w = csv.DictWriter(fh, fieldnames=fields)
+        w.writeheader()
+        t_start = time.time()
+        for m in ms:
+            row = measure_cold_only(sweep_spec(m, nnz_cap, max_rows_exp))
+            w.writerow(row)
+            fh.flush()
+            print(f"[sweep-cold] m={m} x{row['cold_sets']} t={[row[f't_cold_k{k}_us'] for k in range(ND)]} "
+                  f"auto={row['t_cold_auto_mp_us']} ({time.time() - t_start:.0f}s)", file=log, flush=True)
+
+
 def measure_slab_only(spec, device="cuda:0"):
     """The CSR,S columns of a sweep row alone (same matrix, same protocol): for adding the
     kernel to a sweep that was run before it existed."""
@@ -346,7 +389,7 @@ def load_prep(rows):
     return P
 
 
-def gather_overhead_us(rows_csv, T):
+def gather_overhead_us(rows_csv, T, field="t_auto_mp_us"):
     """Device-side cost of gathering + selecting per matrix, from the sweep: the excess
     of the asynchronous path (constant merge-path tree) over the bare merge-path kernel.
     Where the kernel is short the difference is taken as measured (the path has three
@@ -354,7 +397,7 @@ def gather_overhead_us(rows_csv, T):
     microseconds single timings are noisier than the few microseconds being estimated,
     and a least-squares line in the number of rows through the short ones stands in."""
     r = np.array([float(x["rows"]) for x in rows_csv])
-    d = np.array([float(x["t_auto_mp_us"]) for x in rows_csv]) - T[:, S.CSR_MP]
+    d = np.array([float(x[field]) for x in rows_csv]) - T[:, S.CSR_MP]
     keep = T[:, S.CSR_MP] < 200.0            # short kernels give clean differences
     A = np.stack([np.ones(keep.sum()), r[keep]], axis=1)
     (a, b), *_ = np.linalg.lstsq(A, d[keep], rcond=None)
@@ -576,10 +619,16 @@ def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
     rows, X, T_all, tf = load_csv(csv_path)
     P = load_prep(rows)
     T = T_all[:, :ND]               # the single-product models choose among the kernels without preprocessing
+    cold = bool(rows) and rows[0].get("t_cold_k0_us") not in ("", None)
+    if cold:
+        # A single product finds nothing of the matrix in the caches; several products with one
+        # matrix (the iterative models below) do, if it fits.  The single-product models are
+        # therefore fitted to the cold timings where the sweep has them.
+        T = np.array([[float(r[f"t_cold_k{k}_us"]) for k in range(ND)] for r in rows])
     y = T.argmin(axis=1)            # label = fastest kernel; ties -> lowest kernel id
     idx = np.arange(len(rows))
     tr, te = train_test_split(idx, test_size=test_frac, random_state=seed)
-    ovh, ovh_fit = gather_overhead_us(rows, T)
+    ovh, ovh_fit = gather_overhead_us(rows, T, "t_cold_auto_mp_us" if cold else "t_auto_mp_us")
     Xk = np.zeros_like(X)
     Xk[:, KNOWN_IDX] = X[:, KNOWN_IDX]          # what the known-features vector looks like at run time
     cost, imp = choice_costs(T)
@@ -602,7 +651,7 @@ def fit_model(csv_path, out_json, test_frac=0.2, seed=0):
     model = {
         "gathered": gathered, "known": known, "selector": selector,
         "note": f"CART gini max_depth={MAX_DEPTH} on costs = time lost + {RELATIVE_US:g} us * log slowdown, "
-                f"{len(tr)} training matrices",
+                f"{len(tr)} training matrices" + (", single-product models on cold timings" if cold else ""),
         "feature_names": list(S.FEATURE_NAMES), "known_features": KNOWN_IDX,
         "gather_overhead_us": {"intercept": ovh_fit[0], "per_row": ovh_fit[1]},
         "label_counts": np.bincount(y, minlength=ND).tolist(),
@@ -783,8 +832,10 @@ def evaluate_iterative(model_json, out_csv, counts=ITER_EVAL_COUNTS, matrices=No
     fields = CSV_FIELDS + [f"{what}_n{n}" for n in counts for what in ("t_plan_us", "t_product_us", "kernel", "path")]
 
     def plan_path(dA, x, y, ws, row):
+        slab = S.slab_plan_bytes(dA.rows, dA.cols, dA.nnz)
         plan_mem = S.alloc_workspace(max(S.plan_bytes(S.CSR_A, dA.rows, dA.nnz), S.plan_bytes(S.COO_WM, dA.rows, dA.nnz),
-                                         min(12 * dA.nnz + (1 << 20), ELL_MAX_BYTES)))
+                                         min(12 * dA.nnz + (1 << 20), ELL_MAX_BYTES),
+                                         slab if slab <= 2 * ELL_MAX_BYTES else 0))     # (the sweep's own limit)
         for n in counts:
             for _ in range(2):
                 plan, path = S.seer_spmv_plan(dA, model, n, plan_mem, ws)
@@ -792,7 +843,9 @@ def evaluate_iterative(model_json, out_csv, counts=ITER_EVAL_COUNTS, matrices=No
             for _ in range(5):
                 plan, path = S.seer_spmv_plan(dA, model, n, plan_mem, ws)
             row[f"t_plan_us_n{n}"] = round((time.perf_counter() - t0) / 5 * 1e6, 3)
-            row[f"t_product_us_n{n}"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, ws)), 3)
+            need = S.spmv_prepared_workspace_bytes(plan)       # (CSR,S keeps its partials in the products' scratch)
+            wsp = ws if need <= ws.numel() else S.alloc_workspace(need)
+            row[f"t_product_us_n{n}"] = round(time_graph_us(lambda: S.seer_spmv_prepared(plan, dA, x, y, wsp)), 3)
             row[f"kernel_n{n}"], row[f"path_n{n}"] = plan.kernel_id, path
 
     with open(out_csv, "w", newline="") as fh:
@@ -1115,6 +1168,10 @@ def main(argv=None):
     a2.add_argument("--first", type=int, default=0)
     a2.add_argument("--count", type=int, default=3000)
     a2.add_argument("--out", default="sweep_slab.csv")
+    a4 = sub.add_parser("sweep-cold", help="the cold columns alone (kernels without preprocessing on rotating copies)")
+    a4.add_argument("--first", type=int, default=0)
+    a4.add_argument("--count", type=int, default=3000)
+    a4.add_argument("--out", default="sweep_cold.csv")
     a3 = sub.add_parser("merge")
     a3.add_argument("--csv", required=True)
     a3.add_argument("--extra", required=True)
@@ -1151,7 +1208,9 @@ def main(argv=None):
     if args.cmd == "export-header":
         print(export_header(args.model, args.out))
         return
-    if args.cmd == "sweep-slab":
+    if args.cmd == "sweep-cold":
+        run_cold_sweep(range(args.first, args.first + args.count), args.out)
+    elif args.cmd == "sweep-slab":
         run_slab_sweep(range(args.first, args.first + args.count), args.out)
     elif args.cmd == "merge":
         print(merge_columns(args.csv, args.extra, args.out))
