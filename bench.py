@@ -332,7 +332,8 @@ def config_row(name, what, tree, rot=None):
         del A, x
     d0 = rot[0][0]
     mb = 8 * d0.nnz + 4 * (d0.rows + 1) + 4 * d0.cols + 4 * d0.rows
-    reps = max(rot.n, 20) if mb < 100e6 else (5 if mb < 1e9 else 3)
+    # enough launches per replay that the replay's own fixed cost (about 10 us) stays under 1 % of it
+    reps = 200 if mb < 100e6 else (20 if mb < 1e9 else 3)
     per = {}
     for k in range(S.NUM_DIRECT_KERNELS):
         per[S.kernel_name(k)] = round(time_spmv_graph(k, rot, reps, replays=2 if mb > 1e9 else 3), 2)
@@ -495,9 +496,11 @@ def main():
     if not args.no_extras:
         extras = {"per_kernel_cold_us": {}, "per_kernel_warm_us": {}}
         warm = Rotation(A, x, 1)
+        # launches per replay, as in config_row: the replay's fixed cost must stay small beside them
+        table_reps = 200 if mb < 100e6 else (20 if mb < 1e9 else 3)
         for k in S.ONE_CALL_KERNELS:
-            c = time_spmv_graph(k, rot, max(n_sets, 20))
-            w = time_spmv_graph(k, warm, max(n_sets, 20))
+            c = time_spmv_graph(k, rot, table_reps)
+            w = time_spmv_graph(k, warm, table_reps)
             extras["per_kernel_cold_us"][S.kernel_name(k)] = round(c, 2)
             extras["per_kernel_warm_us"][S.kernel_name(k)] = round(w, 2)
         best = min(extras["per_kernel_cold_us"].values())
@@ -513,7 +516,7 @@ def main():
                 plans = [S.seer_spmv_prepare(k, R[i][0]) for i in range(R.n)]
                 # (a plan's products may need more scratch than the one-call kernels: CSR,S keeps its partials there)
                 wss = [S.alloc_workspace(max(S.spmv_prepared_workspace_bytes(p_), 256)) for p_ in plans]
-                reps = max(n_sets, 20)
+                reps = table_reps
 
                 def enqueue_all():
                     for i in range(reps):

@@ -939,11 +939,12 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
          "--model selector_model.json --eval eval.csv" + (" --fresh-eval eval_fresh.csv" if fresh_csv else "") +
          (" --iterative-eval eval_iterative.csv" if iter_csv else "") + " --out profiles/selector_evaluation.md", "",
          f"Population: {len(rows)} seeded synthetic matrices (workloads/sweep_gen.py), timing 10 warm-up + 10 timed "
-         "runs per kernel by one protocol for all eight (HIP-graph replay after an untimed replay), same buffers "
-         "(warm).  CSR,A, ELL,TM and COO,WM are timed with a prepared plan; "
+         "runs per kernel by one protocol for all nine (HIP-graph replay after an untimed replay), same buffers "
+         "(warm); the kernels without preprocessing also on rotating copies (cold columns).  CSR,A, ELL,TM, COO,WM "
+         "and CSR,S are timed with a prepared plan; "
          "their preprocessing calls are timed apart (host wall clock, they wait for the device).  Where the ELL "
-         "form is not applicable (beyond 2 GiB here) ELL,TM is charged what CSR,A costs: that is what "
-         "seer_spmv_plan falls back to.", "",
+         "form (beyond 2 GiB here) or the slabbed form (x within one slab, columns not ascending) is not "
+         "applicable the kernel is charged what CSR,A costs: that is what seer_spmv_plan falls back to.", "",
          f"## Sweep (all {len(rows)} matrices), sum of kernel times in us", "",
          "| family | matrices | " + " | ".join(names) + " | best per matrix (direct kernels) | fastest direct kernel counts |",
          "|---|---|" + "---|" * (len(names) + 2)]
