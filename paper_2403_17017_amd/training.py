@@ -316,9 +316,9 @@ def run_slab_sweep(ms, out_csv, nnz_cap=200_000_000, max_rows_exp=7.0, log=sys.s
 
 def merge_columns(base_csv, extra_csv, out_csv):
     """base_csv with the columns of extra_csv (matched by sweep number m) filled in."""
-    with open(extra_csv) as fh:
+    with open_text(extra_csv) as fh:
         extra = {int(r["m"]): r for r in csv.DictReader(fh)}
-    with open(base_csv) as fh:
+    with open_text(base_csv) as fh:
         rows = list(csv.DictReader(fh))
     with open(out_csv, "w", newline="") as fh:
         w = csv.DictWriter(fh, fieldnames=CSV_FIELDS)
@@ -354,8 +354,17 @@ def run_sweep(ms, out_csv, nnz_cap=200_000_000, max_rows_exp=7.0, log=sys.stderr
                   f"({time.time() - t_start:.0f}s)", file=log, flush=True)
 
 
+def open_text(path):
+    """A CSV for reading; a name ending in .gz is read through gzip (the sweep behind the
+    shipped models is committed that way)."""
+    if str(path).endswith(".gz"):
+        import gzip
+        return gzip.open(path, "rt", newline="")
+    return open(path, newline="")
+
+
 def load_csv(path):
-    with open(path) as fh:
+    with open_text(path) as fh:
         rows = list(csv.DictReader(fh))
     X = np.array([[float(r[f"f_{n}"]) for n in S.FEATURE_NAMES] for r in rows], dtype=np.float32)
     T = np.array([[float(r.get(f"t_k{k}_us") or "inf") for k in range(S.NUM_KERNELS)] for r in rows])
@@ -931,13 +940,18 @@ def write_report_md(csv_path, model_json, eval_csv, out_md, fresh_csv=None, iter
     names = [S.kernel_name(k) for k in range(S.NUM_KERNELS)]
     L = ["# Selector: sweep, training and held-out evaluation (MI355X)", "",
          "Commands (GPU box, repository root):", "",
-         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 3000 --out sweep.csv",
+         "    python -m paper_2403_17017_amd.training sweep --first 0 --count 3000 --out sweep_warm.csv",
+         "    python -m paper_2403_17017_amd.training sweep-cold --first 0 --count 3000 --out sweep_cold.csv",
+         "    python -m paper_2403_17017_amd.training merge --csv sweep_warm.csv --extra sweep_cold.csv --out sweep.csv",
          "    python -m paper_2403_17017_amd.training fit --csv sweep.csv --out selector_model.json",
          "    python -m paper_2403_17017_amd.training evaluate --csv sweep.csv "
          "--model selector_model.json --out eval.csv",
          "    python -m paper_2403_17017_amd.training report-md --csv sweep.csv "
          "--model selector_model.json --eval eval.csv" + (" --fresh-eval eval_fresh.csv" if fresh_csv else "") +
          (" --iterative-eval eval_iterative.csv" if iter_csv else "") + " --out profiles/selector_evaluation.md", "",
+         "The sweep.csv behind the shipped models is committed as paper_2403_17017_amd/selector_sweep.csv.gz "
+         "(every --csv option reads it as it is); `fit` on it gives the committed selector_model.json again "
+         "(tests/test_training_host.py).", "",
          f"Population: {len(rows)} seeded synthetic matrices (workloads/sweep_gen.py), timing 10 warm-up + 10 timed "
          "runs per kernel by one protocol for all nine (HIP-graph replay after an untimed replay), same buffers "
          "(warm); the kernels without preprocessing also on rotating copies (cold columns).  CSR,A, ELL,TM, COO,WM "

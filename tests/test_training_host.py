@@ -143,3 +143,16 @@ def test_committed_header_is_the_export_of_the_committed_model(tmp_path):
     fresh = T.export_header(os.path.join(here, "selector_model.json"), str(tmp_path / "fresh.h"))
     with open(fresh) as a, open(os.path.join(here, "selector_model_generated.h")) as b:
         assert a.read() == b.read(), "run `python -m paper_2403_17017_amd.training export-header` and rebuild"
+
+
+def test_committed_model_is_the_fit_of_the_committed_sweep(tmp_path):
+    """The shipped trees can be derived again from what the repository holds:
+    selector_sweep.csv.gz (the timings of the 3000-matrix sweep, warm and cold columns,
+    all nine kernels) fitted by `training fit` gives selector_model.json, value for value."""
+    import json
+    import os
+    here = os.path.dirname(T.__file__)
+    out = str(tmp_path / "refit.json")
+    T.fit_model(os.path.join(here, "selector_sweep.csv.gz"), out)
+    with open(out) as a, open(os.path.join(here, "selector_model.json")) as b:
+        assert json.load(a) == json.load(b)
