@@ -26,14 +26,22 @@
 
 namespace seer {
 
-constexpr uint32_t kSlabLongRow = 32;       // rows beyond this are cut and copied by their whole wave
+constexpr uint32_t kSlabRun = 1024;         // entries a wave takes at least: one binary search per run
+constexpr uint32_t kSlabGrid = 2048;        // workgroups of the two passes over the entries
 constexpr uint32_t kScanItems = 8;          // per lane of the prefix sum
 constexpr uint32_t kScanTile = kWG * kScanItems;
 
-// ---- preprocessing 1: entries per virtual row, and whether every row's columns ascend.
-// cnt [S * rows + 1] is zero on entry; *descends is set if some row's columns do not ascend.
-// Lane <-> row; a short row is walked entry by entry (its slab ids ascend with its columns, so
-// it is a few runs), a long one is cut by binary searches for the slab boundaries, lane <-> slab.
+// ---- preprocessing 1 and 3 walk the entries, not the rows: lane <-> entry, 64 at a time, every
+// wave an equal contiguous run of the whole matrix, with the row of each entry read from its
+// expansion crow[] (what COO,WM's conversion writes).  A "piece" is the stretch of a row that
+// falls into one slab: it starts where the row or the slab id changes.  For every entry the
+// first entry of its piece is the last such place at or before it -- found among the lanes by
+// a ballot, carried over from step to step, and for the piece that is under way where the
+// wave's run begins by one binary search in that row.
+// (Lane <-> row, as the first version went, a short row is walked by one lane through cache
+// lines that 63 other rows compete for, and a long one is left to one wave: 12 ms for a
+// uniform matrix of 8 M rows and 1.9e8 nonzeros whose entries can be moved in under a
+// millisecond, 3 ms for a 2 M-row Zipf matrix with rows of 200 000.)
 __device__ __forceinline__ uint32_t slab_lower_bound(const int *__restrict__ ci, uint32_t a, uint32_t e, uint64_t key)
 {
     while (a < e) {                          // first k in [a, e) with ci[k] >= key
@@ -43,49 +51,90 @@ __device__ __forceinline__ uint32_t slab_lower_bound(const int *__restrict__ ci,
     return a;
 }
 
-__global__ __launch_bounds__(kWG) void slab_count_kernel(
-    int rows, int shift, uint32_t n_slabs, const int *__restrict__ rp, const int *__restrict__ ci,
-    uint32_t *__restrict__ cnt, int *__restrict__ descends)
+struct SlabWalk {
+    uint32_t k0, k1;                         // this wave's run of entries
+    uint32_t last_i, last_s;                 // row and slab of the entry before the step (none: row 0xFFFFFFFF)
+    int last_c;                              // ... and its column
+    uint32_t cur_start;                      // first entry of that entry's piece
+};
+
+__device__ __forceinline__ SlabWalk slab_walk_begin(
+    uint32_t nnz, int shift, uint32_t n_slabs, const int *__restrict__ rp, const int *__restrict__ ci,
+    const int *__restrict__ crow)
 {
-    const uint32_t i = blockIdx.x * kWG + threadIdx.x, lane = threadIdx.x % kWave;
-    uint32_t a = 0, e = 0;
-    if (i < (uint32_t)rows) {
-        a = (uint32_t)rp[i];
-        e = (uint32_t)rp[i + 1];
+    const uint32_t n_waves = gridDim.x * (kWG / kWave), wv = blockIdx.x * (kWG / kWave) + threadIdx.x / kWave;
+    const uint32_t per = (((nnz + n_waves - 1u) / n_waves) + kWave - 1u) & ~(uint32_t)(kWave - 1u);
+    const uint64_t first = (uint64_t)wv * per;
+    SlabWalk w;
+    w.k0 = first < nnz ? (uint32_t)first : nnz;
+    w.k1 = first + per < nnz ? (uint32_t)(first + per) : nnz;
+    w.last_i = 0xFFFFFFFFu;
+    w.last_s = 0;
+    w.last_c = 0;
+    w.cur_start = w.k0;
+    if (w.k0 > 0 && w.k0 < w.k1) {
+        w.last_i = (uint32_t)crow[w.k0 - 1];
+        w.last_c = ci[w.k0 - 1];
+        w.last_s = min((uint32_t)w.last_c >> shift, n_slabs - 1u);
+        w.cur_start = slab_lower_bound(ci, (uint32_t)rp[w.last_i], w.k0, (uint64_t)w.last_s << shift);
     }
+    return w;
+}
+
+// One step: the lane's entry (row i, column c, slab s), whether it is valid, and the first
+// entry of its piece.  Updates the carry.  All lanes of the wave call it together.
+__device__ __forceinline__ uint32_t slab_walk_step(
+    SlabWalk &w, uint32_t base, uint32_t lane, int shift, uint32_t n_slabs, const int *__restrict__ ci,
+    const int *__restrict__ crow, bool &valid, uint32_t &i, int &c, uint32_t &s, bool &descends)
+{
+    const uint32_t k = base + lane;
+    valid = k < w.k1;
+    i = valid ? (uint32_t)crow[k] : 0u;
+    c = valid ? ci[k] : 0;
+    s = min((uint32_t)c >> shift, n_slabs - 1u);
+    uint32_t pi = (uint32_t)__shfl_up((int)i, 1), ps = (uint32_t)__shfl_up((int)s, 1);
+    int pc = __shfl_up(c, 1);
+    if (lane == 0) { pi = w.last_i; ps = w.last_s; pc = w.last_c; }
+    const bool starts = valid && (i != pi || s != ps);
+    descends = valid && i == pi && c < pc;
+    const uint64_t mask = __ballot(starts);
+    const uint64_t upto = mask & (lane == kWave - 1 ? ~0ull : ((1ull << (lane + 1u)) - 1ull));
+    const uint32_t mine = upto ? base + 63u - (uint32_t)__clzll((long long)upto) : w.cur_start;
+    if (mask) w.cur_start = base + 63u - (uint32_t)__clzll((long long)mask);
+    const int last = (int)min(w.k1 - base, (uint32_t)kWave) - 1;
+    w.last_i = (uint32_t)__shfl((int)i, last);
+    w.last_s = (uint32_t)__shfl((int)s, last);
+    w.last_c = __shfl(c, last);
+    return mine;
+}
+
+// preprocessing 1: entries per virtual row (cnt [S * rows + 1], zero on entry), written by the
+// last entry of each piece; *flag is set if some row's columns do not ascend or lie outside
+// the matrix (then the form is refused instead of written out of bounds).
+__global__ __launch_bounds__(kWG) void slab_count_kernel(
+    int rows, int cols, uint32_t nnz, int shift, uint32_t n_slabs, const int *__restrict__ rp,
+    const int *__restrict__ ci, const int *__restrict__ crow, uint32_t *__restrict__ cnt, int *__restrict__ flag)
+{
+    const uint32_t lane = threadIdx.x % kWave;
+    SlabWalk w = slab_walk_begin(nnz, shift, n_slabs, rp, ci, crow);
     bool bad = false;
-    const bool is_long = e - a > kSlabLongRow;
-    if (!is_long && e > a) {
-        uint32_t cur = (uint32_t)ci[a] >> shift, run = 0;
-        int prev = ci[a];
-        for (uint32_t k = a; k < e; ++k) {
-            const int c = ci[k];
-            bad |= c < prev;
-            prev = c;
-            const uint32_t s = (uint32_t)c >> shift;
-            if (s != cur) {
-                cnt[(size_t)cur * (uint32_t)rows + i] = run;
-                cur = s;
-                run = 0;
-            }
-            ++run;
+    for (uint32_t base = w.k0; base < w.k1; base += kWave) {       // wave-uniform
+        bool valid, desc;
+        uint32_t i, s;
+        int c;
+        const uint32_t mine = slab_walk_step(w, base, lane, shift, n_slabs, ci, crow, valid, i, c, s, desc);
+        bad |= desc || (valid && (uint32_t)c >= (uint32_t)cols);
+        if (!valid) continue;
+        const uint32_t k = base + lane;
+        bool ends = k + 1u == nnz;
+        if (!ends) {
+            const uint32_t ni = (uint32_t)crow[k + 1u];
+            const uint32_t ns = min((uint32_t)ci[k + 1u] >> shift, n_slabs - 1u);
+            ends = ni != i || ns != s;
         }
-        cnt[(size_t)cur * (uint32_t)rows + i] = run;
+        if (ends) cnt[(size_t)s * (uint32_t)rows + i] = k + 1u - mine;
     }
-    uint64_t todo = __ballot(is_long);
-    while (todo) {                                   // wave-uniform
-        const int src = __ffsll((unsigned long long)todo) - 1;
-        todo &= todo - 1;
-        const uint32_t si = (uint32_t)__shfl((int)i, src), sa = (uint32_t)__shfl((int)a, src);
-        const uint32_t se = (uint32_t)__shfl((int)e, src);
-        for (uint32_t k = sa + 1u + lane; k < se; k += kWave) bad |= ci[k] < ci[k - 1];
-        for (uint32_t s = lane; s < n_slabs; s += kWave) {
-            const uint32_t lo = s == 0 ? sa : slab_lower_bound(ci, sa, se, (uint64_t)s << shift);
-            const uint32_t hi = s + 1u == n_slabs ? se : slab_lower_bound(ci, sa, se, (uint64_t)(s + 1u) << shift);
-            if (hi > lo) cnt[(size_t)s * (uint32_t)rows + si] = hi - lo;
-        }
-    }
-    if (bad) *descends = 1;
+    if (bad) *flag = 1;
 }
 
 // ---- preprocessing 2: exclusive prefix sum over n unsigned words, in place, in three kinds
@@ -157,47 +206,25 @@ static void launch_scan_exclusive(uint32_t *data, size_t n, uint32_t *scratch, h
     hipLaunchKernelGGL(scan_tiles_kernel, dim3((uint32_t)nb), dim3(kWG), 0, st, data, n, static_cast<const uint32_t *>(scratch));
 }
 
-// ---- preprocessing 3: the entries into their places.  rp_v holds the finished offsets.
+// ---- preprocessing 3: the entries into their places.  rp_v holds the finished offsets: an
+// entry goes to (start of its virtual row) + (its distance from the first entry of its piece).
 __global__ __launch_bounds__(kWG) void slab_scatter_kernel(
-    int rows, int shift, uint32_t n_slabs, const int *__restrict__ rp, const int *__restrict__ ci,
-    const float *__restrict__ va, const uint32_t *__restrict__ rp_v, int *__restrict__ out_ci, float *__restrict__ out_va)
+    int rows, uint32_t nnz, int shift, uint32_t n_slabs, const int *__restrict__ rp, const int *__restrict__ ci,
+    const float *__restrict__ va, const int *__restrict__ crow, const uint32_t *__restrict__ rp_v,
+    int *__restrict__ out_ci, float *__restrict__ out_va)
 {
-    const uint32_t i = blockIdx.x * kWG + threadIdx.x, lane = threadIdx.x % kWave;
-    uint32_t a = 0, e = 0;
-    if (i < (uint32_t)rows) {
-        a = (uint32_t)rp[i];
-        e = (uint32_t)rp[i + 1];
-    }
-    const bool is_long = e - a > kSlabLongRow;
-    if (!is_long && e > a) {
-        uint32_t cur = 0xFFFFFFFFu, dst = 0;
-        for (uint32_t k = a; k < e; ++k) {
-            const int c = ci[k];
-            const uint32_t s = (uint32_t)c >> shift;
-            if (s != cur) {
-                cur = s;
-                dst = rp_v[(size_t)s * (uint32_t)rows + i];
-            }
-            out_ci[dst] = c;
-            out_va[dst] = va[k];
-            ++dst;
-        }
-    }
-    uint64_t todo = __ballot(is_long);
-    while (todo) {                                   // wave-uniform
-        const int src = __ffsll((unsigned long long)todo) - 1;
-        todo &= todo - 1;
-        const uint32_t si = (uint32_t)__shfl((int)i, src);
-        uint32_t from = (uint32_t)__shfl((int)a, src);
-        for (uint32_t s = 0; s < n_slabs; ++s) {     // the row's pieces lie one after the other in it
-            const size_t v = (size_t)s * (uint32_t)rows + si;
-            const uint32_t d0 = rp_v[v], n = rp_v[v + 1] - d0;
-            for (uint32_t j = lane; j < n; j += kWave) {
-                out_ci[d0 + j] = ci[from + j];
-                out_va[d0 + j] = va[from + j];
-            }
-            from += n;
-        }
+    const uint32_t lane = threadIdx.x % kWave;
+    SlabWalk w = slab_walk_begin(nnz, shift, n_slabs, rp, ci, crow);
+    for (uint32_t base = w.k0; base < w.k1; base += kWave) {       // wave-uniform
+        bool valid, desc;
+        uint32_t i, s;
+        int c;
+        const uint32_t mine = slab_walk_step(w, base, lane, shift, n_slabs, ci, crow, valid, i, c, s, desc);
+        if (!valid) continue;
+        const uint32_t k = base + lane;
+        const uint32_t dst = rp_v[(size_t)s * (uint32_t)rows + i] + (k - mine);
+        out_ci[dst] = c;
+        out_va[dst] = va[k];
     }
 }
 
@@ -277,10 +304,11 @@ uint32_t slab_count(int rows, int cols, int shift)
 // virtual rows that can hold entries (min(nnz, S * rows)), so that the layout follows from the
 // sizes alone: rp_z, p_idx, rp_j, the slabbed col_idx, the slabbed values; then what only the
 // preprocessing uses: the offsets and the kept-row numbers of all S * rows virtual rows, the
-// prefix sums' tile sums, the flag.
+// row of every entry, the prefix
+// sums' tile sums, the flag.
 struct SlabLayout {
     size_t nv, max_kept;
-    size_t rp_z, p_idx, rp_j, ci, va, rp_v, num_v, scan, flag, total;
+    size_t rp_z, p_idx, rp_j, ci, va, rp_v, num_v, crow, scan, flag, total;
 };
 static SlabLayout slab_layout(uint32_t S, int rows, int nnz)
 {
@@ -295,6 +323,7 @@ static SlabLayout slab_layout(uint32_t S, int rows, int nnz)
     L.va = o;    o += pad256((size_t)nnz * 4 + 4);
     L.rp_v = o;  o += pad256(L.nv * 4);
     L.num_v = o; o += pad256(L.nv * 4);
+    L.crow = o;  o += pad256((size_t)nnz * 4 + 4);
     L.scan = o;  o += pad256(scan_scratch_words(L.nv) * 4 + 4);
     L.flag = o;  o += 256;
     L.total = o;
@@ -326,8 +355,15 @@ const uint32_t *slab_kept_count(const void *plan_mem, int rows, int cols, int nn
                                               slab_layout(slab_count(rows, cols, shift), rows, nnz).rp_j) + rows;
 }
 
-// First half of the preprocessing: entries per virtual row with the check of the column
-// order, and the pieces per row prefix-summed into rp_j.  Clears what it needs cleared.  The
+// no more workgroups than runs of kSlabRun entries
+static uint32_t slab_entry_grid(int nnz)
+{
+    const uint32_t most = (uint32_t)nnz / kSlabRun / (kWG / kWave) + 1u;
+    return most < kSlabGrid ? most : kSlabGrid;
+}
+
+// First half of the preprocessing: the row of every entry, entries per virtual row with the
+// check of the columns, and the pieces per row prefix-summed into rp_j.  Clears what it needs cleared.  The
 // caller then waits, reads the flag and rp_j[rows].
 void launch_slab_count(int rows, int cols, int nnz, int shift, const int *rp, const int *ci, void *plan_mem, hipStream_t st)
 {
@@ -339,9 +375,11 @@ void launch_slab_count(int rows, int cols, int nnz, int shift, const int *rp, co
     (void)hipMemsetAsync(cnt, 0, L.nv * 4, st);
     (void)hipMemsetAsync(base + L.flag, 0, sizeof(int), st);
     (void)hipMemsetAsync(rp_j + rows, 0, 4, st);
+    int *crow = reinterpret_cast<int *>(base + L.crow);
+    launch_coo_convert(rows, rp, crow, st);
+    hipLaunchKernelGGL(slab_count_kernel, dim3(slab_entry_grid(nnz)), dim3(kWG), 0, st, rows, cols, (uint32_t)nnz, shift, S,
+                       rp, ci, static_cast<const int *>(crow), cnt, reinterpret_cast<int *>(base + L.flag));
     const dim3 by_rows(((uint32_t)rows + kWG - 1) / kWG);
-    hipLaunchKernelGGL(slab_count_kernel, by_rows, dim3(kWG), 0, st, rows, shift, S, rp, ci, cnt,
-                       reinterpret_cast<int *>(base + L.flag));
     hipLaunchKernelGGL(slab_row_pieces_kernel, by_rows, dim3(kWG), 0, st, rows, S, static_cast<const uint32_t *>(cnt), rp_j);
     launch_scan_exclusive(rp_j, (size_t)rows + 1, reinterpret_cast<uint32_t *>(base + L.scan), st);
 }
@@ -365,9 +403,9 @@ void launch_slab_fill(int rows, int cols, int nnz, int shift, uint32_t n_kept, c
     hipLaunchKernelGGL(slab_compact_kernel, by_rows, dim3(kWG), 0, st, rows, S, static_cast<const uint32_t *>(rp_v),
                        static_cast<const uint32_t *>(num_v), reinterpret_cast<const uint32_t *>(base + L.rp_j), n_kept,
                        (uint32_t)nnz, reinterpret_cast<uint32_t *>(base + L.rp_z), reinterpret_cast<uint32_t *>(base + L.p_idx));
-    hipLaunchKernelGGL(slab_scatter_kernel, by_rows, dim3(kWG), 0, st, rows, shift, S, rp, ci, va,
-                       static_cast<const uint32_t *>(rp_v), reinterpret_cast<int *>(base + L.ci),
-                       reinterpret_cast<float *>(base + L.va));
+    hipLaunchKernelGGL(slab_scatter_kernel, dim3(slab_entry_grid(nnz)), dim3(kWG), 0, st, rows, (uint32_t)nnz, shift, S, rp,
+                       ci, va, reinterpret_cast<const int *>(base + L.crow), static_cast<const uint32_t *>(rp_v),
+                       reinterpret_cast<int *>(base + L.ci), reinterpret_cast<float *>(base + L.va));
 }
 
 // The product: CSR,WO over the kept virtual rows into their partials, its carry fix-up, the

@@ -26,6 +26,9 @@ def small_cases():
         G.explicit_lengths([9] * 6, 40, 6, "few-columns-with-repeats"),
         G.explicit_lengths([0] * 500 + [30_000] + [0] * 500, 70_000, 7, "giant-row-among-empties"),
         G.explicit_lengths([33, 32, 31, 64, 65, 1, 0, 2048, 4097], 5_000, 13, "around-the-long-row-limit"),
+        # rows beyond 4096 entries are copied segment by segment (1024 entries to a wave): whole and
+        # ragged last segments, giant rows side by side, one at the very end of the matrix
+        G.explicit_lengths([8192, 4097, 0, 5120, 7168, 3, 4096, 6000], 20_000, 31, "adjacent-giant-rows"),
         G.random_lengths(5_003, 3_000, 0, 40, 21),
         G.random_lengths(1_237, 9_000, 50, 700, 22),
         G.zipf_rows(20_011, s=1.6, cap=5_000, seed=23),
@@ -103,6 +106,17 @@ def test_where_the_slabbed_form_does_not_apply():
                 continue
             bad = G.HostCSR(B.rows, B.cols, B.row_ptr, ci, B.values, f"descending-{n}")
             assert O.slab_plan(bad.rows, bad.cols, bad.row_ptr, bad.col_idx, 8) is None
+            announce(f"CSR,S refuses {bad.name}")
+            with pytest.raises(S.SeerError) as ei:
+                S.seer_spmv_prepare(S.CSR_S, upload(bad))
+            assert ei.value.status == -1
+        # a column outside the matrix (the caller's contract, but the preprocessing writes by slab
+        # number): refused, in a short row and in a long one
+        for n in (5, 200):
+            B = G.random_lengths(300, 3_000, n, n, 9)
+            ci = B.col_idx.copy()
+            ci[int(B.row_ptr[41]) + n - 1] = B.cols
+            bad = G.HostCSR(B.rows, B.cols, B.row_ptr, ci, B.values, f"column-out-of-range-{n}")
             announce(f"CSR,S refuses {bad.name}")
             with pytest.raises(S.SeerError) as ei:
                 S.seer_spmv_prepare(S.CSR_S, upload(bad))
