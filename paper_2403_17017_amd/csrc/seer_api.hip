@@ -92,13 +92,27 @@ int pow2_at_least(double v, int lo, int hi)
 // Lanes per row for CSR,WM: the power of two at or above mean row length / 8, so that
 // a lane walks about eight entries (two rounds of its four-way unrolled loop).
 // Measured on banded and random matrices with mean lengths 5..200: wider groups
-// lose up to 3x on banded rows, narrower ones at most ~15 % on random ones.
+// lose up to 3x on banded rows, narrower ones at most ~15 % on random ones.  Small
+// matrices get wider groups (below).
 int wm_lanes(int rows, int nnz)
 {
     const int t = g_tune_wm_lanes.load();
     if (t == 2 || t == 4 || t == 8 || t == 16 || t == 32 || t == 64) return t;
     const double mean = rows > 0 ? (double)nnz / (double)rows : 0.0;
-    return pow2_at_least(mean / 8.0, 2, 64);
+    int g = pow2_at_least(mean / 8.0, 4, 64);   // (never two: four are 2 to 14 % faster on rows of 5 to 17, bands and random columns alike)
+    // A matrix of up to half a million nonzeros is all latency: with every row's lanes
+    // resident at once (the chip holds 2^19) a lane per entry, as far as the rows allow,
+    // shortens each row's chain of dependent loads (4096 rows of 16: 4.2 -> 2.4 us, 16 000
+    // rows of 16: 4.8 -> 3.5 us, 1000 rows of 100: 3.5 -> 2.6 us).  Larger matrices are
+    // bound by the rate of the gathers and keep the narrow groups.
+    if (rows > 0 && nnz <= (1 << 19)) {
+        const int by_length = pow2_at_least(mean, 4, 64);
+        int by_rows = 64;
+        while (by_rows > 2 && (int64_t)rows * by_rows > ((int64_t)1 << 19)) by_rows /= 2;
+        const int wide = by_length < by_rows ? by_length : by_rows;
+        if (wide > g) g = wide;
+    }
+    return g;
 }
 
 // Rows per workgroup for CSR,BM, from measurements over banded / random matrices:
