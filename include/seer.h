@@ -76,10 +76,10 @@ enum {
                         row index per nonzero; columns and values are the CSR arrays.   */
     SEER_CSR_S = 8,  /* column slabbed (this build's addition to the pool, not in Table II): a
                         preprocessing pass stores the matrix a second time, every row cut into
-                        one virtual row per slab of 2^19 columns and the entries laid out slab
+                        one virtual row per slab of 2^w columns (w below) and the entries laid out slab
                         after slab; the product is CSR,WO over the virtual rows that hold
                         entries followed by a sum over each row's pieces, so that the gathers
-                        of a long stretch of work stay inside 2 MiB of x.  For large matrices with scattered
+                        of a long stretch of work stay inside one slab of x.  For large matrices with scattered
                         columns, whose x no longer fits one XCD's L2.  No one-call form.       */
     SEER_NUM_KERNELS = 9
 };
@@ -304,10 +304,13 @@ size_t seer_plan_bytes(int kernel_id, int32_t rows, int32_t nnz);
 size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len);
 
 /* Device bytes of the column-slabbed form of a rows x cols matrix with nnz nonzeros: offsets
- * and piece lists for up to min(nnz, S * rows) kept virtual rows, S = ceil(cols / 2^19), a
+ * and piece lists for up to min(nnz, S * rows) kept virtual rows, S = ceil(cols / 2^w), a
  * second copy of col_idx and of values, and the preprocessing's own scratch (8 bytes per
  * virtual row).  0 if the form does not apply by size alone:
- * S < 2 (x is one slab) or S * rows >= 2^31. */
+ * S < 2 (x is one slab) or S * rows >= 2^31.
+ * The slab width: w = 19 (2 MiB of x); w = 20 if that gives at least four slabs and fewer
+ * than three entries are to be expected per piece of a row (nnz / rows < 3 * ceil(cols / 2^19));
+ * the "slab_shift" tuning knob overrides both.  The plan keeps its w in ell_width. */
 size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz);
 
 /* Runs the preprocessing of `kernel_id` for A on `stream` and fills *plan.  For
@@ -327,8 +330,8 @@ size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz);
  * plan_mem cannot even hold the reduction's workspace, the size of the ELL form after that,
  * so sizing may take two rounds.  SEER_EINVAL if the format is not applicable.
  * For SEER_COO_WM: writes the row index of every nonzero, in CSR order (int32 [nnz]).
- * For SEER_CSR_S: with S = ceil(cols / 2^19) slabs, virtual row s * rows + i is the entries of
- * row i with column >> 19 == s, in their CSR order; only the virtual rows that hold entries
+ * For SEER_CSR_S: with S = ceil(cols / 2^w) slabs, virtual row s * rows + i is the entries of
+ * row i with column >> w == s, in their CSR order; only the virtual rows that hold entries
  * are kept, numbered in the order of s * rows + i.  With K of them and M = min(nnz, S * rows),
  * plan_mem receives, each array padded to 256 bytes: rp_z (uint32 [M + 1], used [K + 1]: the
  * entries before kept row j; rp_z[K] = nnz), p_idx (uint32 [M + 1], used [K]: the kept rows that
@@ -408,8 +411,8 @@ int seer_csr_check(const seer_csr *A, int64_t *bad_row_ptr, int64_t *bad_col_idx
  *               launch of its own (both 0: always)
  *   "auto_prune" 0: seer_spmv_auto does not prune the tree with the known features (every
  *               schedule counts as reachable, the features are always gathered); default 1
- *   "slab_shift" CSR,S: log2 of the columns per slab, 1..30 (default 19: 2 MiB of x); the
- *               size functions follow it
+ *   "slab_shift" CSR,S: log2 of the columns per slab, 1..30 (default: 19 or 20, see
+ *               seer_slab_plan_bytes); the size functions follow it
  *   "coo_runs"  COO,WM: 1 (default): a lane sums a run of eight consecutive triples,
  *               0: lane <-> triple in rounds of 64
  *   "poll"      0: seer_features waits with hipStreamSynchronize only; otherwise

@@ -392,6 +392,17 @@ def coo_spmv_python(rows, coo_row, col_idx, values, x):
 SLAB_SHIFT = 19      # a slab of x holds 2^19 columns = 2 MiB, half of one XCD's L2
 
 
+def slab_shift_for(rows: int, cols: int, nnz: int) -> int:
+    """Which slab width the column-slabbed schedule takes for a matrix of this shape (a
+    choice of this build, like the format itself): 2^19 columns, but 2^20 where that width would
+    give at least four slabs and the rows are so short that a row's piece inside one slab would
+    hold fewer than three entries on average (mean row length < 3 * number of slabs)."""
+    slabs = -(-cols // (1 << SLAB_SHIFT))
+    if rows > 0 and slabs >= 4 and nnz < 3 * slabs * rows:
+        return SLAB_SHIFT + 1
+    return SLAB_SHIFT
+
+
 def slab_plan(rows: int, cols: int, row_ptr, col_idx, shift: int = SLAB_SHIFT):
     """The preprocessing result of the column-slabbed schedule (Sec. IV: a kernel may have a
     preprocessing step whose cost is amortised over the products; the format itself is this

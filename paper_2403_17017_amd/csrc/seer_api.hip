@@ -146,10 +146,20 @@ bool coo_runs()
     return g_tune_coo_runs.load() != 0;
 }
 
-int slab_shift()
+// Columns per slab of CSR,S, as a shift.  2^19 (2 MiB of x) keeps a slab inside an XCD's L2
+// beside the streams; but where rows are short and the matrix is many slabs wide a row falls
+// apart into pieces of one or two entries and the handling of the pieces costs more than the
+// gathers save: with fewer than three entries per piece to expect (mean row length over the
+// number of slabs) the slabs are 2^20 columns.  Measured on matrices of 2 M to 9 M rows: 0 to
+// 20 % faster products below that mark (8 M rows of 23: 1917 -> 1600 us), 11 to 17 % slower
+// above five entries per piece; 2^21 columns lose everywhere (x no longer stays in L2).
+int slab_shift(int rows, int cols, int nnz)
 {
     const int t = g_tune_slab_shift.load();
-    return t >= 1 && t <= 30 ? t : kSlabShift;
+    if (t >= 1 && t <= 30) return t;
+    const int64_t slabs = ((int64_t)cols + ((int64_t)1 << kSlabShift) - 1) >> kSlabShift;
+    if (rows > 0 && slabs >= 4 && (int64_t)nnz < 3 * slabs * (int64_t)rows) return kSlabShift + 1;
+    return kSlabShift;
 }
 
 int bm_chunk()
@@ -916,7 +926,7 @@ size_t seer_ell_plan_bytes(int32_t rows, int32_t max_len) { return ell_plan_byte
 size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz)
 {
     if (rows < 0 || cols < 0 || nnz < 0) return 0;
-    return slab_plan_bytes(rows, cols, nnz, slab_shift());
+    return slab_plan_bytes(rows, cols, nnz, slab_shift(rows, cols, nnz));
 }
 
 // The column-slabbed form: counts, the check of the column order and the number of virtual
@@ -924,7 +934,7 @@ size_t seer_slab_plan_bytes(int32_t rows, int32_t cols, int32_t nnz)
 // pieces and the entries.
 static int prepare_slab(const seer_csr *A, void *plan_mem, size_t plan_bytes, void *stream, seer_plan *plan)
 {
-    const int shift = slab_shift();
+    const int shift = slab_shift(A->rows, A->cols, A->nnz);
     const uint32_t S = slab_count(A->rows, A->cols, shift);
     if (S == 0) return SEER_EINVAL;                        // one slab, or too many virtual rows
     const size_t need = slab_plan_bytes(A->rows, A->cols, A->nnz, shift);

@@ -82,6 +82,24 @@ def test_default_slab_size_on_a_matrix_with_several_slabs():
     assert check_plan_and_product(A, O.SLAB_SHIFT)
 
 
+def test_wide_matrix_of_short_rows_takes_the_wider_slabs():
+    """2.2 M columns are five slabs of 2^19; rows of 0 to 8 entries would fall into pieces of
+    about one entry, so the library takes slabs of 2^20 columns (three of them), as the oracle's
+    rule says, and the plan is the oracle's plan for that width."""
+    A = G.random_lengths(2_200_003, 2_200_003, 0, 8, 78)
+    sh = O.slab_shift_for(A.rows, A.cols, A.nnz)
+    assert sh == O.SLAB_SHIFT + 1
+    announce(f"CSR,S rule-chosen shift {sh} {A.name} rows={A.rows} cols={A.cols} nnz={A.nnz}")
+    plan = S.seer_spmv_prepare(S.CSR_S, upload(A))
+    assert int(plan.c.ell_width) == sh and plan.n_blocks == 3
+    assert S.slab_plan_bytes(A.rows, A.cols, A.nnz) == int(plan.c.device_bytes)
+    assert check_plan_and_product(A, sh)
+    B = G.random_lengths(300_007, 2_200_003, 10, 30, 79)     # five slabs, 20 per row: stays at 2^19
+    assert O.slab_shift_for(B.rows, B.cols, B.nnz) == O.SLAB_SHIFT
+    plan = S.seer_spmv_prepare(S.CSR_S, upload(B))
+    assert int(plan.c.ell_width) == O.SLAB_SHIFT and plan.n_blocks == 5
+
+
 def test_where_the_slabbed_form_does_not_apply():
     import torch
     # one slab at the default size

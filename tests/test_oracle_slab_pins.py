@@ -94,3 +94,17 @@ def test_default_slab_is_two_mebibytes_of_x():
     p = O.slab_plan(A.rows, A.cols, A.row_ptr, A.col_idx)
     assert p["n_slabs"] == 3 and p["rp_v"].tolist() == [0, 1, 1, 1, 1, 2, 2, 2, 2, 3] and p["perm"].tolist() == [0, 1, 2]
     assert p["rp_z"].tolist() == [0, 1, 2, 3] and p["rp_j"].tolist() == [0, 1, 2, 3] and p["p_idx"].tolist() == [0, 1, 2]
+
+
+def test_slab_width_rule():
+    """2^19 columns per slab, 2^20 where at least four slabs would hold fewer than three entries
+    per piece of a row: hand cases on both sides of each condition, and the BASELINE shapes."""
+    four = 4 << 19
+    assert O.slab_shift_for(10, four, 119) == 20          # 119 < 3 * 4 * 10
+    assert O.slab_shift_for(10, four, 120) == 19
+    assert O.slab_shift_for(10, four - (1 << 19), 1) == 19   # three slabs: never
+    assert O.slab_shift_for(10, four + 1, 149) == 20      # five slabs: 149 < 150
+    assert O.slab_shift_for(0, four, 0) == 19
+    assert O.slab_shift_for(2_000_000, 2_000_000, 46_532_889) == 19      # config 3: four slabs, 23 per row
+    assert O.slab_shift_for(8_000_000, 1_000_000, 22_818_339) == 19      # config 4: two slabs
+    assert O.slab_shift_for(7_994_277, 7_994_277, 187_889_578) == 20     # 16 slabs, 23.5 per row
