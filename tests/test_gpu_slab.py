@@ -82,6 +82,37 @@ def test_default_slab_size_on_a_matrix_with_several_slabs():
     assert check_plan_and_product(A, O.SLAB_SHIFT)
 
 
+def test_random_matrices_and_slab_widths():
+    """Eighty drawn matrices (short rows, mostly empty with rows of thousands, Zipf lengths, one
+    giant row among near-empty ones) under drawn slab widths of 4 to 8192 columns: every plan
+    entry for entry, every product against the oracle."""
+    rng = np.random.default_rng(20261128)
+    ran = 0
+    try:
+        for it in range(80):
+            rows, cols = int(rng.integers(1, 6000)), int(rng.integers(2, 60000))
+            kind = int(rng.integers(0, 4))
+            if kind == 0:
+                lens = rng.integers(0, min(cols, 40) + 1, rows)
+            elif kind == 1:
+                lens = np.where(rng.random(rows) < 0.7, 0, rng.integers(0, min(cols, 9000) + 1, rows))
+            elif kind == 2:
+                lens = np.minimum(rng.zipf(1.4, rows), min(cols, 20000))
+            else:
+                lens = rng.integers(0, 3, rows)
+                lens[rng.integers(0, rows)] = min(cols, int(rng.integers(1000, 30000)))
+            if lens.sum() > 2_000_000:
+                lens = lens // 4
+            A = G.explicit_lengths([int(v) for v in lens], cols, int(rng.integers(1 << 30)), f"drawn-{it}")
+            sh = int(rng.integers(2, 14))
+            S.set_tuning("slab_shift", sh)
+            announce(f"CSR,S drawn case {it} kind={kind} shift={sh} rows={A.rows} cols={A.cols} nnz={A.nnz}")
+            ran += check_plan_and_product(A, sh)
+    finally:
+        S.set_tuning("slab_shift", -1)
+    assert ran >= 60
+
+
 def test_wide_matrix_of_short_rows_takes_the_wider_slabs():
     """2.2 M columns are five slabs of 2^19; rows of 0 to 8 entries would fall into pieces of
     about one entry, so the library takes slabs of 2^20 columns (three of them), as the oracle's
