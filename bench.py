@@ -410,6 +410,8 @@ def main():
     ap.add_argument("--roofline-kernel", type=int, default=-1,
                     help="price this kernel id in `roofline` instead of the one the step selects (a kernel with "
                          "preprocessing is timed from prepared plans); for profiling a particular schedule")
+    ap.add_argument("--size-scan", action="store_true",
+                    help="extras.tm_size_scan: CSR,TM on 5-point Laplacians from 54 MB to 872 MB (adds about 10 s)")
     ap.add_argument("--no-configs", dest="configs", action="store_false",
                     help="skip the table of every BASELINE config in extras")
     ap.add_argument("--selector-matrices", type=int, default=60,
@@ -620,6 +622,20 @@ def main():
                     continue
                 torch.cuda.empty_cache()
                 extras["configs"].append(config_row(name, what, tree))
+        if args.size_scan:
+            # CSR,TM on 5-point Laplacians of growing size, same cold protocol: where a matrix
+            # stops being one generation of workgroups and the kernel reaches its streaming rate
+            from workloads import csr_gen as G
+            extras["tm_size_scan"] = []
+            for n in (1024, 1200, 1350, 1500, 1800, 2048, 2500, 3000, 3500, 4096):
+                torch.cuda.empty_cache()
+                L = G.laplacian_5pt(n)
+                lb = model_bytes(L.rows, L.cols, L.nnz)
+                lrot = Rotation(L, dense_vector(L.cols, 1), max(1, math.ceil(COLD_BYTES / lb)) + 1)
+                t = time_spmv_graph(S.CSR_TM, lrot, 200 if lb < 100e6 else (60 if lb < 400e6 else 20))
+                extras["tm_size_scan"].append({"grid": n, "model_bytes": lb, "cold_us": round(t, 2),
+                                               "frac_of_hbm_peak": round(lb / (t * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)})
+                del lrot, L
         out["extras"] = extras
 
     if not args.no_cpu_baseline:
