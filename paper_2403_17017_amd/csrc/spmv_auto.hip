@@ -123,11 +123,6 @@ __device__ __forceinline__ HeapRegs heap_load(const AutoHeap &h)
     return HeapRegs{h.feature[l], h.threshold[l], (int)h.klass[l], (int)h.klass[kHeapInternal + l]};
 }
 
-struct FeatTotals {   // the four reduced statistics of the whole matrix
-    int32_t mx, mn;
-    uint64_t sq, em;
-};
-
 // Entry `l` of the feature vector (l < SEER_NUM_FEATURES; other lanes get 1).  The same
 // operations as derive_features_device, arranged so that every lane of a wave runs the same
 // instructions on its own operands: f[l] = fl32((a / b) / c) with b, c = 1 where the entry
@@ -198,39 +193,6 @@ __device__ __forceinline__ int select_in_wave(
         }
     }
     return k;
-}
-
-// The partials of a first pass folded by one wave (lane l takes partials l, l + 64, ..., all
-// requested before the first is used; then a butterfly): no LDS, no barrier.  Every lane ends
-// up with the totals.
-__device__ __forceinline__ FeatTotals fold_partials_wave(const FeatPartial *__restrict__ part, uint32_t n_part)
-{
-    const uint32_t l = threadIdx.x % kWave;
-    FeatTotals t{INT32_MIN, INT32_MAX, 0, 0};
-    for (uint32_t b = l; b < n_part; b += kWave * 4u) {
-        FeatPartial p[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t i = b + (uint32_t)j * kWave;
-            p[j] = part[i < n_part ? i : b];          // (a repeat of partial b changes no statistic but the sums)
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool in = b + (uint32_t)j * kWave < n_part;
-            t.mx = max(t.mx, p[j].max_len);
-            t.mn = min(t.mn, p[j].min_len);
-            t.sq += in ? p[j].sum_sq : 0u;
-            t.em += in ? p[j].empty : 0u;
-        }
-    }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        t.mx = max(t.mx, __shfl_xor(t.mx, off));
-        t.mn = min(t.mn, __shfl_xor(t.mn, off));
-        t.sq += (uint64_t)__shfl_xor((unsigned long long)t.sq, off);
-        t.em += (uint64_t)__shfl_xor((unsigned long long)t.em, off);
-    }
-    return t;
 }
 
 // Finishing launch of the selection after a first pass: ONE wave folds the partials, derives
