@@ -524,7 +524,7 @@ def main():
                      "meets_60pct_of_hbm_peak": bool(achieved >= 0.6 * HBM_PEAK_GBPS),
                      "profiles": {k: v for k, v in prof.items() if k != "traffic"},
                      "how": f"{args.steps} launches of the selected kernel on the rotating cold copies, "
-                            "one HIP graph replay bracketed by HIP events",
+                            "replayed from one HIP graph: mean of five replays, each bracketed by HIP events",
                      "algorithmic_bytes_per_launch": mb},
     }
 
